@@ -1,0 +1,109 @@
+"""Independent helpers for the tests: second implementations and brute force written
+directly from definitions (numpy / pure Python), a golden-file reader, and the
+time-row assembly shared by the oracle pins and the GPU parity tests.  None of this
+is used by the library or by the oracle."""
+
+from __future__ import annotations
+
+import itertools
+import os
+from typing import Dict, List
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def read_golden(name: str) -> Dict[str, np.ndarray]:
+    out: Dict[str, np.ndarray] = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split("=", 1)
+            out[k.strip()] = np.array([float(x) for x in v.split()], dtype=np.float64)
+    return out
+
+
+def bits_of_row(row: np.ndarray) -> List[int]:
+    out = []
+    for w, word in enumerate(row):
+        word = int(word)
+        for b in range(64):
+            if (word >> b) & 1:
+                out.append(w * 64 + b)
+    return out
+
+
+def dep_bool(dep: np.ndarray, R: int) -> np.ndarray:
+    """[n][R] boolean matrix of a bitset matrix."""
+    n, W = dep.shape
+    if W == 0:
+        return np.zeros((n, 0), dtype=bool)
+    b = np.unpackbits(dep.view(np.uint8).reshape(n, W * 8), axis=1, bitorder="little")
+    return b[:, :R].astype(bool)
+
+
+def recv_ancestors_bfs(dag) -> np.ndarray:
+    """[n][R] reachability by a breadth-first search from every op over predecessor
+    edges (brute force, only for small graphs)."""
+    n, R = dag.n_ops, dag.n_recv
+    ri = {int(v): i for i, v in enumerate(dag.recv_ids)}
+    out = np.zeros((n, R), dtype=bool)
+    for v in range(n):
+        seen = {v}
+        frontier = [v]
+        while frontier:
+            nxt = []
+            for x in frontier:
+                if x in ri:
+                    out[v, ri[x]] = True
+                for p in dag.col_idx[dag.row_ptr[x]:dag.row_ptr[x + 1]]:
+                    p = int(p)
+                    if p not in seen:
+                        seen.add(p)
+                        nxt.append(p)
+            frontier = nxt
+    return out
+
+
+def full_time_row(dag, op_row: np.ndarray, recv_row: np.ndarray) -> np.ndarray:
+    """Time(op) by op id from one row of op_time and recv_time."""
+    t = np.zeros(dag.n_ops)
+    t[dag.compute_ids()] = op_row
+    t[dag.recv_ids] = recv_row
+    return t
+
+
+def closed_form_makespan(depb: np.ndarray, dag, order: np.ndarray, op_time: np.ndarray,
+                         recv_time: np.ndarray) -> np.ndarray:
+    """Makespan of every sample from the recv-ancestor matrix alone.
+
+    With one channel that never waits (recvs are roots) transfer k (1-based) ends at
+    F_k = sum of the first k transfer times.  A compute op can start no earlier than
+    F_kappa, kappa = the last position among the recvs it depends on (0 if none).  A
+    work-conserving single device then finishes at  max_k (F_k + S_k),  S_k = total time
+    of the compute ops with kappa >= k, and the iteration ends at the later of that and
+    F_R.  `order` is [R] or [B][R]."""
+    B = recv_time.shape[0]
+    R = dag.n_recv
+    comp = dag.compute_ids()
+    dc = depb[comp]                                   # [N][R]
+    order = np.asarray(order)
+    per_sample = order.ndim == 2
+    out = np.zeros(B)
+    for b in range(B):
+        o = order[b] if per_sample else order
+        pos = np.zeros(R, dtype=np.int64)
+        pos[o] = np.arange(1, R + 1)
+        kappa = (dc * pos[None, :]).max(axis=1) if R else np.zeros(len(comp), dtype=np.int64)
+        F = np.concatenate([[0.0], np.cumsum(recv_time[b][o])])
+        A = np.bincount(kappa, weights=op_time[b], minlength=R + 1)
+        S = np.cumsum(A[::-1])[::-1]
+        out[b] = max((F + S).max(), F[-1])
+    return out
+
+
+def all_orders(R: int) -> np.ndarray:
+    return np.array(list(itertools.permutations(range(R))), dtype=np.int32).reshape(-1, R)

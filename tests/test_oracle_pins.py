@@ -1,0 +1,390 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix: the worked
+examples of the paper (tests/golden), closed forms, invariants, special cases that
+reduce to textbook results (Johnson's rule for the two-machine flow shop) and brute
+force on tiny inputs.  No GPU is involved."""
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1803_03288_amd import workloads as wl
+
+from helpers import (all_orders, bits_of_row, closed_form_makespan, dep_bool, full_time_row,
+                     read_golden, recv_ancestors_bfs)
+
+
+def deps(d):
+    return oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+
+
+def sim(d, order, op, rv, key=None):
+    return oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, order, op, rv, key)
+
+
+def rand_times(rng, B, n, lo=1, hi=2000):
+    """Random multiples of 2**-30 s (exact sums)."""
+    return rng.integers(lo, hi, size=(B, n)).astype(np.float64) * wl.QUANTUM * 1024
+
+
+# --------------------------------------------------------------------------
+# worked examples printed in the paper
+# --------------------------------------------------------------------------
+
+def test_fig1_toy_graph_values():
+    g = read_golden("fig1_toy.txt")
+    d = wl.toy_dag()
+    dep = deps(d)
+    op1, op2 = d.compute_ids()
+    assert bits_of_row(dep[op1]) == list(g["dep_op1"].astype(int))
+    assert bits_of_row(dep[op2]) == list(g["dep_op2"].astype(int))
+    rv, op = g["recv_time"][None, :], g["op_time"][None, :]
+    t = full_time_row(d, op[0], rv[0])
+    M, P, Mplus = oracle.update_properties(dep, d.recv_ids, t, np.ones(2, dtype=np.uint8))
+    assert M[op1] == g["M_op1"][0] and M[op2] == g["M_op2"][0]
+    assert M[d.recv_ids[0]] == rv[0, 0] and M[d.recv_ids[1]] == rv[0, 1]    # recv.M = Time(recv)
+    np.testing.assert_array_equal(P, g["P"])
+    np.testing.assert_array_equal(Mplus, g["Mplus"])
+    order, rank, sel_P, sel_Mplus = oracle.tac(dep, d.recv_ids, op, rv)
+    np.testing.assert_array_equal(order[0], g["tac_order"].astype(int))
+    np.testing.assert_array_equal(rank[0], [0, 1])
+    m01, e01, U, L, S = sim(d, np.array([0, 1]), op, rv)
+    m10, e10, _, _, _ = sim(d, np.array([1, 0]), op, rv)
+    assert m01[0] == g["makespan_order_0_1"][0] and m10[0] == g["makespan_order_1_0"][0]
+    assert U[0] == g["U"][0] and L[0] == g["L"][0] and S[0] == g["S"][0]
+    assert e01[0] == pytest.approx(g["E_order_0_1"][0], rel=1e-15)
+    assert e10[0] == g["E_order_1_0"][0]
+
+
+def test_printed_comparator_listing_contradicts_toy_example():
+    """The comparator as its listing prints it sends recv2 first on the toy graph,
+    against Sec. 2.2; the derived pairwise rule (the oracle's reading) does not."""
+    g = read_golden("fig1_toy.txt")
+    d = wl.toy_dag()
+    dep = deps(d)
+    rv, op = g["recv_time"][None, :], g["op_time"][None, :]
+    good = oracle.tac(dep, d.recv_ids, op, rv, comparator_mode=0)[0][0]
+    printed = oracle.tac(dep, d.recv_ids, op, rv, comparator_mode=1)[0][0]
+    assert list(good) == [0, 1] and list(printed) == [1, 0]
+
+
+def test_case2_graph_values():
+    g = read_golden("case2.txt")
+    d = wl.case2_dag()
+    dep = deps(d)
+    rv, op = g["recv_time"][None, :], g["op_time"][None, :]
+    t = full_time_row(d, op[0], rv[0])
+    M, P, Mplus = oracle.update_properties(dep, d.recv_ids, t, np.ones(4, dtype=np.uint8))
+    np.testing.assert_array_equal(P, g["P_round0"])
+    np.testing.assert_array_equal(Mplus, g["Mplus_round0"])
+    assert Mplus[0] == Mplus[1] == rv[0, 0] + rv[0, 1] < Mplus[2] < Mplus[3]
+    prio, tic_order, _ = oracle.tic(dep, d.recv_ids)
+    np.testing.assert_array_equal(prio, g["tic_prio"].astype(int))
+    np.testing.assert_array_equal(tic_order, [0, 1, 2, 3])
+    order, rank, sel_P, sel_Mplus = oracle.tac(dep, d.recv_ids, op, rv)
+    np.testing.assert_array_equal(order[0], g["tac_order"].astype(int))
+    np.testing.assert_array_equal(sel_P[0], g["sel_P"])
+    np.testing.assert_array_equal(sel_Mplus[0], g["sel_Mplus"])
+    m, e, U, L, S = sim(d, order[0], op, rv)
+    assert m[0] == g["makespan"][0] and U[0] == g["U"][0] and L[0] == g["L"][0]
+    assert e[0] == pytest.approx(g["E"][0], rel=1e-15)
+
+
+def test_case1_two_job_makespan_formula_and_pairwise_rule():
+    """Sec. 4.3 Case 1: Makespan(A->B) = M_A + max{P_A, M_B} + P_B, and A goes first
+    iff min{P_B, M_A} < min{P_A, M_B}."""
+    d = wl.independent_jobs_dag(2)
+    dep = deps(d)
+    rng = np.random.default_rng(11)
+    B = 400
+    rv, op = rand_times(rng, B, 2, 1, 50), rand_times(rng, B, 2, 1, 50)
+    MA, MB, PA, PB = rv[:, 0], rv[:, 1], op[:, 0], op[:, 1]
+    mab = sim(d, np.array([0, 1]), op, rv)[0]
+    mba = sim(d, np.array([1, 0]), op, rv)[0]
+    np.testing.assert_array_equal(mab, MA + np.maximum(PA, MB) + PB)
+    np.testing.assert_array_equal(mba, MB + np.maximum(PB, MA) + PA)
+    order = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    a_first = np.minimum(PB, MA) < np.minimum(PA, MB)
+    b_first = np.minimum(PA, MB) < np.minimum(PB, MA)
+    assert a_first.sum() > 50 and b_first.sum() > 50
+    assert (order[a_first, 0] == 0).all() and (order[b_first, 0] == 1).all()
+    # the rule is the makespan comparison
+    assert ((mab < mba) == a_first).all()
+    # TAC never picks the strictly worse order; the printed listing does
+    chosen = np.where(order[:, 0] == 0, mab, mba)
+    assert (chosen == np.minimum(mab, mba)).all()
+    printed = oracle.tac(dep, d.recv_ids, op, rv, comparator_mode=1)[0]
+    worse = np.where(printed[:, 0] == 0, mab, mba)
+    assert (worse > np.minimum(mab, mba)).any()
+
+
+# --------------------------------------------------------------------------
+# dependency sets
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_dependencies_equal_bfs_reachability(seed):
+    d = wl.layered_dag(seed, levels=6, width=5, fan_in=(1, 3), back=2, n_recv=70, attach=(1, 3))
+    dep = deps(d)
+    assert dep.shape == (d.n_ops, 2)
+    np.testing.assert_array_equal(dep_bool(dep, d.n_recv), recv_ancestors_bfs(d))
+    # padding bits beyond R stay clear
+    assert (dep[:, 1] >> np.uint64(70 - 64)).max() == 0
+
+
+def test_dependencies_monotone_along_edges_and_relabel():
+    d = wl.layered_dag(5, levels=7, width=6, fan_in=(1, 3), back=3, n_recv=20, attach=(1, 4))
+    dep = deps(d)
+    for v in range(d.n_ops):
+        for u in d.col_idx[d.row_ptr[v]:d.row_ptr[v + 1]]:
+            assert ((dep[u] & ~dep[v]) == 0).all()
+    d2, new_id = wl.relabel(d, 3)
+    dep2 = deps(d2)
+    np.testing.assert_array_equal(dep2[new_id], dep)
+
+
+def test_cycle_is_reported():
+    row_ptr = np.array([0, 0, 2, 3], dtype=np.int32)      # op1 <- {recv0, op2}; op2 <- {op1}
+    col_idx = np.array([0, 2, 1], dtype=np.int32)
+    with pytest.raises(RuntimeError):
+        oracle.find_dependencies(3, row_ptr, col_idx, np.array([0], dtype=np.int32))
+
+
+def test_chain_dependencies_and_priorities():
+    """Layer-by-layer model: the priority order must equal the consumption order."""
+    R = 9
+    d = wl.chain_dag(R)
+    dep = deps(d)
+    comp = d.compute_ids()
+    for k in range(R):
+        assert bits_of_row(dep[comp[k]]) == list(range(k + 1))
+    prio, order, rank = oracle.tic(dep, d.recv_ids)
+    np.testing.assert_array_equal(prio, [2, 2] + list(range(3, R + 1)))
+    np.testing.assert_array_equal(order, np.arange(R))
+    rng = np.random.default_rng(5)
+    rv, op = rand_times(rng, 64, R), rand_times(rng, 64, R)
+    tac_order = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    assert (tac_order == np.arange(R)[None, :]).all()
+
+
+# --------------------------------------------------------------------------
+# TIC
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 7])
+def test_tic_is_mplus_under_general_time_oracle(seed):
+    d = wl.layered_dag(seed, levels=6, width=6, fan_in=(1, 3), back=2, n_recv=30, attach=(1, 3))
+    dep = deps(d)
+    t = np.zeros(d.n_ops)
+    t[d.recv_ids] = 1.0
+    M, P, Mplus = oracle.update_properties(dep, d.recv_ids, t, np.ones(d.n_recv, dtype=np.uint8))
+    prio, order, rank = oracle.tic(dep, d.recv_ids)
+    assert (P == 0).all()
+    expect = np.where(np.isinf(Mplus), oracle.PRIO_INF, Mplus).astype(np.int64)
+    np.testing.assert_array_equal(prio, expect)
+    # definition by brute force: min size of a dependency set that holds the recv and another
+    db = recv_ancestors_bfs(d)
+    comp = d.compute_ids()
+    cnt = db[comp].sum(axis=1)
+    for i in range(d.n_recv):
+        c = cnt[db[comp, i] & (cnt > 1)]
+        assert prio[i] == (c.min() if c.size else oracle.PRIO_INF)
+    # order = stable sort, rank = inverse
+    np.testing.assert_array_equal(order, np.argsort(prio, kind="stable"))
+    np.testing.assert_array_equal(rank[order], np.arange(d.n_recv))
+
+
+def test_single_recv_has_no_finite_priority():
+    d = wl.chain_dag(1)
+    dep = deps(d)
+    prio, order, rank = oracle.tic(dep, d.recv_ids)
+    assert prio[0] == oracle.PRIO_INF and order[0] == 0 and rank[0] == 0
+
+
+# --------------------------------------------------------------------------
+# simulation: closed form, bounds, pick-rule invariance, degenerate graphs
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_simulation_equals_closed_form_and_is_pick_rule_invariant(seed):
+    d = wl.layered_dag(seed, levels=8, width=6, fan_in=(1, 3), back=3, n_recv=12, attach=(1, 3))
+    dep = deps(d)
+    depb = dep_bool(dep, d.n_recv)
+    rng = np.random.default_rng(seed)
+    B = 40
+    rv, op = rand_times(rng, B, d.n_recv), rand_times(rng, B, d.n_compute)
+    op[rng.random(op.shape) < 0.15] = 0.0           # zero-duration ops
+    rv[rng.random(rv.shape) < 0.10] = 0.0
+    orders = np.stack([rng.permutation(d.n_recv) for _ in range(B)]).astype(np.int32)
+    m, e, U, L, S = sim(d, orders, op, rv)
+    np.testing.assert_array_equal(m, closed_form_makespan(depb, d, orders, op, rv))
+    for key in (np.arange(d.n_ops)[::-1].copy(), rng.permutation(d.n_ops)):
+        m2 = sim(d, orders, op, rv, key)[0]
+        np.testing.assert_array_equal(m2, m)
+    np.testing.assert_array_equal(U, op.sum(axis=1) + rv.sum(axis=1))
+    np.testing.assert_array_equal(L, np.maximum(op.sum(axis=1), rv.sum(axis=1)))
+    assert (L <= m).all() and (m <= U).all()
+    assert (e >= 0).all() and (e <= 1).all()
+    ok = U > L
+    np.testing.assert_allclose(e[ok], ((U - m) / (U - L))[ok], rtol=1e-15)
+    np.testing.assert_allclose(S[ok], ((U - L) / L)[ok], rtol=1e-15)
+    # shared order = the same order for every sample
+    m3 = sim(d, orders[0], op, rv)[0]
+    np.testing.assert_array_equal(m3, closed_form_makespan(depb, d, orders[0], op, rv))
+
+
+def test_no_recvs():
+    d = wl.no_recv_dag(17)
+    dep = deps(d)
+    assert dep.shape == (17, 0)
+    rng = np.random.default_rng(0)
+    op = rand_times(rng, 5, 17)
+    rv = np.zeros((5, 0))
+    prio, order, rank = oracle.tic(dep, d.recv_ids)
+    assert order.size == 0
+    o = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    assert o.shape == (5, 0)
+    m, e, U, L, S = sim(d, np.zeros(0, dtype=np.int32), op, rv)
+    np.testing.assert_array_equal(m, op.sum(axis=1))
+    np.testing.assert_array_equal(U, m)
+    np.testing.assert_array_equal(L, m)
+    assert (e == 1).all() and (S == 0).all()
+
+
+def test_all_recvs_at_the_root_gives_zero_efficiency():
+    R = 5
+    d = wl.funnel_dag(R, 6)
+    dep = deps(d)
+    assert (dep_bool(dep, R)[d.compute_ids()]).all()
+    prio, order, _ = oracle.tic(dep, d.recv_ids)
+    assert (prio == R).all() and (order == np.arange(R)).all()
+    rng = np.random.default_rng(1)
+    perms = all_orders(R)
+    rv = np.repeat(rand_times(rng, 1, R), len(perms), axis=0)
+    op = np.repeat(rand_times(rng, 1, 6), len(perms), axis=0)
+    m, e, U, L, S = sim(d, perms, op, rv)
+    np.testing.assert_array_equal(m, U)
+    assert (e == 0).all()
+    tac_order = oracle.tac(dep, d.recv_ids, op[:1], rv[:1])[0][0]
+    np.testing.assert_array_equal(tac_order, np.arange(R))
+
+
+def test_unused_recvs_and_free_compute_give_full_overlap():
+    # 3 recvs without consumers, 4 chained compute ops without recv dependencies
+    row_ptr = np.array([0, 0, 0, 0, 0, 1, 2, 3], dtype=np.int32)
+    col_idx = np.array([3, 4, 5], dtype=np.int32)
+    recv_ids = np.array([0, 1, 2], dtype=np.int32)
+    rng = np.random.default_rng(2)
+    rv, op = rand_times(rng, 6, 3), rand_times(rng, 6, 4)
+    m, e, U, L, S = oracle.simulate(7, row_ptr, col_idx, recv_ids, np.array([2, 0, 1]), op, rv)
+    np.testing.assert_array_equal(m, L)
+    assert (e == 1).all()
+    dep = oracle.find_dependencies(7, row_ptr, col_idx, recv_ids)
+    prio, order, _ = oracle.tic(dep, recv_ids)
+    assert (prio == oracle.PRIO_INF).all() and list(order) == [0, 1, 2]
+    tac_order, _, sel_P, sel_Mplus = oracle.tac(dep, recv_ids, op, rv)
+    assert (tac_order == np.arange(3)).all() and (sel_P == 0).all() and np.isinf(sel_Mplus).all()
+
+
+# --------------------------------------------------------------------------
+# Johnson's rule and brute force over all transfer orders
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("R", [3, 5, 7])
+def test_independent_jobs_tac_is_johnson_optimal(R):
+    """recv i -> private op i is the two-machine flow shop (channel, then device), for
+    which ordering by the pairwise rule of Case 1 is makespan-optimal (Johnson 1954).
+    So TAC must reach the brute-force minimum over all R! orders."""
+    d = wl.independent_jobs_dag(R)
+    dep = deps(d)
+    perms = all_orders(R)
+    rng = np.random.default_rng(R)
+    n_printed_worse = 0
+    for trial in range(12):
+        rv1, op1 = rand_times(rng, 1, R, 1, 40), rand_times(rng, 1, R, 1, 40)
+        rv, op = np.repeat(rv1, len(perms), axis=0), np.repeat(op1, len(perms), axis=0)
+        m = sim(d, perms, op, rv)[0]
+        order = oracle.tac(dep, d.recv_ids, op1, rv1)[0][0]
+        assert sorted(order) == list(range(R))
+        m_tac = sim(d, order, op1, rv1)[0][0]
+        assert m_tac == m.min()
+        printed = oracle.tac(dep, d.recv_ids, op1, rv1, comparator_mode=1)[0][0]
+        n_printed_worse += sim(d, printed, op1, rv1)[0][0] > m.min()
+    assert n_printed_worse > 0
+
+
+@pytest.mark.parametrize("seed,R", [(0, 4), (1, 6), (2, 7), (3, 8)])
+def test_brute_force_no_order_beats_the_bounds(seed, R):
+    d = wl.layered_dag(seed, levels=5, width=4, fan_in=(1, 2), back=2, n_recv=R, attach=(1, 2))
+    dep = deps(d)
+    depb = dep_bool(dep, R)
+    perms = all_orders(R)
+    rng = np.random.default_rng(seed)
+    rv1, op1 = rand_times(rng, 1, R), rand_times(rng, 1, d.n_compute)
+    rv, op = np.repeat(rv1, len(perms), axis=0), np.repeat(op1, len(perms), axis=0)
+    m, e, U, L, S = sim(d, perms, op, rv)
+    assert (m >= L).all() and (m <= U).all() and (e >= 0).all() and (e <= 1).all()
+    np.testing.assert_array_equal(m, closed_form_makespan(depb, d, perms, op, rv))
+    best = m.min()
+    tac_order = oracle.tac(dep, d.recv_ids, op1, rv1)[0][0]
+    tic_order = oracle.tic(dep, d.recv_ids)[1]
+    assert sorted(tac_order) == list(range(R)) and sorted(tic_order) == list(range(R))
+    assert sim(d, tac_order, op1, rv1)[0][0] >= best
+    assert sim(d, tic_order, op1, rv1)[0][0] >= best
+    assert best >= L[0]
+
+
+# --------------------------------------------------------------------------
+# invariances
+# --------------------------------------------------------------------------
+
+def test_power_of_two_scaling_and_relabelling():
+    d = wl.layered_dag(9, levels=6, width=5, fan_in=(1, 3), back=2, n_recv=10, attach=(1, 3))
+    dep = deps(d)
+    rng = np.random.default_rng(4)
+    B = 16
+    rv, op = rand_times(rng, B, d.n_recv), rand_times(rng, B, d.n_compute)
+    o1, r1, p1, mp1 = oracle.tac(dep, d.recv_ids, op, rv)
+    o2, r2, p2, mp2 = oracle.tac(dep, d.recv_ids, op * 8, rv * 8)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(p1 * 8, p2)
+    np.testing.assert_array_equal(mp1 * 8, mp2)
+    m1, e1, U1, L1, S1 = sim(d, o1, op, rv)
+    m2, e2, U2, L2, S2 = sim(d, o1, op * 8, rv * 8)
+    np.testing.assert_array_equal(m1 * 8, m2)
+    np.testing.assert_array_equal(e1, e2)
+    np.testing.assert_array_equal(S1, S2)
+    # op ids permuted, recv indices kept: identical orders and makespans
+    d2, new_id = wl.relabel(d, 1)
+    cmap = wl.compute_column_map(d, d2, new_id)
+    dep2 = deps(d2)
+    o3 = oracle.tac(dep2, d2.recv_ids, op[:, cmap], rv)[0]
+    np.testing.assert_array_equal(o3, o1)
+    m3 = sim(d2, o3, op[:, cmap], rv)[0]
+    np.testing.assert_array_equal(m3, m1)
+    np.testing.assert_array_equal(oracle.tic(dep2, d2.recv_ids)[0], oracle.tic(dep, d.recv_ids)[0])
+
+
+def test_summation_order_does_not_matter_on_quantised_presets():
+    """Times of the presets are multiples of 2**-30 s, so every sum is exact: recv
+    indices can be visited in any order without changing a single bit of the result."""
+    d = wl.tiny_dag()
+    dep = deps(d)
+    op, rv = wl.timing_samples(d, 0, 8)
+    assert (op == np.rint(op / wl.QUANTUM) * wl.QUANTUM).all() and (op >= wl.QUANTUM).all()
+    t = full_time_row(d, op[0], rv[0])
+    alive = np.ones(d.n_recv, dtype=np.uint8)
+    M, P, Mplus = oracle.update_properties(dep, d.recv_ids, t, alive)
+    depb = dep_bool(dep, d.n_recv)
+    perm = np.random.default_rng(0).permutation(d.n_recv)
+    M_shuffled = np.array([sum(rv[0][i] for i in perm if depb[v, i]) for v in range(d.n_ops)])
+    np.testing.assert_array_equal(M, M_shuffled)
+
+
+def test_partial_rounds_prefix():
+    d = wl.tiny_dag()
+    dep = deps(d)
+    op, rv = wl.timing_samples(d, 0, 4)
+    full = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    part = oracle.tac(dep, d.recv_ids, op, rv, max_rounds=5)[0]
+    np.testing.assert_array_equal(part[:, :5], full[:, :5])
+    assert (part[:, 5:] == -1).all()
