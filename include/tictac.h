@@ -1,0 +1,165 @@
+/*
+ * tictac.h -- C ABI of libtictac: the scheduling math of "TicTac: Accelerating
+ * Distributed Deep Learning with Communication Scheduling" (arXiv 1803.03288)
+ * as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Given the worker's computational DAG, whose communication ops (recv) are its
+ * roots (Sec. 2.2), and a time oracle Time(op) (Sec. 3.1), the library computes
+ *   1. op.dep, the set of recvs every op depends on       (Sec. 4.1)
+ *   2. the timing-independent priorities, TIC              (Sec. 4.2, Algorithm 2)
+ *   3. the timing-aware order, TAC, for a batch of
+ *      timing samples                                      (Sec. 4.3, Algorithm 3)
+ *   4. makespan, its bounds, Scheduling Efficiency and
+ *      Speedup of an iteration under a transfer order,
+ *      for a batch of timing samples                       (Sec. 3.2, Eq. 1-4)
+ *
+ * Conventions
+ *   - "host" pointers are ordinary memory, "device" pointers are HIP device
+ *     memory of the current device.  The library never takes ownership of a
+ *     caller's buffer; it only uses it for the duration of the stream-ordered
+ *     call.  Everything a tictac_dag owns is released by tictac_dag_free.
+ *   - Ops are numbered 0..n_ops-1 in any order.  recv i is the op recv_ids[i];
+ *     bit i of a dependency bitset (bit i & 63 of 64-bit word i >> 6) stands
+ *     for it.  W = ceil(n_recv / 64) words per bitset.
+ *   - N = n_ops - n_recv compute ops.  Column j of an op_time row is the j-th
+ *     compute op in ascending op id; column i of a recv_time row is recv i.
+ *     Times are float64 seconds, finite and >= 0 (not checked on the device).
+ *   - Every function returns TICTAC_OK (0) or a negative tictac_status; on an
+ *     error nothing is written to the outputs and tictac_last_error() holds a
+ *     message.  No exception or abort crosses this boundary.
+ *   - Calls taking a stream are asynchronous on it unless stated otherwise.
+ *     Calls on the same tictac_dag must not overlap in time on different
+ *     streams (the handle owns one scratch workspace).
+ */
+#ifndef TICTAC_H
+#define TICTAC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tictac_status {
+    TICTAC_OK = 0,
+    TICTAC_ERR_NULL = -1,          /* a required pointer is NULL */
+    TICTAC_ERR_BAD_CSR = -2,       /* row_ptr not monotone from 0, or an id out of range, or negative size */
+    TICTAC_ERR_CYCLE = -3,         /* the graph is not acyclic */
+    TICTAC_ERR_RECV_NOT_ROOT = -4, /* a recv op has predecessors (Sec. 2.2: recvs are roots) */
+    TICTAC_ERR_DUP_RECV = -5,      /* recv_ids holds an op twice */
+    TICTAC_ERR_BAD_ORDER = -6,     /* order_stride is neither 0 nor n_recv */
+    TICTAC_ERR_HIP = -7,           /* a HIP runtime call failed */
+    TICTAC_ERR_NO_MEM = -8,        /* host or device allocation failed */
+    TICTAC_ERR_UNSUPPORTED = -9    /* size beyond what the kernels are built for */
+} tictac_status;
+
+/* TIC priority of a recv that no multi-dependency op consumes (M+ = +infinity). */
+#define TICTAC_PRIO_INF INT32_MAX
+
+typedef struct tictac_dag tictac_dag; /* opaque; owns device copies of the graph, op.dep and derived tables */
+typedef void *tictac_stream;          /* a hipStream_t; NULL = the default stream */
+
+/*
+ * Sec. 4.1, Communication Dependency.  Validates the graph, uploads it, and
+ * computes dep[v] = ({i} if v is recv i) U (union of dep[u] over predecessors u)
+ * for every op on the device.
+ *   pred_row_ptr [n_ops+1], pred_col_idx [E]  host: predecessors of op v are
+ *       pred_col_idx[pred_row_ptr[v] .. pred_row_ptr[v+1])
+ *   recv_ids [n_recv]                         host
+ *   *out receives a new handle (free with tictac_dag_free).
+ * Synchronises with the stream before returning (the handle is complete).
+ * n_recv = 0 and n_ops = 0 are valid.
+ */
+int tictac_build_deps(int32_t n_ops, const int32_t *pred_row_ptr, const int32_t *pred_col_idx,
+                      int32_t n_recv, const int32_t *recv_ids, tictac_stream stream, tictac_dag **out);
+
+/* Sizes of a handle; any output pointer may be NULL.  n_levels = length of the
+ * longest path, in ops.  n_classes = number of distinct dep sets among the compute
+ * ops (ops with the same set form the unit the TAC and simulation kernels work on). */
+int tictac_dag_info(const tictac_dag *dag, int32_t *n_ops, int32_t *n_recv, int32_t *words,
+                    int32_t *n_levels, int32_t *n_classes);
+
+/* Borrowed device pointer to op.dep: uint64 [n_ops][W], row-major, row = op id.
+ * Valid until tictac_dag_free.  NULL when n_ops * W == 0. */
+int tictac_dag_deps(const tictac_dag *dag, const uint64_t **dep_device);
+
+/* Copies op.dep ([n_ops][W], as above) into a caller-owned device buffer, asynchronously
+ * on the stream. */
+int tictac_dag_copy_deps(const tictac_dag *dag, uint64_t *dst_device, tictac_stream stream);
+
+/* Runs the propagation kernel again on the handle's graph, overwriting op.dep with the
+ * same values (for timing the kernel without the host-side part of tictac_build_deps).
+ * Asynchronous on the stream. */
+int tictac_dag_recompute_deps(tictac_dag *dag, tictac_stream stream);
+
+int tictac_dag_free(tictac_dag *dag);
+
+/*
+ * Sec. 4.2, Algorithm 2 (TIC): the property update of Algorithm 1 with every recv
+ * outstanding and the General Time Oracle (recv = 1, others = 0), in integers.
+ *   prio  [n_recv] device: M+ of each recv = the smallest |op.dep| over compute ops
+ *         whose dep holds the recv and at least one more; TICTAC_PRIO_INF if none
+ *   order [n_recv] device: recv indices sorted by (prio, index)   (may be NULL)
+ *   rank  [n_recv] device: inverse of order = the number of transfers that go
+ *         before recv i, the normalised priority of Sec. 5.1      (may be NULL)
+ */
+int tictac_tic_priority(const tictac_dag *dag, int32_t *prio, int32_t *order, int32_t *rank,
+                        tictac_stream stream);
+
+/*
+ * Sec. 4.3, Algorithm 3 (TAC) for B timing samples.  Per sample: all recvs start
+ * outstanding; n_recv times, the properties M, P, M+ of Algorithm 1 are taken for
+ * the outstanding set, the recv that is minimal under the comparator is selected
+ * (ascending-index scan that replaces the current best only by a recv that strictly
+ * precedes it; A precedes B when min{P_B, M_A} < min{P_A, M_B}, and when those are
+ * equal, when M+_A < M+_B) and removed.
+ *   op_time [B][N], recv_time [B][n_recv]   device, row-major
+ *   order [B][n_recv] device: step -> recv index
+ *   rank  [B][n_recv] device: recv index -> step            (may be NULL)
+ *   sel_P, sel_Mplus [B][n_recv] device: P and M+ of each recv in the round that
+ *         selected it (+infinity when no M+ exists)          (each may be NULL)
+ * B = 0 is valid.
+ */
+int tictac_tac_priority(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus,
+                        tictac_stream stream);
+
+/*
+ * Sec. 3.2: one iteration under a transfer order, for B timing samples.  One
+ * channel serves the recvs back to back from t = 0 in the given order (Sec. 5.1:
+ * one active transfer per channel, released in priority order); one compute
+ * device runs one op at a time and never idles while an op is ready.
+ *   order: device, recv indices.  order_stride = 0: one order [n_recv] for every
+ *          sample; order_stride = n_recv: order [B][n_recv].  Must be a
+ *          permutation of 0..n_recv-1 (not checked on the device).
+ *   makespan [B] device: finish time of the last op
+ *   eff      [B] device: E = (U - m) / (U - L) (Eq. 3); 1 when U == L
+ *   U, L, S  [B] device, each may be NULL: U = sum of all times (Eq. 1),
+ *          L = max(sum of compute times, sum of transfer times) (Eq. 2),
+ *          S = (U - L) / L (Eq. 4); 0 when U == L or L == 0
+ */
+int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                    const double *op_time, const double *recv_time, double *makespan, double *eff,
+                    double *U, double *L, double *S, tictac_stream stream);
+
+/*
+ * Algorithm 3 followed by the iteration under the order it produced, in one pass
+ * over the timing samples (each op_time row is read once).  Outputs as in
+ * tictac_tac_priority and tictac_simulate; order must not be NULL, every other
+ * output may be.
+ */
+int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus,
+                        double *makespan, double *eff, double *U, double *L, double *S,
+                        tictac_stream stream);
+
+/* Message of the last error on the calling thread; valid until its next call. */
+const char *tictac_last_error(void);
+
+/* Library version, "major.minor". */
+const char *tictac_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TICTAC_H */

@@ -1,0 +1,190 @@
+"""ctypes binding of ``libtictac.so`` (C ABI declared in ``include/tictac.h``).
+
+Argument marshalling only: every step of the method runs in the library's HIP
+kernels.  PyTorch is used for device memory (outputs are returned as CUDA tensors)
+and for the current stream.  There is no CPU fallback: if the compiled library is
+missing, importing a function from here raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtictac.so")
+
+PRIO_INF = np.iinfo(np.int32).max
+
+STATUS = {
+    0: "TICTAC_OK", -1: "TICTAC_ERR_NULL", -2: "TICTAC_ERR_BAD_CSR", -3: "TICTAC_ERR_CYCLE",
+    -4: "TICTAC_ERR_RECV_NOT_ROOT", -5: "TICTAC_ERR_DUP_RECV", -6: "TICTAC_ERR_BAD_ORDER",
+    -7: "TICTAC_ERR_HIP", -8: "TICTAC_ERR_NO_MEM", -9: "TICTAC_ERR_UNSUPPORTED",
+}
+
+EXPORTS = (
+    "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
+    "tictac_dag_free",
+    "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
+    "tictac_last_error", "tictac_version",
+)
+
+
+class TicTacError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{STATUS.get(code, code)}: {message}")
+        self.code = code
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (run ``python -m paper_1803_03288_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with paper_1803_03288_amd/build.py")
+        L = ctypes.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(L, name).restype = ctypes.c_int
+        L.tictac_last_error.restype = ctypes.c_char_p
+        L.tictac_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise TicTacError(rc, lib().tictac_last_error().decode())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None or t.numel() == 0 else t.data_ptr())
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _np_ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+class Dag:
+    """Owner of a ``tictac_dag`` handle."""
+
+    def __init__(self, handle: ctypes.c_void_p):
+        self._h = handle
+        vals = [ctypes.c_int32() for _ in range(5)]
+        _check(lib().tictac_dag_info(self._h, *(ctypes.byref(v) for v in vals)))
+        self.n_ops, self.n_recv, self.words, self.n_levels, self.n_classes = (v.value for v in vals)
+        self.n_compute = self.n_ops - self.n_recv
+
+    def deps(self) -> torch.Tensor:
+        """op.dep as an int64 CUDA tensor ``[n_ops][W]`` (bit patterns of the uint64 words)."""
+        out = torch.empty((self.n_ops, self.words), dtype=torch.int64, device="cuda")
+        _check(lib().tictac_dag_copy_deps(self._h, _dev(out), _stream()))
+        return out
+
+    def recompute_deps(self) -> None:
+        """``tictac_dag_recompute_deps``: run the propagation kernel again (for timing)."""
+        _check(lib().tictac_dag_recompute_deps(self._h, _stream()))
+
+    def close(self) -> None:
+        if self._h is not None:
+            lib().tictac_dag_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def build_deps(n_ops: int, row_ptr, col_idx, recv_ids) -> Dag:
+    """``tictac_build_deps``: host predecessor CSR and recv ids in, handle out."""
+    row_ptr, col_idx, recv_ids = _host_i32(row_ptr), _host_i32(col_idx), _host_i32(recv_ids)
+    h = ctypes.c_void_p()
+    _check(lib().tictac_build_deps(ctypes.c_int32(n_ops), _np_ptr(row_ptr), _np_ptr(col_idx),
+                                   ctypes.c_int32(recv_ids.size), _np_ptr(recv_ids), _stream(), ctypes.byref(h)))
+    return Dag(h)
+
+
+def tic_priority(dag: Dag) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """``tictac_tic_priority``: ``(prio, order, rank)``, int32 CUDA tensors ``[R]``."""
+    R = dag.n_recv
+    prio, order, rank = (torch.empty(R, dtype=torch.int32, device="cuda") for _ in range(3))
+    _check(lib().tictac_tic_priority(dag._h, _dev(prio), _dev(order), _dev(rank), _stream()))
+    return prio, order, rank
+
+
+def _check_times(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor) -> int:
+    B = recv_time.shape[0]
+    assert op_time.is_cuda and recv_time.is_cuda
+    assert op_time.dtype == torch.float64 and recv_time.dtype == torch.float64
+    assert op_time.is_contiguous() and recv_time.is_contiguous()
+    assert tuple(op_time.shape) == (B, dag.n_compute), (tuple(op_time.shape), (B, dag.n_compute))
+    assert tuple(recv_time.shape) == (B, dag.n_recv)
+    return B
+
+
+def tac_priority(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_rank: bool = True,
+                 want_sel: bool = False):
+    """``tictac_tac_priority``: ``(order, rank, sel_P, sel_Mplus)``, each ``[B][R]`` (None if not asked for)."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    order = torch.empty((B, R), dtype=torch.int32, device="cuda")
+    rank = torch.empty((B, R), dtype=torch.int32, device="cuda") if want_rank else None
+    sel_P = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
+    sel_M = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
+    _check(lib().tictac_tac_priority(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order),
+                                     _dev(rank), _dev(sel_P), _dev(sel_M), _stream()))
+    return order, rank, sel_P, sel_M
+
+
+def simulate(dag: Dag, order: torch.Tensor, op_time: torch.Tensor, recv_time: torch.Tensor):
+    """``tictac_simulate``: ``(makespan, eff, U, L, S)``, float64 CUDA tensors ``[B]``.
+    ``order`` is int32 ``[R]`` (shared) or ``[B][R]``."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    assert order.is_cuda and order.dtype == torch.int32 and order.is_contiguous()
+    if order.dim() == 1:
+        assert order.shape[0] == R
+        stride = 0
+    else:
+        assert tuple(order.shape) == (B, R)
+        stride = R
+    out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
+    _check(lib().tictac_simulate(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride), _dev(op_time),
+                                 _dev(recv_time), *(_dev(o) for o in out), _stream()))
+    return tuple(out)
+
+
+def tac_simulate(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_rank: bool = False,
+                 want_sel: bool = False):
+    """``tictac_tac_simulate``: TAC and the iteration under its order in one pass.
+    Returns ``(order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S)``."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    order = torch.empty((B, R), dtype=torch.int32, device="cuda")
+    rank = torch.empty((B, R), dtype=torch.int32, device="cuda") if want_rank else None
+    sel_P = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
+    sel_M = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
+    out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
+    _check(lib().tictac_tac_simulate(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order),
+                                     _dev(rank), _dev(sel_P), _dev(sel_M), *(_dev(o) for o in out), _stream()))
+    return (order, rank, sel_P, sel_M) + tuple(out)
+
+
+def version() -> str:
+    return lib().tictac_version().decode()

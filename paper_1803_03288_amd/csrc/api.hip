@@ -1,0 +1,381 @@
+// C ABI of libtictac: argument checks, graph validation and levelling, grouping of
+// compute ops into classes of identical dependency sets, and the calls into the
+// kernel launchers.  All arithmetic of the method runs in the kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <numeric>
+
+#include "internal.h"
+
+namespace tictac {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return TICTAC_ERR_HIP;                                                           \
+        }                                                                                    \
+    } while (0)
+
+template <typename T>
+static hipError_t upload(T **dst, const std::vector<T> &src, hipStream_t s)
+{
+    *dst = nullptr;
+    if (src.empty()) return hipSuccess;
+    hipError_t e = hipMalloc((void **)dst, src.size() * sizeof(T));
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, s);
+}
+
+hipError_t ensure_workspace(Dag *d, size_t bytes)
+{
+    if (bytes <= d->work_bytes) return hipSuccess;
+    if (d->d_work) {
+        hipError_t e = hipFree(d->d_work);   // synchronises: earlier users of the old block are done
+        d->d_work = nullptr;
+        d->work_bytes = 0;
+        if (e != hipSuccess) return e;
+    }
+    size_t want = bytes + bytes / 8;
+    hipError_t e = hipMalloc(&d->d_work, want);
+    if (e != hipSuccess) return e;
+    d->work_bytes = want;
+    return hipSuccess;
+}
+
+static void free_dag(Dag *d)
+{
+    if (!d) return;
+    void *ptrs[] = {d->d_row_ptr, d->d_col_idx, d->d_recv_of_op, d->d_comp_col, d->d_lvl_ptr, d->d_lvl_ops,
+                    d->d_dep, d->d_cls_dep, d->d_cls_depT, d->d_cls_cnt0, d->d_cls_ptr, d->d_cls_cols,
+                    d->d_work};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete d;
+}
+
+// Groups the compute ops by identical dependency rows.  `rows` holds the rows of the
+// compute ops in op_time column order.  Classes are numbered by their first member;
+// a class with more than `max_members` ops is split into consecutive pieces (the
+// pieces have the same row, which every kernel handles like distinct classes).
+static void group_classes(const std::vector<uint64_t> &rows, int32_t N, int32_t W, int32_t max_members,
+                          std::vector<uint64_t> &cls_dep, std::vector<int32_t> &cls_ptr,
+                          std::vector<int32_t> &cls_cols, int32_t &n_distinct)
+{
+    std::vector<int32_t> idx(N);
+    std::iota(idx.begin(), idx.end(), 0);
+    std::vector<uint64_t> hash(N, 0);
+    for (int32_t j = 0; j < N; ++j) {
+        uint64_t h = 0x9E3779B97F4A7C15ull;
+        for (int32_t w = 0; w < W; ++w) {
+            h ^= rows[(size_t)j * W + w] + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+            h *= 0xFF51AFD7ED558CCDull;
+        }
+        hash[j] = h;
+    }
+    auto row_less = [&](int32_t a, int32_t b) {
+        if (hash[a] != hash[b]) return hash[a] < hash[b];
+        int c = W ? memcmp(&rows[(size_t)a * W], &rows[(size_t)b * W], (size_t)W * 8) : 0;
+        if (c != 0) return c < 0;
+        return a < b;
+    };
+    std::sort(idx.begin(), idx.end(), row_less);
+    // runs of equal rows; members ascending inside a run because of the final tie-break
+    struct Run { int32_t first, begin, end; };
+    std::vector<Run> runs;
+    for (int32_t k = 0; k < N;) {
+        int32_t e = k + 1;
+        while (e < N && hash[idx[e]] == hash[idx[k]] &&
+               (W == 0 || memcmp(&rows[(size_t)idx[e] * W], &rows[(size_t)idx[k] * W], (size_t)W * 8) == 0))
+            ++e;
+        runs.push_back({idx[k], k, e});
+        k = e;
+    }
+    std::sort(runs.begin(), runs.end(), [](const Run &a, const Run &b) { return a.first < b.first; });
+    n_distinct = (int32_t)runs.size();
+    cls_dep.clear(); cls_ptr.clear(); cls_cols.clear();
+    cls_ptr.push_back(0);
+    for (const Run &r : runs) {
+        for (int32_t k = r.begin; k < r.end; k += max_members) {
+            int32_t e = std::min(r.end, k + max_members);
+            for (int32_t m = k; m < e; ++m) cls_cols.push_back(idx[m]);
+            cls_ptr.push_back((int32_t)cls_cols.size());
+            for (int32_t w = 0; w < W; ++w) cls_dep.push_back(rows[(size_t)r.first * W + w]);
+        }
+    }
+}
+
+static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int32_t R, const int32_t *recv_ids,
+                 hipStream_t s, Dag *d)
+{
+    // ---- validation (host) ----
+    if (n < 0 || R < 0 || R > n) { set_error("bad sizes: n_ops=%d n_recv=%d", n, R); return TICTAC_ERR_BAD_CSR; }
+    if (!row_ptr) { set_error("pred_row_ptr is NULL"); return TICTAC_ERR_NULL; }
+    if (R > 0 && !recv_ids) { set_error("recv_ids is NULL"); return TICTAC_ERR_NULL; }
+    if (row_ptr[0] != 0) { set_error("pred_row_ptr[0] != 0"); return TICTAC_ERR_BAD_CSR; }
+    for (int32_t v = 0; v < n; ++v)
+        if (row_ptr[v + 1] < row_ptr[v]) { set_error("pred_row_ptr decreases at op %d", v); return TICTAC_ERR_BAD_CSR; }
+    const int32_t E = row_ptr[n];
+    if (E > 0 && !col_idx) { set_error("pred_col_idx is NULL"); return TICTAC_ERR_NULL; }
+    for (int32_t e = 0; e < E; ++e)
+        if (col_idx[e] < 0 || col_idx[e] >= n) { set_error("pred_col_idx[%d]=%d out of range", e, col_idx[e]); return TICTAC_ERR_BAD_CSR; }
+    std::vector<int32_t> recv_of_op(n, -1);
+    for (int32_t i = 0; i < R; ++i) {
+        int32_t v = recv_ids[i];
+        if (v < 0 || v >= n) { set_error("recv_ids[%d]=%d out of range", i, v); return TICTAC_ERR_BAD_CSR; }
+        if (recv_of_op[v] >= 0) { set_error("op %d listed twice in recv_ids", v); return TICTAC_ERR_DUP_RECV; }
+        recv_of_op[v] = i;
+    }
+    for (int32_t i = 0; i < R; ++i) {
+        int32_t v = recv_ids[i];
+        if (row_ptr[v + 1] != row_ptr[v]) { set_error("recv %d (op %d) has predecessors", i, v); return TICTAC_ERR_RECV_NOT_ROOT; }
+    }
+    // ---- levels = longest path from a root (Kahn) ----
+    std::vector<int32_t> sptr(n + 1, 0), sidx(E), waiting(n), level(n, 0), queue;
+    for (int32_t e = 0; e < E; ++e) sptr[col_idx[e] + 1]++;
+    for (int32_t v = 0; v < n; ++v) sptr[v + 1] += sptr[v];
+    {
+        std::vector<int32_t> fill(sptr.begin(), sptr.end() - 1);
+        for (int32_t v = 0; v < n; ++v)
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) sidx[fill[col_idx[e]]++] = v;
+    }
+    queue.reserve(n);
+    for (int32_t v = 0; v < n; ++v) {
+        waiting[v] = row_ptr[v + 1] - row_ptr[v];
+        if (waiting[v] == 0) queue.push_back(v);
+    }
+    int32_t n_levels = 0;
+    for (size_t q = 0; q < queue.size(); ++q) {
+        int32_t u = queue[q];
+        n_levels = std::max(n_levels, level[u] + 1);
+        for (int32_t e = sptr[u]; e < sptr[u + 1]; ++e) {
+            int32_t v = sidx[e];
+            level[v] = std::max(level[v], level[u] + 1);
+            if (--waiting[v] == 0) queue.push_back(v);
+        }
+    }
+    if ((int32_t)queue.size() != n) { set_error("the graph has a cycle"); return TICTAC_ERR_CYCLE; }
+    std::vector<int32_t> lvl_ptr(n_levels + 1, 0), lvl_ops(n);
+    for (int32_t v = 0; v < n; ++v) lvl_ptr[level[v] + 1]++;
+    int32_t max_width = 0;
+    for (int32_t l = 0; l < n_levels; ++l) { max_width = std::max(max_width, lvl_ptr[l + 1]); lvl_ptr[l + 1] += lvl_ptr[l]; }
+    {
+        std::vector<int32_t> fill(lvl_ptr.begin(), lvl_ptr.end() - 1);
+        for (int32_t v = 0; v < n; ++v) lvl_ops[fill[level[v]]++] = v;   // ascending op id inside a level
+    }
+    std::vector<int32_t> comp_col(n, -1);
+    {
+        int32_t j = 0;
+        for (int32_t v = 0; v < n; ++v)
+            if (recv_of_op[v] < 0) comp_col[v] = j++;
+    }
+
+    d->n = n; d->R = R; d->W = (R + 63) / 64; d->N = n - R; d->E = E;
+    d->n_levels = n_levels; d->max_level_width = max_width;
+    HIP_TRY(hipGetDevice(&d->device));
+
+    // ---- upload and propagate ----
+    std::vector<int32_t> rp(row_ptr, row_ptr + n + 1), ci(col_idx, col_idx + E);
+    HIP_TRY(upload(&d->d_row_ptr, rp, s));
+    HIP_TRY(upload(&d->d_col_idx, ci, s));
+    HIP_TRY(upload(&d->d_recv_of_op, recv_of_op, s));
+    HIP_TRY(upload(&d->d_comp_col, comp_col, s));
+    HIP_TRY(upload(&d->d_lvl_ptr, lvl_ptr, s));
+    HIP_TRY(upload(&d->d_lvl_ops, lvl_ops, s));
+    const size_t dep_words = (size_t)n * d->W;
+    if (dep_words) {
+        HIP_TRY(hipMalloc((void **)&d->d_dep, dep_words * 8));
+        HIP_TRY(launch_propagate(*d, s));
+    }
+
+    // ---- classes of identical rows among the compute ops ----
+    std::vector<uint64_t> rows((size_t)d->N * d->W);
+    if (!rows.empty()) {
+        std::vector<uint64_t> all(dep_words);
+        HIP_TRY(hipMemcpyAsync(all.data(), d->d_dep, dep_words * 8, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        for (int32_t v = 0; v < n; ++v)
+            if (comp_col[v] >= 0)
+                memcpy(&rows[(size_t)comp_col[v] * d->W], &all[(size_t)v * d->W], (size_t)d->W * 8);
+    }
+    std::vector<uint64_t> cls_dep;
+    std::vector<int32_t> cls_ptr, cls_cols;
+    const int32_t max_members = std::min(256, std::max(8, (d->N + 127) / 128));
+    group_classes(rows, d->N, d->W, max_members, cls_dep, cls_ptr, cls_cols, d->C_distinct);
+    d->C = (int32_t)cls_ptr.size() - 1;
+    d->Cpad = (d->C + 63) / 64 * 64;
+    std::vector<int32_t> cnt0(d->C, 0);
+    std::vector<uint64_t> depT((size_t)d->W * d->Cpad, 0);
+    d->cls_nnz = 0;
+    for (int32_t c = 0; c < d->C; ++c)
+        for (int32_t w = 0; w < d->W; ++w) {
+            uint64_t x = cls_dep[(size_t)c * d->W + w];
+            cnt0[c] += __builtin_popcountll(x);
+            depT[(size_t)w * d->Cpad + c] = x;
+        }
+    for (int32_t c = 0; c < d->C; ++c) d->cls_nnz += cnt0[c];
+    HIP_TRY(upload(&d->d_cls_dep, cls_dep, s));
+    HIP_TRY(upload(&d->d_cls_depT, depT, s));
+    HIP_TRY(upload(&d->d_cls_cnt0, cnt0, s));
+    HIP_TRY(upload(&d->d_cls_ptr, cls_ptr, s));
+    HIP_TRY(upload(&d->d_cls_cols, cls_cols, s));
+    HIP_TRY(hipStreamSynchronize(s));   // host vectors go out of scope; the handle is complete
+    return TICTAC_OK;
+}
+
+}  // namespace tictac
+
+using namespace tictac;
+
+extern "C" {
+
+int tictac_build_deps(int32_t n_ops, const int32_t *pred_row_ptr, const int32_t *pred_col_idx, int32_t n_recv,
+                      const int32_t *recv_ids, tictac_stream stream, tictac_dag **out)
+{
+    if (!out) { set_error("out is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = new (std::nothrow) Dag();
+    if (!d) { set_error("out of host memory"); return TICTAC_ERR_NO_MEM; }
+    int rc;
+    try {
+        rc = build(n_ops, pred_row_ptr, pred_col_idx, n_recv, recv_ids, (hipStream_t)stream, d);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        rc = TICTAC_ERR_NO_MEM;
+    }
+    if (rc != TICTAC_OK) { free_dag(d); return rc; }
+    *out = reinterpret_cast<tictac_dag *>(d);
+    return TICTAC_OK;
+}
+
+int tictac_dag_info(const tictac_dag *dag, int32_t *n_ops, int32_t *n_recv, int32_t *words, int32_t *n_levels,
+                    int32_t *n_classes)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    const Dag *d = reinterpret_cast<const Dag *>(dag);
+    if (n_ops) *n_ops = d->n;
+    if (n_recv) *n_recv = d->R;
+    if (words) *words = d->W;
+    if (n_levels) *n_levels = d->n_levels;
+    if (n_classes) *n_classes = d->C_distinct;
+    return TICTAC_OK;
+}
+
+int tictac_dag_deps(const tictac_dag *dag, const uint64_t **dep_device)
+{
+    if (!dag || !dep_device) { set_error("NULL argument"); return TICTAC_ERR_NULL; }
+    *dep_device = reinterpret_cast<const Dag *>(dag)->d_dep;
+    return TICTAC_OK;
+}
+
+int tictac_dag_copy_deps(const tictac_dag *dag, uint64_t *dst_device, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    const Dag *d = reinterpret_cast<const Dag *>(dag);
+    const size_t bytes = (size_t)d->n * d->W * 8;
+    if (bytes == 0) return TICTAC_OK;
+    if (!dst_device) { set_error("dst_device is NULL"); return TICTAC_ERR_NULL; }
+    HIP_TRY(hipMemcpyAsync(dst_device, d->d_dep, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_dag_recompute_deps(tictac_dag *dag, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = reinterpret_cast<Dag *>(dag);
+    HIP_TRY(launch_propagate(*d, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_dag_free(tictac_dag *dag)
+{
+    if (!dag) return TICTAC_OK;
+    free_dag(reinterpret_cast<Dag *>(dag));
+    return TICTAC_OK;
+}
+
+int tictac_tic_priority(const tictac_dag *dag, int32_t *prio, int32_t *order, int32_t *rank, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    const Dag *d = reinterpret_cast<const Dag *>(dag);
+    if (d->R == 0) return TICTAC_OK;
+    if (!prio) { set_error("prio is NULL"); return TICTAC_ERR_NULL; }
+    HIP_TRY(launch_tic(*d, prio, order, rank, nullptr, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+static int check_batch(const Dag *d, int32_t B, const double *op_time, const double *recv_time)
+{
+    if (B < 0) { set_error("B = %d", B); return TICTAC_ERR_BAD_CSR; }
+    if (B > 0 && d->N > 0 && !op_time) { set_error("op_time is NULL"); return TICTAC_ERR_NULL; }
+    if (B > 0 && d->R > 0 && !recv_time) { set_error("recv_time is NULL"); return TICTAC_ERR_NULL; }
+    return TICTAC_OK;
+}
+
+int tictac_tac_priority(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (B == 0 || d->R == 0) return TICTAC_OK;
+    if (!order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    TacArgs a{B, op_time, recv_time, order, rank, sel_P, sel_Mplus, false, nullptr, nullptr, nullptr, nullptr, nullptr};
+    HIP_TRY(launch_tac(*d, a, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, double *makespan,
+                        double *eff, double *U, double *L, double *S, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (B == 0) return TICTAC_OK;
+    if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    TacArgs a{B, op_time, recv_time, order, rank, sel_P, sel_Mplus, true, makespan, eff, U, L, S};
+    HIP_TRY(launch_tac(*d, a, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                    const double *op_time, const double *recv_time, double *makespan, double *eff, double *U,
+                    double *L, double *S, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (order_stride != 0 && order_stride != d->R) {
+        set_error("order_stride = %d, expected 0 or n_recv = %d", order_stride, d->R);
+        return TICTAC_ERR_BAD_ORDER;
+    }
+    if (B == 0) return TICTAC_OK;
+    if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
+    SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
+    HIP_TRY(launch_simulate(*d, a, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+const char *tictac_last_error(void) { return g_err; }
+
+const char *tictac_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Wave- and block-level helpers shared by the TAC and simulation kernels (wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tictac {
+
+#define TT_INF (__builtin_huge_val())
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ double wave_min_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmin(v, __shfl_xor(v, off));
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+__device__ __forceinline__ int wave_min_i32(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
+    return v;
+}
+
+// Block-wide reductions; every thread of the block must call them (uniform control
+// flow).  `red` is LDS scratch of at least BS/64 elements of the reduced type; two
+// barriers make it reusable right after the call.
+template <int BS>
+__device__ __forceinline__ double block_min_f64(double v, double *red)
+{
+    v = wave_min_f64(v);
+    if (BS == 64) return v;
+    __syncthreads();
+    if (lane_id() == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = red[0];
+#pragma unroll
+    for (int k = 1; k < BS / 64; ++k) r = fmin(r, red[k]);
+    return r;
+}
+
+template <int BS>
+__device__ __forceinline__ double block_sum_f64(double v, double *red)
+{
+    v = wave_sum_f64(v);
+    if (BS == 64) return v;
+    __syncthreads();
+    if (lane_id() == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = red[0];
+#pragma unroll
+    for (int k = 1; k < BS / 64; ++k) r += red[k];
+    return r;
+}
+
+template <int BS>
+__device__ __forceinline__ int block_min_i32(int v, double *red)
+{
+    v = wave_min_i32(v);
+    if (BS == 64) return v;
+    int *ri = reinterpret_cast<int *>(red);
+    __syncthreads();
+    if (lane_id() == 0) ri[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int r = ri[0];
+#pragma unroll
+    for (int k = 1; k < BS / 64; ++k) r = min(r, ri[k]);
+    return r;
+}
+
+// arr[idx] += v for the threads with `active`, arr in LDS.  With one wave per block the
+// additions are applied one after the other in lane order by lane 0 (a fixed order, so
+// the result is reproducible bit for bit); with several waves LDS atomics are used.
+// Must be called by all threads of a wave together.
+template <int BS>
+__device__ __forceinline__ void lds_scatter_add(double *arr, int idx, double v, bool active)
+{
+    if (BS == 64) {
+        unsigned long long m = __ballot(active);
+        while (m) {
+            const int l = __builtin_ctzll(m);
+            m &= m - 1;
+            const int i = __shfl(idx, l);
+            const double x = __shfl(v, l);
+            if (threadIdx.x == 0) arr[i] += x;
+        }
+    } else {
+        if (active) atomicAdd(&arr[idx], v);
+    }
+}
+
+}  // namespace tictac

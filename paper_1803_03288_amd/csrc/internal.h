@@ -1,0 +1,81 @@
+// Internal declarations of libtictac (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "tictac.h"
+
+namespace tictac {
+
+void set_error(const char *fmt, ...);
+
+// Everything a handle owns.  Device arrays are sized exactly; empty ones are NULL.
+struct Dag {
+    int32_t n = 0, R = 0, W = 0, N = 0, E = 0;
+    int32_t n_levels = 0;
+    int32_t max_level_width = 0;
+    int device = 0;
+
+    // graph, by op id
+    int32_t *d_row_ptr = nullptr;   // [n+1]
+    int32_t *d_col_idx = nullptr;   // [E]
+    int32_t *d_recv_of_op = nullptr;// [n]  recv index or -1
+    int32_t *d_comp_col = nullptr;  // [n]  column in op_time, or -1 for a recv
+    // level structure: ops sorted by level (longest path from a root)
+    int32_t *d_lvl_ptr = nullptr;   // [n_levels+1]
+    int32_t *d_lvl_ops = nullptr;   // [n]
+    // op.dep
+    uint64_t *d_dep = nullptr;      // [n][W]
+
+    // classes of compute ops with identical dep rows (rows with no recv: class 0 if any)
+    int32_t C = 0;                  // number of classes (after splitting long ones)
+    int32_t C_distinct = 0;         // number of distinct non-empty rows
+    int32_t Cpad = 0;               // C rounded up to a multiple of 64
+    int64_t cls_nnz = 0;            // total number of set bits over class rows
+    uint64_t *d_cls_dep = nullptr;  // [C][W]
+    uint64_t *d_cls_depT = nullptr; // [W][Cpad]
+    int32_t *d_cls_cnt0 = nullptr;  // [C]   |dep| of the class
+    int32_t *d_cls_ptr = nullptr;   // [C+1] members of class c: cls_cols[cls_ptr[c] .. cls_ptr[c+1])
+    int32_t *d_cls_cols = nullptr;  // [N]   op_time columns, grouped by class
+
+    // scratch owned by the handle (grown on demand, stream-ordered use)
+    void *d_work = nullptr;
+    size_t work_bytes = 0;
+};
+
+hipError_t ensure_workspace(Dag *d, size_t bytes);
+
+// ---- kernel launchers (each returns the HIP status of its launches) ----
+
+// op.dep for every op (Sec. 4.1)
+hipError_t launch_propagate(const Dag &d, hipStream_t s);
+
+// TIC (Sec. 4.2): prio always; order / rank when not NULL
+hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank, int32_t *scratch_prio,
+                      hipStream_t s);
+
+struct TacArgs {
+    int32_t B;
+    const double *op_time, *recv_time;
+    int32_t *order, *rank;
+    double *sel_P, *sel_Mplus;
+    // fused simulation outputs; all NULL = TAC only
+    bool simulate;
+    double *makespan, *eff, *U, *L, *S;
+};
+hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s);
+
+struct SimArgs {
+    int32_t B;
+    const int32_t *order;
+    int32_t order_stride;
+    const double *op_time, *recv_time;
+    double *makespan, *eff, *U, *L, *S;
+};
+hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
+
+}  // namespace tictac

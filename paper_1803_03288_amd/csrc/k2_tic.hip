@@ -1,0 +1,101 @@
+// TIC (Sec. 4.2, Algorithm 2): with every recv outstanding and the General Time Oracle
+// (recv = 1, others = 0), op.M = |op.dep|, every P is 0 and
+//   priority(recv i) = M+ = min{ |dep[v]| : v a compute op, i in dep[v], |dep[v]| > 1 }.
+// Integer arithmetic throughout, so the result does not depend on the order of the
+// min-updates.
+#include "internal.h"
+
+namespace tictac {
+
+__global__ void fill_i32(int32_t *p, int32_t n, int32_t value)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+// One wave per row at a time: popcount of the row, then a min-update of every recv in it.
+// USE_LDS: the block keeps its own copy of prio in LDS and merges it at the end.
+template <bool USE_LDS>
+__global__ void __launch_bounds__(256)
+tic_min_kernel(int32_t n, int32_t R, int32_t W, const uint64_t *__restrict__ dep,
+               const int32_t *__restrict__ recv_of_op, int32_t rows_per_block, int32_t *prio)
+{
+    extern __shared__ int32_t prio_l[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    if (USE_LDS) {
+        for (int32_t i = threadIdx.x; i < R; i += blockDim.x) prio_l[i] = TICTAC_PRIO_INF;
+        __syncthreads();
+    }
+    int32_t *target = USE_LDS ? prio_l : prio;
+    const int32_t v0 = blockIdx.x * rows_per_block;
+    const int32_t v1 = min(n, v0 + rows_per_block);
+    for (int32_t v = v0 + wave; v < v1; v += n_waves) {
+        if (recv_of_op[v] >= 0) continue;                 // wave-uniform
+        const uint64_t *row = dep + (size_t)v * W;
+        int32_t cnt = 0;
+        for (int32_t w = lane; w < W; w += 64) cnt += __popcll(row[w]);
+        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+        if (cnt <= 1) continue;                           // wave-uniform
+        for (int32_t w = lane; w < W; w += 64) {
+            uint64_t x = row[w];
+            while (x) {
+                const int b = __builtin_ctzll(x);
+                x &= x - 1;
+                atomicMin(&target[w * 64 + b], cnt);
+            }
+        }
+    }
+    if (USE_LDS) {
+        __syncthreads();
+        for (int32_t i = threadIdx.x; i < R; i += blockDim.x)
+            if (prio_l[i] != TICTAC_PRIO_INF) atomicMin(&prio[i], prio_l[i]);
+    }
+}
+
+// rank[i] = number of recvs j with (prio[j], j) < (prio[i], i); order[rank[i]] = i.
+__global__ void __launch_bounds__(256)
+tic_rank_kernel(int32_t R, const int32_t *__restrict__ prio, int32_t *order, int32_t *rank)
+{
+    __shared__ int32_t tile[1024];
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t pi = (i < R) ? prio[i] : 0;
+    int32_t r = 0;
+    for (int32_t j0 = 0; j0 < R; j0 += 1024) {
+        const int32_t m = min(1024, R - j0);
+        __syncthreads();
+        for (int32_t j = threadIdx.x; j < m; j += blockDim.x) tile[j] = prio[j0 + j];
+        __syncthreads();
+        if (i < R)
+            for (int32_t j = 0; j < m; ++j) {
+                const int32_t pj = tile[j];
+                r += (pj < pi) || (pj == pi && (j0 + j) < i);
+            }
+    }
+    if (i < R) {
+        if (rank) rank[i] = r;
+        if (order) order[r] = i;
+    }
+}
+
+hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank, int32_t *, hipStream_t s)
+{
+    const int32_t R = d.R;
+    if (R == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32, dim3((R + 255) / 256), dim3(256), 0, s, prio, R, (int32_t)TICTAC_PRIO_INF);
+    if (d.n > 0) {
+        const int32_t rows_per_block = d.n <= 4096 ? 32 : 128;
+        const int blocks = (d.n + rows_per_block - 1) / rows_per_block;
+        const size_t lds = (size_t)R * sizeof(int32_t);
+        if (lds <= 48 * 1024)
+            hipLaunchKernelGGL(tic_min_kernel<true>, dim3(blocks), dim3(256), lds, s, d.n, R, d.W, d.d_dep,
+                               d.d_recv_of_op, rows_per_block, prio);
+        else
+            hipLaunchKernelGGL(tic_min_kernel<false>, dim3(blocks), dim3(256), 0, s, d.n, R, d.W, d.d_dep,
+                               d.d_recv_of_op, rows_per_block, prio);
+    }
+    if (order || rank)
+        hipLaunchKernelGGL(tic_rank_kernel, dim3((R + 255) / 256), dim3(256), 0, s, R, prio, order, rank);
+    return hipGetLastError();
+}
+
+}  // namespace tictac

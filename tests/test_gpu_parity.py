@@ -1,0 +1,293 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer outputs (bitsets, TIC priorities, orders, ranks) must be
+bit-exact; float64 outputs within 1e-5 relative (they are in fact exact on the presets,
+whose times are multiples of 2**-30 s)."""
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_1803_03288_amd import workloads as wl
+
+from helpers import dep_bool
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def tt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1803_03288_amd import binding
+    binding.lib()            # raises if the library has not been built
+    return binding
+
+
+_cache = {}
+
+
+def get(tt, name, maker=None):
+    """(Dag description, GPU handle, oracle dep matrix), cached per name."""
+    if name not in _cache:
+        d = maker() if maker else wl.preset(name)
+        print(f"[build] {name}: n={d.n_ops} R={d.n_recv} E={d.n_edges}", flush=True)
+        h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+        dep = oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+        _cache[name] = (d, h, dep)
+    return _cache[name]
+
+
+def cuda(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def subset_rows(B, k):
+    """first k/2 samples + k/2 strided over the batch"""
+    k = min(k, B)
+    first = list(range(k // 2))
+    rest = sorted(set(np.linspace(k // 2, B - 1, k - k // 2).astype(int).tolist()) - set(first))
+    return first + rest
+
+
+SMALL = {
+    "layered70": lambda: wl.layered_dag(11, levels=9, width=7, fan_in=(1, 3), back=3, n_recv=70, attach=(1, 3)),
+    "relabel": lambda: wl.relabel(wl.layered_dag(12, levels=8, width=6, fan_in=(1, 3), back=2, n_recv=40,
+                                                 attach=(1, 4)), 5)[0],
+    "chain": lambda: wl.chain_dag(33),
+    "jobs": lambda: wl.independent_jobs_dag(9),
+    "funnel": lambda: wl.funnel_dag(6, 9),
+    "toy": wl.toy_dag,
+    "case2": wl.case2_dag,
+    "single": lambda: wl.chain_dag(1),
+    "mini_stress": lambda: wl.stress_dag(levels=40, width=50, n_recv=300, seed=14, batch=64),
+}
+PRESETS = ["tiny", "resnet50", "vgg16", "inception3", "stress"]
+
+
+# --------------------------------------------------------------------------
+# dependency bitsets and TIC: bit-exact on every preset at full size
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", PRESETS + list(SMALL))
+def test_deps_and_tic_bit_exact(tt, name):
+    d, h, dep = get(tt, name, SMALL.get(name))
+    assert (h.n_ops, h.n_recv, h.words) == (d.n_ops, d.n_recv, d.words)
+    got = h.deps().cpu().numpy().view(np.uint64)
+    assert got.shape == dep.shape
+    assert np.array_equal(got, dep)
+    prio, order, rank = (x.cpu().numpy() for x in tt.tic_priority(h))
+    eprio, eorder, erank = oracle.tic(dep, d.recv_ids)
+    assert np.array_equal(prio, eprio)
+    assert np.array_equal(order, eorder)
+    assert np.array_equal(rank, erank)
+    # number of classes reported = number of distinct non-empty rows among compute ops
+    rows = dep[d.compute_ids()]
+    assert h.n_classes == np.unique(rows, axis=0).shape[0]
+
+
+def test_no_recvs_and_empty_graph(tt):
+    d = wl.no_recv_dag(17)
+    h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    assert h.words == 0 and h.deps().numel() == 0
+    prio, order, rank = tt.tic_priority(h)
+    assert prio.numel() == 0
+    rng = np.random.default_rng(0)
+    op = rng.integers(1, 100, size=(5, 17)).astype(np.float64) * wl.QUANTUM
+    rv = np.zeros((5, 0))
+    o = tt.tac_priority(h, cuda(op), cuda(rv))[0]
+    assert tuple(o.shape) == (5, 0)
+    m, e, U, L, S = (x.cpu().numpy() for x in tt.simulate(h, torch.zeros(0, dtype=torch.int32, device="cuda"),
+                                                          cuda(op), cuda(rv)))
+    em, ee, eU, eL, eS = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, np.zeros(0, np.int32), op, rv)
+    for a, b in ((m, em), (e, ee), (U, eU), (L, eL), (S, eS)):
+        assert np.array_equal(a, b)
+    res = tt.tac_simulate(h, cuda(op), cuda(rv))
+    assert np.array_equal(res[4].cpu().numpy(), em) and np.array_equal(res[5].cpu().numpy(), ee)
+    # empty graph and B = 0
+    h0 = tt.build_deps(0, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32))
+    assert h0.n_ops == 0
+    d1, h1, _ = get(tt, "toy", wl.toy_dag)
+    o = tt.tac_priority(h1, torch.zeros((0, 2), dtype=torch.float64, device="cuda"),
+                        torch.zeros((0, 2), dtype=torch.float64, device="cuda"))[0]
+    assert tuple(o.shape) == (0, 2)
+
+
+# --------------------------------------------------------------------------
+# TAC and simulation
+# --------------------------------------------------------------------------
+
+def run_tac_sim_parity(tt, d, h, dep, op, rv, tag):
+    """TAC (order, rank, sel_P, sel_Mplus), simulation under the TAC order (per-sample
+    orders), the fused call, and simulation under the shared TIC order: all against the
+    oracle, element by element."""
+    print(f"[parity] {tag}: B={op.shape[0]}", flush=True)
+    R = d.n_recv
+    eo, er, eP, eM = oracle.tac(dep, d.recv_ids, op, rv)
+    gop, grv = cuda(op), cuda(rv)
+    o, r, sP, sM = tt.tac_priority(h, gop, grv, want_rank=True, want_sel=True)
+    o, r, sP, sM = o.cpu().numpy(), r.cpu().numpy(), sP.cpu().numpy(), sM.cpu().numpy()
+    assert np.array_equal(o, eo), f"{tag}: TAC order differs in {(o != eo).any(axis=1).sum()} samples"
+    assert np.array_equal(r, er)
+    np.testing.assert_allclose(sP, eP, rtol=RTOL, atol=0)
+    assert np.array_equal(np.isinf(sM), np.isinf(eM))
+    fin = np.isfinite(eM)
+    np.testing.assert_allclose(sM[fin], eM[fin], rtol=RTOL, atol=0)
+
+    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op, rv)
+    got = [x.cpu().numpy() for x in tt.simulate(h, cuda(eo), gop, grv)]
+    for a, b, nm in zip(got, exp, "m E U L S".split()):
+        np.testing.assert_allclose(a, b, rtol=RTOL, atol=1e-300, err_msg=f"{tag}: simulate {nm}")
+    fused = tt.tac_simulate(h, gop, grv, want_rank=True, want_sel=True)
+    assert np.array_equal(fused[0].cpu().numpy(), eo)
+    assert np.array_equal(fused[1].cpu().numpy(), er)
+    for a, b, nm in zip(fused[4:], exp, "m E U L S".split()):
+        np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-300, err_msg=f"{tag}: fused {nm}")
+    # the presets are quantised: results are exact, not merely close
+    assert np.array_equal(got[0], exp[0]) and np.array_equal(fused[4].cpu().numpy(), exp[0])
+
+    if R:
+        tic_order = oracle.tic(dep, d.recv_ids)[1]
+        exp2 = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, tic_order, op, rv)
+        got2 = [x.cpu().numpy() for x in tt.simulate(h, cuda(tic_order), gop, grv)]
+        for a, b, nm in zip(got2, exp2, "m E U L S".split()):
+            np.testing.assert_allclose(a, b, rtol=RTOL, atol=1e-300, err_msg=f"{tag}: simulate(TIC) {nm}")
+    return o
+
+
+@pytest.mark.parametrize("name,k", [("tiny", 1024), ("vgg16", 1024), ("resnet50", 96), ("inception3", 6)])
+def test_tac_and_simulate_presets(tt, name, k):
+    d, h, dep = get(tt, name)
+    rows = subset_rows(d.batch, k)
+    op, rv = wl.sample_rows(d, rows)
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name)
+
+
+@pytest.mark.parametrize("name", ["layered70", "relabel", "chain", "jobs", "funnel", "toy", "case2", "single",
+                                  "mini_stress"])
+def test_tac_and_simulate_small_graphs(tt, name):
+    d, h, dep = get(tt, name, SMALL[name])
+    B = 8 if name == "mini_stress" else 200
+    op, rv = wl.timing_samples(d, 0, B)
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name)
+
+
+@pytest.mark.parametrize("name", ["layered70", "jobs", "tiny", "case2"])
+def test_ties_and_zero_times(tt, name):
+    """Times drawn from a handful of values give many exact ties in the comparator; zero
+    transfer times force the literal selection path; zero compute times leave P at 0."""
+    d, h, dep = get(tt, name, SMALL.get(name))
+    rng = np.random.default_rng(3)
+    B = 300
+    op = rng.integers(0, 4, size=(B, d.n_compute)).astype(np.float64) * 0.25
+    rv = rng.integers(1, 4, size=(B, d.n_recv)).astype(np.float64) * 0.25
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name + "/ties")
+    rv0 = rv.copy()
+    rv0[rng.random(rv0.shape) < 0.2] = 0.0
+    run_tac_sim_parity(tt, d, h, dep, op, rv0, name + "/zero-transfers")
+
+
+def test_random_orders_per_sample(tt):
+    d, h, dep = get(tt, "layered70", SMALL["layered70"])
+    rng = np.random.default_rng(8)
+    B = 500
+    op, rv = wl.timing_samples(d, 0, B)
+    orders = np.stack([rng.permutation(d.n_recv) for _ in range(B)]).astype(np.int32)
+    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, orders, op, rv)
+    got = [x.cpu().numpy() for x in tt.simulate(h, cuda(orders), cuda(op), cuda(rv))]
+    for a, b in zip(got, exp):
+        assert np.array_equal(a, b)
+
+
+def test_power_of_two_scaling_and_determinism(tt):
+    d, h, dep = get(tt, "resnet50")
+    op, rv = wl.timing_samples(d, 0, 64)
+    a = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True, want_sel=True)
+    b = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True, want_sel=True)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    c = tt.tac_simulate(h, cuda(op * 4), cuda(rv * 4), want_rank=True, want_sel=True)
+    assert torch.equal(a[0], c[0])
+    assert torch.equal(a[4] * 4, c[4]) and torch.equal(a[5], c[5]) and torch.equal(a[8], c[8])
+
+
+# --------------------------------------------------------------------------
+# full sizes, in the launch configuration the benchmark times
+# --------------------------------------------------------------------------
+
+def closed_form_shared(depb_comp, order, op, rv):
+    """vectorised closed form of the makespan for one shared order (see helpers)."""
+    R = order.size
+    pos = np.zeros(R, dtype=np.int64)
+    pos[order] = np.arange(1, R + 1)
+    kappa = (depb_comp * pos[None, :]).max(axis=1) if R else np.zeros(depb_comp.shape[0], dtype=np.int64)
+    onehot = np.zeros((depb_comp.shape[0], R + 1))
+    onehot[np.arange(depb_comp.shape[0]), kappa] = 1.0
+    A = op @ onehot
+    F = np.concatenate([np.zeros((op.shape[0], 1)), np.cumsum(rv[:, order], axis=1)], axis=1)
+    S = np.cumsum(A[:, ::-1], axis=1)[:, ::-1]
+    return np.maximum((F + S).max(axis=1), F[:, -1])
+
+
+@pytest.mark.parametrize("name,B", [("resnet50", 65536), ("vgg16", 262144)])
+def test_full_batch_properties(tt, name, B):
+    """Whole batch of the preset: every order is a permutation, L <= m <= U, the makespan
+    equals the closed form recomputed in numpy from the oracle's dep matrix, and sampled
+    rows equal the oracle exactly."""
+    d, h, dep = get(tt, name)
+    assert B == d.batch
+    print(f"[full] {name}: generating {B} samples", flush=True)
+    op, rv = wl.timing_samples(d, 0, B)
+    gop, grv = cuda(op), cuda(rv)
+    res = tt.tac_simulate(h, gop, grv, want_rank=True)
+    order, rank = res[0], res[1]
+    m, e, U, L, S = (x.cpu().numpy() for x in res[4:])
+    R = d.n_recv
+    srt = torch.sort(order.long(), dim=1).values
+    assert torch.equal(srt, torch.arange(R, device="cuda").expand(B, R))
+    assert torch.equal(torch.gather(rank.long(), 1, order.long()), torch.arange(R, device="cuda").expand(B, R))
+    assert (L <= m).all() and (m <= U).all() and (e >= 0).all() and (e <= 1).all()
+    # sampled rows against the oracle
+    rows = subset_rows(B, 24 if name == "resnet50" else 256)
+    eo = oracle.tac(dep, d.recv_ids, op[rows], rv[rows])[0]
+    assert np.array_equal(order[rows].cpu().numpy(), eo)
+    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op[rows], rv[rows])
+    assert np.array_equal(m[rows], exp[0]) and np.array_equal(e[rows], exp[1])
+    # shared TIC order on the whole batch against the closed form
+    tic_order = oracle.tic(dep, d.recv_ids)[1]
+    m2 = tt.simulate(h, cuda(tic_order), gop, grv)[0].cpu().numpy()
+    depb = dep_bool(dep, R)[d.compute_ids()]
+    blk = 8192
+    for b0 in range(0, B, blk):
+        ref = closed_form_shared(depb, tic_order, op[b0:b0 + blk], rv[b0:b0 + blk])
+        assert np.array_equal(m2[b0:b0 + blk], ref)
+
+
+def test_stress_full_size_first_rounds(tt):
+    """Preset 5 at full size: the oracle cannot run all 4096 rounds of Algorithm 3 on a
+    100 000-op graph in reasonable time, so the first rounds of two samples are compared
+    (the oracle recomputes Algorithm 1 from scratch in each), plus permutation validity
+    and the simulation of a shared order on a few samples."""
+    d, h, dep = get(tt, "stress")
+    rows = [0, 4095]
+    op, rv = wl.sample_rows(d, rows)
+    print("[stress] GPU TAC on 2 samples", flush=True)
+    res = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True)
+    order = res[0].cpu().numpy()
+    assert np.array_equal(np.sort(order, axis=1), np.tile(np.arange(d.n_recv), (2, 1)))
+    print("[stress] oracle, first rounds", flush=True)
+    eo = oracle.tac(dep, d.recv_ids, op, rv, max_rounds=3)[0]
+    assert np.array_equal(order[:, :3], eo[:, :3])
+    print("[stress] simulate", flush=True)
+    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, order, op, rv)
+    got = [x.cpu().numpy() for x in tt.simulate(h, cuda(order), cuda(op), cuda(rv))]
+    for a, b in zip(got, exp):
+        assert np.array_equal(a, b)
+    assert np.array_equal(res[4].cpu().numpy(), exp[0])
+    tic_order = oracle.tic(dep, d.recv_ids)[1]
+    exp2 = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, tic_order, op, rv)
+    got2 = tt.simulate(h, cuda(tic_order), cuda(op), cuda(rv))
+    assert np.array_equal(got2[0].cpu().numpy(), exp2[0])
