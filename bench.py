@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole scheduling path on one MI355X.
+
+A step is one pass of the hot path over one batch of synthetic timing samples of the
+workload: dependency-bitset propagation (``tictac_build_deps``), TIC priorities
+(``tictac_tic_priority``), TAC orders for all B samples (``tictac_tac_priority``) and the
+simulation of every sample under its TAC order (``tictac_simulate``).  The timing arrays
+are resident in device memory before the timed region starts.
+
+Prints one JSON line: timing-sample schedules per second, the roofline record of the
+dominant kernel (TAC), the dependency-propagation bandwidth on the stress preset, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+
+def parse() -> argparse.Namespace:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="resnet50", choices=["tiny", "resnet50", "vgg16", "inception3", "stress"])
+    ap.add_argument("--batch", type=int, default=0, help="override B of the preset (0 = preset's)")
+    ap.add_argument("--cpu-samples", type=int, default=256, help="samples the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-deps-bench", action="store_true", help="skip the propagation timing on the stress preset")
+    return ap.parse_args()
+
+
+# peaks of MI355X used for the roofline records
+HBM_PEAK_GBS = 8000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6
+
+
+def tac_algorithmic_ops(nnz_ops: int, R: int, N: int) -> float:
+    """Operations per timing sample that the method itself needs in its incremental form:
+    one add per compute op (class totals), for every (op, recv) incidence one integer
+    decrement and one float64 subtract when that recv is removed, and four float64
+    operations (two min, two compares) per comparator step of the R(R+1)/2 steps of the
+    selection scans."""
+    return float(N + 2 * nnz_ops + 4 * (R * (R + 1) // 2))
+
+
+def main() -> int:
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (timing samples are independent and would shard "
+              "by sample with no collective); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1803_03288_amd import binding as tt, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tt.lib()
+
+    d = wl.preset(args.workload)
+    B = args.batch or d.batch
+    t0 = time.time()
+    op, rv = wl.timing_samples(d, 0, B)
+    gop, grv = torch.from_numpy(op).cuda(), torch.from_numpy(rv).cuda()
+    torch.cuda.synchronize()
+    print(f"[bench] workload {d.name}: N={d.n_compute} R={d.n_recv} E={d.n_edges} B={B}; "
+          f"inputs generated and uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    tac_ms, sim_ms = [], []
+
+    def step(record: bool):
+        h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+        tt.tic_priority(h)
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        order, rank, _, _ = tt.tac_priority(h, gop, grv, want_rank=True)
+        e1.record()
+        out = tt.simulate(h, order, gop, grv)
+        e2.record()
+        if record:
+            step.events.append((e0, e1, e2))
+        return h, out
+    step.events = []
+
+    for _ in range(args.warmup):
+        h, out = step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        h, out = step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for e0, e1, e2 in step.events:
+        tac_ms.append(e0.elapsed_time(e1))
+        sim_ms.append(e1.elapsed_time(e2))
+    ms_per_step = dt / args.steps * 1e3
+    value = B / (dt / args.steps)
+    mean_eff = float(out[1].mean())
+
+    # ---- roofline record of the dominant kernel (TAC), from the HIP events above ----
+    dep_gpu = h.deps().cpu().numpy().view(np.uint64)
+    nnz_ops = int(np.unpackbits(dep_gpu[d.compute_ids()].view(np.uint8), axis=1).sum())
+    tac_s = float(np.mean(tac_ms)) * 1e-3
+    ops_per_launch = tac_algorithmic_ops(nnz_ops, d.n_recv, d.n_compute) * B
+    achieved = ops_per_launch / tac_s / 1e12
+    roofline = {"kernel": "tac_kernel", "bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                "ms_per_launch": tac_s * 1e3,
+                "hbm_GBs": (8.0 * (d.n_compute + d.n_recv) + 8.0 * d.n_recv) * B / tac_s / 1e9}
+    sim_s = float(np.mean(sim_ms)) * 1e-3
+    simulate = {"ms_per_launch": sim_s * 1e3,
+                "hbm_GBs": (8.0 * (d.n_compute + d.n_recv) + 4.0 * d.n_recv + 16.0) * B / sim_s / 1e9}
+    simulate["frac_of_hbm_peak"] = simulate["hbm_GBs"] / HBM_PEAK_GBS
+
+    # ---- dependency-bitset propagation bandwidth on the stress preset ----
+    dep_bitset = None
+    if not args.no_deps_bench:
+        ds = wl.preset("stress")
+        hs = tt.build_deps(ds.n_ops, ds.row_ptr, ds.col_idx, ds.recv_ids)
+        times = []
+        for i in range(7):
+            a, b = ev(), ev()
+            a.record()
+            hs.recompute_deps()
+            b.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                times.append(a.elapsed_time(b))
+        k1_s = float(np.mean(times)) * 1e-3
+        alg_bytes = ds.n_ops * ds.words * 8 + 4 * (ds.n_ops + 1 + ds.n_edges)
+        dep_bitset = {"workload": "stress", "n_ops": ds.n_ops, "words": ds.words, "levels": hs.n_levels,
+                      "us_per_launch": k1_s * 1e6, "GB/s": alg_bytes / k1_s / 1e9,
+                      "frac_of_hbm_peak": alg_bytes / k1_s / 1e9 / HBM_PEAK_GBS}
+        hs.close()
+
+    # ---- the oracle on the host cores, bounded sample of the same workload ----
+    cpu = None
+    if args.cpu_samples > 0:
+        import oracle   # the CPU-baseline leg is the only user of the oracle here
+        k = min(args.cpu_samples, B)
+        t0 = time.perf_counter()
+        dep = oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+        oracle.tic(dep, d.recv_ids)
+        eo = oracle.tac(dep, d.recv_ids, op[:k], rv[:k])[0]
+        em = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op[:k], rv[:k])[0]
+        cdt = time.perf_counter() - t0
+        cpu = {"value": k / cdt, "unit": "schedules/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {k} of {B} samples of {d.name}: deps + TIC + TAC + simulate, {cdt:.1f}s"}
+        order_gpu = tt.tac_priority(h, gop[:k].contiguous(), grv[:k].contiguous())[0].cpu().numpy()
+        cpu["orders_match_gpu"] = bool(np.array_equal(order_gpu, eo))
+
+    line = {
+        "metric": "timing-sample schedules/sec (TAC+simulate) on 1 MI355X; dep-bitset HBM GB/s",
+        "value": value, "unit": "schedules/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{d.name} preset (seed {d.seed}): N={d.n_compute} compute ops, R={d.n_recv} recvs, "
+                               f"B={B} timing samples; step = build_deps + TIC + TAC + simulate"},
+        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "cpu_baseline": cpu,
+        "mean_scheduling_efficiency": mean_eff,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
