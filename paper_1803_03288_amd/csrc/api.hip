@@ -62,7 +62,7 @@ static void free_dag(Dag *d)
     if (!d) return;
     void *ptrs[] = {d->d_row_ptr, d->d_col_idx, d->d_recv_of_op, d->d_comp_col, d->d_lvl_ptr, d->d_lvl_ops,
                     d->d_dep, d->d_cls_dep, d->d_cls_depT, d->d_cls_cnt0, d->d_cls_ptr, d->d_cls_cols,
-                    d->d_work};
+                    d->d_run_ptr, d->d_run_lo, d->d_run_hi, d->d_cls_isum, d->d_work};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete d;
@@ -228,6 +228,29 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             depT[(size_t)w * d->Cpad + c] = x;
         }
     for (int32_t c = 0; c < d->C; ++c) d->cls_nnz += cnt0[c];
+    // runs of consecutive recv indices of every class row
+    std::vector<int32_t> run_ptr(1, 0), run_lo, run_hi;
+    for (int32_t c = 0; c < d->C; ++c) {
+        int32_t lo = -1;
+        for (int32_t i = 0; i <= d->R; ++i) {
+            const bool set = i < d->R && ((cls_dep[(size_t)c * d->W + (i >> 6)] >> (i & 63)) & 1ull);
+            if (set && lo < 0) lo = i;
+            if (!set && lo >= 0) { run_lo.push_back(lo); run_hi.push_back(i); lo = -1; }
+        }
+        run_ptr.push_back((int32_t)run_lo.size());
+    }
+    if (d->R <= 1024) {   // index sums stay below 2^20
+        std::vector<int32_t> isum(d->C, 0);
+        for (int32_t c = 0; c < d->C; ++c)
+            for (int32_t i = 0; i < d->R; ++i)
+                if ((cls_dep[(size_t)c * d->W + (i >> 6)] >> (i & 63)) & 1ull) isum[c] += i;
+        HIP_TRY(upload(&d->d_cls_isum, isum, s));
+    }
+    d->max_members = 0;
+    for (int32_t c = 0; c < d->C; ++c) d->max_members = std::max(d->max_members, cls_ptr[c + 1] - cls_ptr[c]);
+    HIP_TRY(upload(&d->d_run_ptr, run_ptr, s));
+    HIP_TRY(upload(&d->d_run_lo, run_lo, s));
+    HIP_TRY(upload(&d->d_run_hi, run_hi, s));
     HIP_TRY(upload(&d->d_cls_dep, cls_dep, s));
     HIP_TRY(upload(&d->d_cls_depT, depT, s));
     HIP_TRY(upload(&d->d_cls_cnt0, cnt0, s));

@@ -24,6 +24,31 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
+__device__ __forceinline__ double wave_max_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+    return v;
+}
+
+// inclusive prefix sum over the lanes of a wave
+__device__ __forceinline__ double wave_incl_scan_f64(double v)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double u = __shfl_up(v, off);
+        if (lane_id() >= off) v += u;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
 __device__ __forceinline__ int wave_min_i32(int v)
 {
 #pragma unroll

@@ -39,8 +39,14 @@ struct Dag {
     uint64_t *d_cls_dep = nullptr;  // [C][W]
     uint64_t *d_cls_depT = nullptr; // [W][Cpad]
     int32_t *d_cls_cnt0 = nullptr;  // [C]   |dep| of the class
+    int32_t *d_cls_isum = nullptr;  // [C]   sum of the recv indices in dep of the class (R <= 1024 only)
     int32_t *d_cls_ptr = nullptr;   // [C+1] members of class c: cls_cols[cls_ptr[c] .. cls_ptr[c+1])
     int32_t *d_cls_cols = nullptr;  // [N]   op_time columns, grouped by class
+    // every class row as runs of consecutive recv indices [lo, hi): row c = runs run_ptr[c] .. run_ptr[c+1])
+    int32_t *d_run_ptr = nullptr;   // [C+1]
+    int32_t *d_run_lo = nullptr;    // [n_runs]
+    int32_t *d_run_hi = nullptr;    // [n_runs]
+    int32_t max_members = 0;        // largest class (ops)
 
     // scratch owned by the handle (grown on demand, stream-ordered use)
     void *d_work = nullptr;
@@ -68,6 +74,10 @@ struct TacArgs {
     double *makespan, *eff, *U, *L, *S;
 };
 hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s);
+// register-resident variant for graphs with few classes; returns hipErrorNotSupported when
+// the graph does not fit it.  Samples it cannot order (a transfer time of zero) are marked
+// in flags[b] = 1 for the general kernel.
+hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t s);
 
 struct SimArgs {
     int32_t B;

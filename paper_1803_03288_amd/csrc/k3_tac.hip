@@ -45,6 +45,8 @@ struct TacKernelParams {
     // per-workgroup state in global memory (GSTATE kernels): ct, M [C] f64, Mp [R] f64, cnt [C] i32
     char *gstate;
     size_t gstate_stride;
+    // when not NULL, only the samples with only_flagged[b] != 0 are processed
+    const int32_t *only_flagged;
 };
 
 // M+ values of the literal path are produced by atomics of other threads; when they live
@@ -97,6 +99,7 @@ tac_kernel(const TacKernelParams p)
     }
 
     for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
+        if (p.only_flagged && p.only_flagged[b] == 0) continue;   // uniform over the workgroup
         const double *rt = p.recv_time + (size_t)b * R;
         const double *ot = p.op_time + (size_t)b * N;
         __syncthreads();   // previous sample's LDS fully consumed
@@ -382,6 +385,18 @@ hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s)
     p.order = a.order; p.rank = a.rank; p.sel_P = a.sel_P; p.sel_Mplus = a.sel_Mplus;
     p.simulate = a.simulate ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
+    p.only_flagged = nullptr;
+
+    // graphs with few classes: register-resident kernel, then the general kernel for the
+    // samples it flagged (those with a transfer time of zero)
+    if (!a.sel_P && !a.sel_Mplus && d.C <= 8 * 64 && d.W <= 6) {
+        hipError_t e = ensure_workspace(&d, (size_t)a.B * sizeof(int32_t));
+        if (e != hipSuccess) return e;
+        int32_t *flags = static_cast<int32_t *>(d.d_work);
+        e = launch_tac_reg(d, a, flags, s);
+        if (e == hipSuccess) p.only_flagged = flags;
+        else if (e != hipErrorNotSupported) return e;
+    }
 
     const size_t lds_small = tac_lds_bytes(d, false);
     if (lds_small <= 40 * 1024 && d.C <= 1024) {
