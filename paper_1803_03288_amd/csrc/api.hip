@@ -214,7 +214,8 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     }
     std::vector<uint64_t> cls_dep;
     std::vector<int32_t> cls_ptr, cls_cols;
-    const int32_t max_members = std::min(256, std::max(8, (d->N + 127) / 128));
+    // only classes far larger than a lane's fair share of the ops are split
+    const int32_t max_members = std::min(256, std::max(16, (d->N + 63) / 64));
     group_classes(rows, d->N, d->W, max_members, cls_dep, cls_ptr, cls_cols, d->C_distinct);
     d->C = (int32_t)cls_ptr.size() - 1;
     d->Cpad = (d->C + 63) / 64 * 64;

@@ -1,32 +1,34 @@
 // TAC (Sec. 4.3, Algorithm 3) with the iteration under its order (Sec. 3.2), one wavefront
-// per timing sample, for graphs whose classes fit the register file: lane l owns the
-// classes l, l + 64, ... (KT per lane) and keeps their dependency rows, outstanding
-// counts, M and class times in VGPRs for the whole selection loop.  The bitsets of
-// outstanding recvs and of Q = {outstanding recvs with P > 0} are wave-uniform values
-// (scalar registers); LDS holds the per-recv arrays (Time, P) and the order built so far.
-// Per round nothing is read from global memory.
+// per timing sample, for graphs with few classes (at most 8 per lane).  A workgroup is four
+// independent waves that share one read-only LDS copy of the class rows; lane l of a wave
+// owns the classes l, l + 64, ... and keeps their outstanding counts, M and class times in
+// VGPRs for the whole selection loop.  Per round nothing is read from global memory.
 //
-// The algorithm is the one described at the top of k3_tac.hip (incremental Algorithm 1,
-// selection by the scan over Q or by the minimum of M over classes with two or more
-// outstanding recvs).  Differences in how it is carried out:
-//   * the op_time row is staged into LDS by coalesced loads and the class totals are
-//     gathered from there;
-//   * M of a class is initialised from prefix sums T of the transfer times:
-//     sum over the runs [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo];
-//   * the outstanding count of a class and the sum of the indices of its outstanding
-//     recvs share one register; when the count reaches 1 the index sum *is* the last
-//     outstanding recv, to whose P the class time is added (LDS atomic issued by the
-//     owning lane; lanes of one instruction and successive instructions are served in a
-//     fixed order, so the result is reproducible).  Q gets that recv's bit when the class
-//     time is positive (P only grows while the recv is outstanding);
-//   * a class whose count reaches 0 after k transfers adds its time to A[k]; the makespan
-//     is formed after the loop as max_k (F_k + S_k), F_k the end of the k-th transfer,
-//     S_k = A[k] + A[k+1] + ...  (the closed form of the work-conserving device described
-//     in k4_simulate.hip);
-//   * blocks of 64 classes whose counts are all 0 are skipped (classes are numbered by
-//     their first op, so on layered models they finish roughly in order);
+// The algorithm is the one described at the top of k3_tac.hip (incremental Algorithm 1;
+// selection by the scan over Q = {outstanding recvs with P > 0}, or by the minimum of M over
+// classes with two or more outstanding recvs when Q is empty).  How it is carried out here:
+//   * a round is instruction-bound, so it is kept short: the row bits of the selected recv
+//     come from one LDS read per lane, the per-class update is branch-free, and whatever is
+//     wave-uniform stays in scalar registers;
+//   * one register per class holds (count - 2) << 20 | sum of the indices of its outstanding
+//     recvs.  It goes negative when the count falls below 2 (the only moments at which
+//     anything else has to happen), and once the count is 1 the index sum *is* the last
+//     outstanding recv of the class, to whose P the class time is then added;
+//   * Q is tracked by its size and the sum of its members (one member: the sum is the
+//     member, the common case on layered models), next to a bitset used by the scan when it
+//     has several;
+//   * M of a class is initialised from prefix sums T of the transfer times: the sum over the
+//     runs [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo];
+//   * the step at which a class's count reaches 0 is its release position kappa; after the
+//     loop the class times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
+//     the end of the k-th transfer, S_k the time of the classes with kappa >= k (the closed
+//     form of the work-conserving device described in k4_simulate.hip);
+//   * blocks of 64 classes whose counts are all 0 are skipped (classes are numbered by their
+//     first op, so on layered models they finish roughly in order);
 //   * a sample with a transfer time of zero is not handled here: it is flagged for the
 //     general kernel, which takes the literal path for it.
+// LDS atomics of one wave are served in issue order and lane order, so the sums they form
+// are reproducible from run to run.
 #include <type_traits>
 
 #include "device_utils.h"
@@ -48,85 +50,85 @@ struct TacRegParams {
     int32_t simulate;
     double *makespan, *eff, *U, *L, *S;
     int32_t *flags;             // [B] 1 = left to the general kernel
-    int32_t xlen;               // doubles in the staging / simulation region of LDS
+    int32_t wave_doubles;       // LDS doubles per wave
+    int32_t n_waves;            // total waves of the grid
 };
 
-// calls f(std::integral_constant<int, i>) for the i in [I, IN) equal to the (wave-uniform) index
-template <int I, int IN, class F>
-__device__ __forceinline__ void dispatch_index(int idx, F &&f)
+constexpr int kRegWaves = 4;           // waves per workgroup
+constexpr int CNT1 = 1 << 20;          // one unit of the outstanding count in `packed`
+constexpr int IDX_MASK = CNT1 - 1;
+
+// ordering point for LDS traffic between the lanes of one wave (LDS operations of a wave
+// complete in issue order; this only keeps the compiler from moving them across)
+__device__ __forceinline__ void wave_sync()
 {
-    if constexpr (I < IN) {
-        if (idx == I) f(std::integral_constant<int, I>{});
-        else dispatch_index<I + 1, IN>(idx, f);
-    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int WT>
-__device__ __forceinline__ int first_alive(const uint32_t (&row)[2 * WT], const uint64_t (&alive)[WT])
+// lowest outstanding recv of class (lane, k); rows: [2W][64][KT] halves, alive: [2W] halves in LDS
+template <int KT>
+__device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t *alive, int W, int lane, int k)
 {
-    int r = INT32_MAX;
-#pragma unroll
-    for (int j = WT - 1; j >= 0; --j) {
-        const uint64_t x = (((uint64_t)row[2 * j + 1] << 32) | row[2 * j]) & alive[j];
-        if (x) r = j * 64 + __builtin_ctzll(x);
+    for (int h = 0; h < 2 * W; ++h) {
+        const uint32_t x = rows[(h * 64 + lane) * KT + k] & alive[h];
+        if (x) return h * 32 + __builtin_ctz(x);
     }
-    return r;
+    return INT32_MAX;
 }
 
-// does the row hold recv q?  (AND with a one-hot mask per word: no element of the register
-// array is selected by a run-time index)
-template <int WT>
-__device__ __forceinline__ bool row_has(const uint32_t (&row)[2 * WT], int q)
-{
-    uint32_t acc = 0;
-#pragma unroll
-    for (int j = 0; j < 2 * WT; ++j) {
-        const uint32_t mask = ((q >> 5) == j) ? (1u << (q & 31)) : 0u;
-        acc |= row[j] & mask;
-    }
-    return acc != 0;
-}
-
-template <int KT, int WT, bool STAGE>
-__global__ void __launch_bounds__(64)
+template <int KT, bool STAGE>
+__global__ void __launch_bounds__(64 * kRegWaves)
 tac_reg_kernel(const TacRegParams p)
 {
     extern __shared__ double smem[];
     const int R = p.R, W = p.W, C = p.C, N = p.N;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    double *t = smem;                       // [R]    Time(recv)
+    // ---- LDS: class rows shared by the workgroup, then one private region per wave ----
+    uint32_t *rows = reinterpret_cast<uint32_t *>(smem);            // [2W][64][KT]
+    const int rows_doubles = (2 * W * 64 * KT + 1) / 2;
+    double *mine = smem + rows_doubles + (size_t)wave * p.wave_doubles;
+    double *t = mine;                       // [R]    Time(recv) (rare paths only)
     double *P = t + R;                      // [R+1]  P; before the loop: prefix sums T
-    double *X = P + (R + 1);                // [xlen] op_time row, later A [R+1] and F [R+1]
-    int32_t *ordl = reinterpret_cast<int32_t *>(X + p.xlen);                     // [R]
-    double *A = X, *Fs = X + (R + 1);
+    double *A = P + (R + 1);                // [R+1]  class time by release position
+    int32_t *ordl = reinterpret_cast<int32_t *>(A + (R + 1));       // [R] order built so far
+    uint32_t *aliveh = reinterpret_cast<uint32_t *>(ordl + R);      // [2W] outstanding recvs
+    uint32_t *Qh = aliveh + 2 * W;                                  // [2W] Q
+    double *X = reinterpret_cast<double *>(Qh + 2 * W + ((R + 4 * W) & 1));   // [N] op_time row (STAGE)
 
-    // ---- per-lane tables, the same for every sample ----
-    // packed0 = (|row| << 20) + sum of the recv indices of the row.  The running value
-    // `packed` loses (1 << 20) + r when recv r of the row is removed, so its upper bits are
-    // the outstanding count and, once that count is 1, its lower 20 bits are the index of
-    // the last outstanding recv of the class.
-    constexpr int CNT1 = 1 << 20;
-    uint32_t row[KT][2 * WT];
-    int packed0[KT];
+    for (int idx = threadIdx.x; idx < 2 * W * 64 * KT; idx += blockDim.x) {
+        const int h = idx / (64 * KT), rem = idx % (64 * KT);
+        const int l = rem / KT, k = rem % KT;
+        const int c = k * 64 + l;
+        const uint64_t x = c < C ? p.cls_dep[(size_t)c * W + (h >> 1)] : 0ull;
+        rows[idx] = (h & 1) ? (uint32_t)(x >> 32) : (uint32_t)x;
+    }
+    __syncthreads();                        // the only workgroup barrier
+
+    // ---- per-lane constants ----
+    int packed0[KT], mbeg[KT], mcnt[KT];
+    int mmax[KT];                           // wave-uniform bounds of the member loops
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
         const int c = k * 64 + lane;
+        packed0[k] = c < C ? (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c] : -2 * CNT1;
+        mbeg[k] = c < C ? p.cls_ptr[c] : 0;
+        mcnt[k] = c < C ? p.cls_ptr[c + 1] - mbeg[k] : 0;
+        int mx = mcnt[k];
 #pragma unroll
-        for (int j = 0; j < WT; ++j) {
-            const uint64_t x = (c < C && j < W) ? p.cls_dep[(size_t)c * W + j] : 0ull;
-            row[k][2 * j] = (uint32_t)x;
-            row[k][2 * j + 1] = (uint32_t)(x >> 32);
-        }
-        packed0[k] = c < C ? p.cls_cnt0[c] * CNT1 + p.cls_isum[c] : 0;
+        for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
+        mmax[k] = __builtin_amdgcn_readfirstlane(mx);
     }
 
-    for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
+    const int gwave = blockIdx.x * kRegWaves + wave;
+    for (int b = gwave; b < p.B; b += p.n_waves) {
         const double *rt = p.recv_time + (size_t)b * R;
         const double *ot = p.op_time + (size_t)b * N;
-        __syncthreads();                    // LDS of the previous sample is no longer read
+        wave_sync();                        // LDS of the previous sample is no longer read
 
-        // ---- a. transfer times, their prefix sums, and the op_time row ----
+        // ---- a. transfer times, their prefix sums T (in P), the op_time row ----
         bool zero_seen = false;
         double carry = 0.0;
         for (int base = 0; base < R; base += 64) {
@@ -143,92 +145,98 @@ tac_reg_kernel(const TacRegParams p)
         if (skip) continue;
         if (STAGE)
             for (int j = lane; j < N; j += 64) X[j] = ot[j];
-        __syncthreads();
+        wave_sync();
 
         // ---- b. class totals and initial M ----
         double ct[KT], M[KT];
-        int packed[KT];
+        int packed[KT], kap[KT];
         double ct_sum = 0.0;
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
             const int c = k * 64 + lane;
             double s = 0.0, Mk = 0.0;
+#pragma unroll 4
+            for (int m = 0; m < mmax[k]; ++m)
+                if (m < mcnt[k]) {
+                    const int col = p.cls_cols[mbeg[k] + m];
+                    s += STAGE ? X[col] : ot[col];
+                }
             if (c < C) {
-                const int mend = p.cls_ptr[c + 1], rend = p.run_ptr[c + 1];
-                for (int m = p.cls_ptr[c]; m < mend; ++m) s += STAGE ? X[p.cls_cols[m]] : ot[p.cls_cols[m]];
+                const int rend = p.run_ptr[c + 1];
                 for (int q = p.run_ptr[c]; q < rend; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]];
             }
-            ct[k] = s; M[k] = Mk; packed[k] = packed0[k];
+            ct[k] = s; M[k] = Mk; packed[k] = packed0[k]; kap[k] = 0;
             ct_sum += s;
         }
-        __syncthreads();                    // T and the staged row are consumed
+        wave_sync();                        // T and the staged row are consumed
 
-        // ---- c. P, A; the wave-uniform bitsets of outstanding recvs and of Q ----
+        // ---- c. P, A, the bitsets of outstanding recvs and of Q ----
         for (int r = lane; r < R; r += 64) P[r] = 0.0;
         if (p.simulate)
             for (int j = lane; j <= R; j += 64) A[j] = 0.0;
-        if (p.simulate && lane == 0) Fs[0] = 0.0;
-        uint64_t alive[WT], Q[WT];
-#pragma unroll
-        for (int j = 0; j < WT; ++j) {
-            const int nbits = R - j * 64;
-            alive[j] = nbits >= 64 ? ~0ull : (nbits > 0 ? ((1ull << nbits) - 1ull) : 0ull);
-            Q[j] = 0ull;
+        if (lane < 2 * W) {
+            const int nb = R - lane * 32;
+            aliveh[lane] = nb >= 32 ? ~0u : (nb > 0 ? ((1u << nb) - 1u) : 0u);
+            Qh[lane] = 0u;
         }
-        __syncthreads();
+        wave_sync();
         uint32_t live = 0;                  // bit k: some class of block k still has outstanding recvs
+        int qcount = 0, qsum = 0;           // size of Q and sum of its members
 #pragma unroll
         for (int k = 0; k < KT; ++k) {
-            const bool one = (unsigned)(packed[k] - CNT1) < (unsigned)CNT1;      // count == 1
-            if (one) atomicAdd(&P[packed[k] & (CNT1 - 1)], ct[k]);
+            const bool one = packed[k] < 0 && packed[k] >= -CNT1;        // count == 1
+            if (one) atomicAdd(&P[packed[k] & IDX_MASK], ct[k]);
             uint64_t qm = __ballot(one && ct[k] > 0.0);
             while (qm) {
                 const int l = __builtin_ctzll(qm);
                 qm &= qm - 1;
-                const int sole = __builtin_amdgcn_readlane(packed[k], l) & (CNT1 - 1);
-#pragma unroll
-                for (int j = 0; j < WT; ++j)
-                    if (j == (sole >> 6)) Q[j] |= 1ull << (sole & 63);
+                const int sole = __builtin_amdgcn_readlane(packed[k], l) & IDX_MASK;
+                const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);
+                const uint32_t bit = 1u << (sole & 31);
+                if (!(old & bit)) { qcount += 1; qsum += sole; }
+                if (lane == 0) Qh[sole >> 5] = old | bit;
+                wave_sync();
             }
-            if (p.simulate && packed[k] < CNT1 && k * 64 + lane < C) atomicAdd(&A[0], ct[k]);
-            if (__ballot(packed[k] >= CNT1)) live |= 1u << k;
+            if (__ballot(packed[k] >= -CNT1)) live |= 1u << k;
         }
 
         // ---- d. selection loop ----
         double F = 0.0;
         for (int step = 0; step < R; ++step) {
-            int nq = 0;
-#pragma unroll
-            for (int j = 0; j < WT; ++j) nq += __builtin_popcountll(Q[j]);
-            int best = INT32_MAX;
-            if (nq == 1) {
-#pragma unroll
-                for (int j = WT - 1; j >= 0; --j)
-                    if (Q[j]) best = j * 64 + __builtin_ctzll(Q[j]);
-            } else if (nq == 0) {
+            int best;
+            const bool from_q = qcount > 0;
+            if (qcount == 1) {
+                best = qsum;
+            } else if (qcount == 0) {
                 // every outstanding recv has P = 0: lowest index among those of minimal M+
                 double lmin = TT_INF;
 #pragma unroll
                 for (int k = 0; k < KT; ++k)
-                    if (packed[k] >= 2 * CNT1) lmin = fmin(lmin, M[k]);
+                    if (packed[k] >= 0) lmin = fmin(lmin, M[k]);
                 const double g = wave_min_f64(lmin);
                 int cand = INT32_MAX;
                 if (g != TT_INF) {
 #pragma unroll
                     for (int k = 0; k < KT; ++k)
-                        if (packed[k] >= 2 * CNT1 && M[k] == g) cand = min(cand, first_alive<WT>(row[k], alive));
+                        if (packed[k] >= 0 && M[k] == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k));
                 }
                 best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
+                best = __builtin_amdgcn_readfirstlane(best);
+                if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
+                    for (int h = 2 * W - 1; h >= 0; --h) {
+                        const uint32_t x = aliveh[h];
+                        if (x) best = h * 32 + __builtin_ctz(x);
+                    }
+                    best = __builtin_amdgcn_readfirstlane(best);
+                }
             } else {
                 // ascending scan over Q with the comparator
                 double mp_best = -1.0;
                 best = -1;
-                __syncthreads();                      // P of this round is complete
-#pragma unroll
-                for (int j = 0; j < WT; ++j) {
-                    uint64_t x = Q[j];
+                for (int h = 0; h < 2 * W; ++h) {
+                    uint32_t x = __builtin_amdgcn_readfirstlane(Qh[h]);
                     while (x) {
-                        const int a = j * 64 + __builtin_ctzll(x);
+                        const int a = h * 32 + __builtin_ctz(x);
                         x &= x - 1;
                         if (best < 0) { best = a; continue; }
                         const double xa = fmin(P[best], t[a]);
@@ -241,8 +249,10 @@ tac_reg_kernel(const TacRegParams p)
                             double v = TT_INF, u = TT_INF;
 #pragma unroll
                             for (int k = 0; k < KT; ++k) {
-                                if (packed[k] >= 2 * CNT1 && row_has<WT>(row[k], a)) v = fmin(v, M[k]);
-                                if (packed[k] >= 2 * CNT1 && row_has<WT>(row[k], best)) u = fmin(u, M[k]);
+                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);
+                                const uint32_t rb = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31);
+                                if (packed[k] >= 0 && (ra & 1u)) v = fmin(v, M[k]);
+                                if (packed[k] >= 0 && (rb & 1u)) u = fmin(u, M[k]);
                             }
                             mp_a = wave_min_f64(v);
                             if (mp_best < 0.0) mp_best = wave_min_f64(u);
@@ -251,60 +261,61 @@ tac_reg_kernel(const TacRegParams p)
                         if (prec) { best = a; mp_best = mp_a; }
                     }
                 }
-            }
-            best = __builtin_amdgcn_readfirstlane(best);
-            if ((unsigned)best >= (unsigned)R) {      // no M+ exists: the lowest outstanding recv
-#pragma unroll
-                for (int j = WT - 1; j >= 0; --j)
-                    if (alive[j]) best = j * 64 + __builtin_ctzll(alive[j]);
+                best = __builtin_amdgcn_readfirstlane(best);
             }
             const double tb = t[best];
             F += tb;
-            const int bw = best >> 6;
-            const uint64_t bbit = 1ull << (best & 63);
-#pragma unroll
-            for (int j = 0; j < WT; ++j)
-                if (j == bw) { alive[j] &= ~bbit; Q[j] &= ~bbit; }
+            const int bh = best >> 5;
+            const uint32_t bbit = 1u << (best & 31);
             if (lane == 0) {
                 ordl[step] = best;
-                if (p.simulate) Fs[step + 1] = F;
+                aliveh[bh] &= ~bbit;
+                if (from_q) Qh[bh] &= ~bbit;
             }
+            if (from_q) { qcount -= 1; qsum -= best; }
 
-            // ---- incremental property update ----
+            // ---- incremental property update (branch-free per class) ----
+            const uint32_t *rb = rows + (bh * 64 + lane) * KT;
             const int sh = best & 31;
             const int delta = CNT1 + best;
             const long long tb_bits = __double_as_longlong(tb);
-            dispatch_index<0, 2 * WT>(best >> 5, [&](auto hc) {      // wave-uniform branch on the word half
-                constexpr int hh = decltype(hc)::value;
+            int mask[KT];
+            int evacc = 0;
 #pragma unroll
-                for (int k = 0; k < KT; ++k) {
-                    if (!(live & (1u << k))) continue;               // wave-uniform
-                    const int mask = __builtin_amdgcn_sbfe(row[k][hh], sh, 1);     // 0 or -1
-                    packed[k] += __mul24(mask, delta);
-                    M[k] -= __longlong_as_double(tb_bits & (long long)mask);
-                    const bool ev = mask != 0 && (unsigned)packed[k] < (unsigned)(2 * CNT1);
-                    if (__ballot(ev)) {
-                        const bool hit0 = ev && packed[k] < CNT1;
-                        const bool hit1 = ev && !hit0;
-                        if (hit1) atomicAdd(&P[packed[k] & (CNT1 - 1)], ct[k]);
-                        uint64_t qm = __ballot(hit1 && ct[k] > 0.0);
-                        while (qm) {
-                            const int l = __builtin_ctzll(qm);
-                            qm &= qm - 1;
-                            const int sole = __builtin_amdgcn_readlane(packed[k], l) & (CNT1 - 1);
+            for (int k = 0; k < KT; ++k) {
+                if (!(live & (1u << k))) { mask[k] = 0; continue; }      // wave-uniform
+                mask[k] = __builtin_amdgcn_sbfe(rb[k], sh, 1);            // 0 or -1
+                packed[k] -= mask[k] & delta;
+                M[k] -= __longlong_as_double(tb_bits & (long long)mask[k]);
+                evacc |= packed[k] & mask[k];                             // negative: count fell to 1 or 0
+            }
+            if (__ballot(evacc < 0) == 0ull) continue;
+
+            // ---- some class fell to one outstanding recv, or to none ----
+            wave_sync();
 #pragma unroll
-                            for (int j = 0; j < WT; ++j)
-                                if (j == (sole >> 6)) Q[j] |= 1ull << (sole & 63);
-                        }
-                        if (__ballot(hit0)) {
-                            if (p.simulate && hit0) atomicAdd(&A[step + 1], ct[k]);
-                            if (__ballot(packed[k] >= CNT1) == 0ull) live &= ~(1u << k);
-                        }
-                    }
+            for (int k = 0; k < KT; ++k) {
+                const bool ev = (packed[k] & mask[k]) < 0;
+                if (__ballot(ev) == 0ull) continue;
+                const bool hit0 = ev && packed[k] < -CNT1;
+                const bool hit1 = ev && !hit0;
+                if (hit1) atomicAdd(&P[packed[k] & IDX_MASK], ct[k]);
+                kap[k] = hit0 ? step + 1 : kap[k];
+                uint64_t qm = __ballot(hit1 && ct[k] > 0.0);
+                while (qm) {
+                    const int l = __builtin_ctzll(qm);
+                    qm &= qm - 1;
+                    const int sole = __builtin_amdgcn_readlane(packed[k], l) & IDX_MASK;
+                    const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);
+                    const uint32_t bit = 1u << (sole & 31);
+                    if (!(old & bit)) { qcount += 1; qsum += sole; }
+                    if (lane == 0) Qh[sole >> 5] = old | bit;
+                    wave_sync();
                 }
-            });
+                if (__ballot(hit0) != 0ull && __ballot(packed[k] >= -CNT1) == 0ull) live &= ~(1u << k);
+            }
         }
-        __syncthreads();
+        wave_sync();
 
         // ---- e. outputs ----
         for (int s = lane; s < R; s += 64) {
@@ -313,17 +324,32 @@ tac_reg_kernel(const TacRegParams p)
             if (p.rank) p.rank[(size_t)b * R + r] = s;
         }
         if (p.simulate) {
-            // makespan = max over k of F_k + (time of the classes released after k or more transfers)
-            double sfx = 0.0, mloc = 0.0;
-            for (int base = (R / 64) * 64; base >= 0; base -= 64) {
-                const int j = base + 63 - lane;              // descending index along the lanes
-                const double x = j <= R ? A[j] : 0.0;
-                const double inc = wave_incl_scan_f64(x);    // sum of A over indices >= j of this chunk
-                if (j <= R) mloc = fmax(mloc, Fs[j] + (sfx + inc));
-                sfx += __shfl(inc, 63);
+            // A[k] = time of the classes released after k transfers; F_k = end of the k-th transfer;
+            // makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
+#pragma unroll
+            for (int k = 0; k < KT; ++k)
+                if (k * 64 + lane < C) atomicAdd(&A[kap[k]], ct[k]);
+            // F_k into P[k - 1] (P is free now): prefix sums of the transfer times in TAC order
+            double fc = 0.0;
+            for (int base = 0; base < R; base += 64) {
+                const int s = base + lane;
+                const double x = s < R ? t[ordl[s]] : 0.0;
+                const double inc = wave_incl_scan_f64(x);
+                if (s < R) P[s] = fc + inc;
+                fc += __shfl(inc, 63);
+            }
+            wave_sync();
+            const double sum_c = wave_sum_f64(ct_sum);
+            double sfx = 0.0, mloc = sum_c;               // k = 0: F_0 + S_0 = all class time
+            for (int base = ((R - 1) / 64) * 64; base >= 0; base -= 64) {
+                const int k = base + lane + 1;            // 1 <= k <= R handled here
+                const double x = k <= R ? A[k] : 0.0;
+                const double inc = wave_incl_scan_f64(x);
+                const double tot = __shfl(inc, 63);
+                if (k <= R) mloc = fmax(mloc, P[k - 1] + (sfx + (tot - inc + x)));
+                sfx += tot;
             }
             const double m = wave_max_f64(mloc);
-            const double sum_c = wave_sum_f64(ct_sum);
             if (lane == 0) {
                 const double U = sum_c + F;
                 const double L = fmax(sum_c, F);
@@ -337,29 +363,54 @@ tac_reg_kernel(const TacRegParams p)
     }
 }
 
-template <int KT, int WT>
-static hipError_t launch_reg_t(const TacRegParams &p, bool stage, int grid, size_t lds, hipStream_t s)
-{
-    if (stage)
-        hipLaunchKernelGGL((tac_reg_kernel<KT, WT, true>), dim3(grid), dim3(64), lds, s, p);
-    else
-        hipLaunchKernelGGL((tac_reg_kernel<KT, WT, false>), dim3(grid), dim3(64), lds, s, p);
-    return hipGetLastError();
-}
-
 template <int KT>
-static hipError_t launch_reg_k(const TacRegParams &p, int W, bool stage, int grid, size_t lds, hipStream_t s)
+static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
 {
-    if (W <= 1) return launch_reg_t<KT, 1>(p, stage, grid, lds, s);
-    if (W <= 2) return launch_reg_t<KT, 2>(p, stage, grid, lds, s);
-    if (W <= 3) return launch_reg_t<KT, 3>(p, stage, grid, lds, s);
-    if (W <= 4) return launch_reg_t<KT, 4>(p, stage, grid, lds, s);
-    return launch_reg_t<KT, 6>(p, stage, grid, lds, s);
+    // LDS: shared rows + per wave t [R], P [R+1], A [R+1], ordl [R] i32, two bitsets [2W] u32, row [N]
+    const size_t rows_doubles = ((size_t)2 * d.W * 64 * KT + 1) / 2;
+    const size_t wave_fixed = (size_t)d.R + 2 * (d.R + 1) + ((size_t)d.R + 4 * d.W + 1) / 2 + 1;
+    size_t per_wave = wave_fixed + d.N;
+    bool stage = true;
+    auto lds_of = [&](size_t pw) { return (rows_doubles + pw * kRegWaves) * 8; };
+    // stage the op_time row only while six workgroups (24 waves) still fit a compute unit
+    if (lds_of(per_wave) > (160 * 1024) / 6) { stage = false; per_wave = wave_fixed; }
+    const size_t lds = lds_of(per_wave);
+    if (lds > 80 * 1024) return hipErrorNotSupported;
+    p.wave_doubles = (int32_t)per_wave;
+    int per_cu = 0;
+    hipError_t e;
+    if (lds > 48 * 1024) {
+        e = stage ? hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                  : hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT, false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (stage)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT, true>, 64 * kRegWaves, lds);
+    else
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT, false>, 64 * kRegWaves, lds);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
+    int n_cu = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
+        n_cu = prop.multiProcessorCount;
+    int grid = per_cu * n_cu;                       // one resident set of workgroups, no tail
+    const int need = (p.B + kRegWaves - 1) / kRegWaves;
+    if (grid > need) grid = need;
+    p.n_waves = grid * kRegWaves;
+    if (stage)
+        hipLaunchKernelGGL((tac_reg_kernel<KT, true>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
+    else
+        hipLaunchKernelGGL((tac_reg_kernel<KT, false>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t s)
 {
-    if (d.R == 0 || d.W > 6 || d.C > 8 * 64 || a.sel_P || a.sel_Mplus) return hipErrorNotSupported;
+    if (d.R == 0 || d.R > 1024 || d.C > 8 * 64 || a.sel_P || a.sel_Mplus || !d.d_cls_isum)
+        return hipErrorNotSupported;
     TacRegParams p{};
     p.B = a.B; p.R = d.R; p.W = d.W; p.C = d.C; p.N = d.N;
     p.cls_dep = d.d_cls_dep; p.cls_cnt0 = d.d_cls_cnt0; p.cls_isum = d.d_cls_isum;
@@ -370,17 +421,13 @@ hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t 
     p.simulate = a.simulate ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
     p.flags = flags;
-    const bool stage = (size_t)d.N * 8 <= 16 * 1024;
-    const int sim_len = a.simulate ? 2 * (d.R + 1) : 0;
-    p.xlen = std::max(stage ? d.N : 0, sim_len);
-    const size_t lds = ((size_t)d.R + (d.R + 1) + p.xlen) * 8 + (size_t)d.R * 4;
-    if (lds > 60 * 1024) return hipErrorNotSupported;
-    const int grid = a.B < 256 * 16 ? a.B : 256 * 16;
     const int K = (d.C + 63) / 64;
-    if (K <= 1) return launch_reg_k<1>(p, d.W, stage, grid, lds, s);
-    if (K <= 2) return launch_reg_k<2>(p, d.W, stage, grid, lds, s);
-    if (K <= 4) return launch_reg_k<4>(p, d.W, stage, grid, lds, s);
-    return launch_reg_k<8>(p, d.W, stage, grid, lds, s);
+    if (K <= 1) return launch_reg_k<1>(p, d, s);
+    if (K <= 2) return launch_reg_k<2>(p, d, s);
+    if (K <= 3) return launch_reg_k<3>(p, d, s);
+    if (K <= 4) return launch_reg_k<4>(p, d, s);
+    if (K <= 6) return launch_reg_k<6>(p, d, s);
+    return launch_reg_k<8>(p, d, s);
 }
 
 }  // namespace tictac
