@@ -23,8 +23,6 @@
 //     loop the class times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
 //     the end of the k-th transfer, S_k the time of the classes with kappa >= k (the closed
 //     form of the work-conserving device described in k4_simulate.hip);
-//   * blocks of 64 classes whose counts are all 0 are skipped (classes are numbered by their
-//     first op, so on layered models they finish roughly in order);
 //   * a sample with a transfer time of zero is not handled here: it is flagged for the
 //     general kernel, which takes the literal path for it.
 // LDS atomics of one wave are served in issue order and lane order, so the sums they form
@@ -78,6 +76,11 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
     return INT32_MAX;
 }
 
+// The per-class state is kept in individually named scalars (not arrays), so that every
+// class stays in its own registers across the branches of the loop.  K(F) applies F to the
+// class slots 0..7; a slot beyond KT compiles to nothing.
+#define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
+
 template <int KT, bool STAGE>
 __global__ void __launch_bounds__(64 * kRegWaves)
 tac_reg_kernel(const TacRegParams p)
@@ -90,7 +93,7 @@ tac_reg_kernel(const TacRegParams p)
     uint32_t *rows = reinterpret_cast<uint32_t *>(smem);            // [2W][64][KT]
     const int rows_doubles = (2 * W * 64 * KT + 1) / 2;
     double *mine = smem + rows_doubles + (size_t)wave * p.wave_doubles;
-    double *t = mine;                       // [R]    Time(recv) (rare paths only)
+    double *t = mine;                       // [R]    Time(recv)
     double *P = t + R;                      // [R+1]  P; before the loop: prefix sums T
     double *A = P + (R + 1);                // [R+1]  class time by release position
     int32_t *ordl = reinterpret_cast<int32_t *>(A + (R + 1));       // [R] order built so far
@@ -107,20 +110,24 @@ tac_reg_kernel(const TacRegParams p)
     }
     __syncthreads();                        // the only workgroup barrier
 
-    // ---- per-lane constants ----
-    int packed0[KT], mbeg[KT], mcnt[KT];
-    int mmax[KT];                           // wave-uniform bounds of the member loops
-#pragma unroll
-    for (int k = 0; k < KT; ++k) {
-        const int c = k * 64 + lane;
-        packed0[k] = c < C ? (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c] : -2 * CNT1;
-        mbeg[k] = c < C ? p.cls_ptr[c] : 0;
-        mcnt[k] = c < C ? p.cls_ptr[c + 1] - mbeg[k] : 0;
-        int mx = mcnt[k];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));
-        mmax[k] = __builtin_amdgcn_readfirstlane(mx);
+    // ---- per-lane constants of the class slots ----
+#define TT_DECL_CONST(k) int pk0_##k = -2 * CNT1, mbeg_##k = 0, mcnt_##k = 0, mmax_##k = 0, rbeg_##k = 0, rend_##k = 0;
+    TT_EACH_K(TT_DECL_CONST)
+#define TT_INIT_CONST(k)                                                                  \
+    if constexpr (k < KT) {                                                               \
+        const int c = k * 64 + lane;                                                      \
+        if (c < C) {                                                                      \
+            pk0_##k = (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c];                         \
+            mbeg_##k = p.cls_ptr[c];                                                      \
+            mcnt_##k = p.cls_ptr[c + 1] - mbeg_##k;                                       \
+            rbeg_##k = p.run_ptr[c];                                                      \
+            rend_##k = p.run_ptr[c + 1];                                                  \
+        }                                                                                 \
+        int mx = mcnt_##k;                                                                \
+        for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));         \
+        mmax_##k = __builtin_amdgcn_readfirstlane(mx);                                    \
     }
+    TT_EACH_K(TT_INIT_CONST)
 
     const int gwave = blockIdx.x * kRegWaves + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
@@ -148,26 +155,23 @@ tac_reg_kernel(const TacRegParams p)
         wave_sync();
 
         // ---- b. class totals and initial M ----
-        double ct[KT], M[KT];
-        int packed[KT], kap[KT];
+#define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, kap_##k = 0, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
+        TT_EACH_K(TT_DECL_STATE)
         double ct_sum = 0.0;
-#pragma unroll
-        for (int k = 0; k < KT; ++k) {
-            const int c = k * 64 + lane;
-            double s = 0.0, Mk = 0.0;
-#pragma unroll 4
-            for (int m = 0; m < mmax[k]; ++m)
-                if (m < mcnt[k]) {
-                    const int col = p.cls_cols[mbeg[k] + m];
-                    s += STAGE ? X[col] : ot[col];
-                }
-            if (c < C) {
-                const int rend = p.run_ptr[c + 1];
-                for (int q = p.run_ptr[c]; q < rend; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]];
-            }
-            ct[k] = s; M[k] = Mk; packed[k] = packed0[k]; kap[k] = 0;
-            ct_sum += s;
+#define TT_INIT_STATE(k)                                                                  \
+        if constexpr (k < KT) {                                                           \
+            double s = 0.0, Mk = 0.0;                                                     \
+            _Pragma("unroll 4")                                                           \
+            for (int m = 0; m < mmax_##k; ++m)                                            \
+                if (m < mcnt_##k) {                                                       \
+                    const int col = p.cls_cols[mbeg_##k + m];                             \
+                    s += STAGE ? X[col] : ot[col];                                        \
+                }                                                                         \
+            for (int q = rbeg_##k; q < rend_##k; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]]; \
+            ct_##k = s; M_##k = Mk; pk_##k = pk0_##k;                                     \
+            ct_sum += s;                                                                  \
         }
+        TT_EACH_K(TT_INIT_STATE)
         wave_sync();                        // T and the staged row are consumed
 
         // ---- c. P, A, the bitsets of outstanding recvs and of Q ----
@@ -180,29 +184,37 @@ tac_reg_kernel(const TacRegParams p)
             Qh[lane] = 0u;
         }
         wave_sync();
-        uint32_t live = 0;                  // bit k: some class of block k still has outstanding recvs
-        int qcount = 0, qsum = 0;           // size of Q and sum of its members
-#pragma unroll
-        for (int k = 0; k < KT; ++k) {
-            const bool one = packed[k] < 0 && packed[k] >= -CNT1;        // count == 1
-            if (one) atomicAdd(&P[packed[k] & IDX_MASK], ct[k]);
-            uint64_t qm = __ballot(one && ct[k] > 0.0);
-            while (qm) {
-                const int l = __builtin_ctzll(qm);
-                qm &= qm - 1;
-                const int sole = __builtin_amdgcn_readlane(packed[k], l) & IDX_MASK;
-                const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);
-                const uint32_t bit = 1u << (sole & 31);
-                if (!(old & bit)) { qcount += 1; qsum += sole; }
-                if (lane == 0) Qh[sole >> 5] = old | bit;
-                wave_sync();
-            }
-            if (__ballot(packed[k] >= -CNT1)) live |= 1u << k;
+        int qcount = 0, qsum = 0;           // size of Q and sum of its members (wave-uniform)
+
+        // a class with one outstanding recv: its time goes to P of that recv, which joins Q
+        // when the time is positive
+#define TT_TO_P(k, hit1)                                                                  \
+        {                                                                                 \
+            if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
+            uint64_t qm = __ballot((hit1) && ct_##k > 0.0);                               \
+            while (qm) {                                                                  \
+                const int l = __builtin_ctzll(qm);                                        \
+                qm &= qm - 1;                                                             \
+                const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
+                const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);       \
+                const uint32_t bit = 1u << (sole & 31);                                   \
+                if (!(old & bit)) { qcount += 1; qsum += sole; }                          \
+                if (lane == 0) Qh[sole >> 5] = old | bit;                                 \
+                wave_sync();                                                              \
+            }                                                                             \
         }
+#define TT_INIT_P(k)                                                                      \
+        if constexpr (k < KT) {                                                           \
+            const bool one = pk_##k < 0 && pk_##k >= -CNT1;                               \
+            TT_TO_P(k, one)                                                               \
+        }
+        TT_EACH_K(TT_INIT_P)
 
         // ---- d. selection loop ----
         double F = 0.0;
         for (int step = 0; step < R; ++step) {
+            qcount = __builtin_amdgcn_readfirstlane(qcount);
+            qsum = __builtin_amdgcn_readfirstlane(qsum);
             int best;
             const bool from_q = qcount > 0;
             if (qcount == 1) {
@@ -210,24 +222,20 @@ tac_reg_kernel(const TacRegParams p)
             } else if (qcount == 0) {
                 // every outstanding recv has P = 0: lowest index among those of minimal M+
                 double lmin = TT_INF;
-#pragma unroll
-                for (int k = 0; k < KT; ++k)
-                    if (packed[k] >= 0) lmin = fmin(lmin, M[k]);
+#define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
+                TT_EACH_K(TT_LMIN)
                 const double g = wave_min_f64(lmin);
                 int cand = INT32_MAX;
                 if (g != TT_INF) {
-#pragma unroll
-                    for (int k = 0; k < KT; ++k)
-                        if (packed[k] >= 0 && M[k] == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k));
+#define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
+                    TT_EACH_K(TT_CAND)
                 }
                 best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
-                best = __builtin_amdgcn_readfirstlane(best);
                 if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
                     for (int h = 2 * W - 1; h >= 0; --h) {
                         const uint32_t x = aliveh[h];
                         if (x) best = h * 32 + __builtin_ctz(x);
                     }
-                    best = __builtin_amdgcn_readfirstlane(best);
                 }
             } else {
                 // ascending scan over Q with the comparator
@@ -247,13 +255,14 @@ tac_reg_kernel(const TacRegParams p)
                             prec = xa < ya;
                         } else {
                             double v = TT_INF, u = TT_INF;
-#pragma unroll
-                            for (int k = 0; k < KT; ++k) {
-                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);
-                                const uint32_t rb = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31);
-                                if (packed[k] >= 0 && (ra & 1u)) v = fmin(v, M[k]);
-                                if (packed[k] >= 0 && (rb & 1u)) u = fmin(u, M[k]);
+#define TT_MPLUS(k)                                                                       \
+                            if constexpr (k < KT) {                                       \
+                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
+                                const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
+                                if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);         \
+                                if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);        \
                             }
+                            TT_EACH_K(TT_MPLUS)
                             mp_a = wave_min_f64(v);
                             if (mp_best < 0.0) mp_best = wave_min_f64(u);
                             prec = mp_a < mp_best;
@@ -261,8 +270,8 @@ tac_reg_kernel(const TacRegParams p)
                         if (prec) { best = a; mp_best = mp_a; }
                     }
                 }
-                best = __builtin_amdgcn_readfirstlane(best);
             }
+            best = __builtin_amdgcn_readfirstlane(best);
             const double tb = t[best];
             F += tb;
             const int bh = best >> 5;
@@ -274,46 +283,35 @@ tac_reg_kernel(const TacRegParams p)
             }
             if (from_q) { qcount -= 1; qsum -= best; }
 
-            // ---- incremental property update (branch-free per class) ----
+            // ---- incremental property update, straight-line per class ----
             const uint32_t *rb = rows + (bh * 64 + lane) * KT;
             const int sh = best & 31;
             const int delta = CNT1 + best;
             const long long tb_bits = __double_as_longlong(tb);
-            int mask[KT];
             int evacc = 0;
-#pragma unroll
-            for (int k = 0; k < KT; ++k) {
-                if (!(live & (1u << k))) { mask[k] = 0; continue; }      // wave-uniform
-                mask[k] = __builtin_amdgcn_sbfe(rb[k], sh, 1);            // 0 or -1
-                packed[k] -= mask[k] & delta;
-                M[k] -= __longlong_as_double(tb_bits & (long long)mask[k]);
-                evacc |= packed[k] & mask[k];                             // negative: count fell to 1 or 0
+#define TT_UPDATE(k)                                                                      \
+            if constexpr (k < KT) {                                                       \
+                mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
+                pk_##k -= mk_##k & delta;                                                 \
+                M_##k -= __longlong_as_double(tb_bits & (long long)mk_##k);               \
+                evacc |= pk_##k & mk_##k;            /* negative: count fell to 1 or 0 */ \
             }
+            TT_EACH_K(TT_UPDATE)
             if (__ballot(evacc < 0) == 0ull) continue;
 
             // ---- some class fell to one outstanding recv, or to none ----
             wave_sync();
-#pragma unroll
-            for (int k = 0; k < KT; ++k) {
-                const bool ev = (packed[k] & mask[k]) < 0;
-                if (__ballot(ev) == 0ull) continue;
-                const bool hit0 = ev && packed[k] < -CNT1;
-                const bool hit1 = ev && !hit0;
-                if (hit1) atomicAdd(&P[packed[k] & IDX_MASK], ct[k]);
-                kap[k] = hit0 ? step + 1 : kap[k];
-                uint64_t qm = __ballot(hit1 && ct[k] > 0.0);
-                while (qm) {
-                    const int l = __builtin_ctzll(qm);
-                    qm &= qm - 1;
-                    const int sole = __builtin_amdgcn_readlane(packed[k], l) & IDX_MASK;
-                    const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);
-                    const uint32_t bit = 1u << (sole & 31);
-                    if (!(old & bit)) { qcount += 1; qsum += sole; }
-                    if (lane == 0) Qh[sole >> 5] = old | bit;
-                    wave_sync();
-                }
-                if (__ballot(hit0) != 0ull && __ballot(packed[k] >= -CNT1) == 0ull) live &= ~(1u << k);
+#define TT_EVENT(k)                                                                       \
+            if constexpr (k < KT) {                                                       \
+                const bool ev = (pk_##k & mk_##k) < 0;                                    \
+                if (__ballot(ev) != 0ull) {                                               \
+                    const bool hit0 = ev && pk_##k < -CNT1;                               \
+                    const bool hit1 = ev && !hit0;                                        \
+                    kap_##k = hit0 ? step + 1 : kap_##k;                                  \
+                    TT_TO_P(k, hit1)                                                      \
+                }                                                                         \
             }
+            TT_EACH_K(TT_EVENT)
         }
         wave_sync();
 
@@ -326,9 +324,8 @@ tac_reg_kernel(const TacRegParams p)
         if (p.simulate) {
             // A[k] = time of the classes released after k transfers; F_k = end of the k-th transfer;
             // makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
-#pragma unroll
-            for (int k = 0; k < KT; ++k)
-                if (k * 64 + lane < C) atomicAdd(&A[kap[k]], ct[k]);
+#define TT_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); }
+            TT_EACH_K(TT_RELEASE)
             // F_k into P[k - 1] (P is free now): prefix sums of the transfer times in TAC order
             double fc = 0.0;
             for (int base = 0; base < R; base += 64) {
