@@ -60,7 +60,7 @@ hipError_t ensure_workspace(Dag *d, size_t bytes)
 static void free_dag(Dag *d)
 {
     if (!d) return;
-    void *ptrs[] = {d->d_row_ptr, d->d_col_idx, d->d_recv_of_op, d->d_comp_col, d->d_lvl_ptr, d->d_lvl_ops,
+    void *ptrs[] = {d->d_recv_of_op, d->d_nodes, d->d_ovf_idx, d->d_nlvl_ptr, d->d_src,
                     d->d_dep, d->d_cls_dep, d->d_cls_depT, d->d_cls_cnt0, d->d_cls_ptr, d->d_cls_cols,
                     d->d_run_ptr, d->d_run_lo, d->d_run_hi, d->d_cls_isum, d->d_work};
     for (void *p : ptrs)
@@ -169,14 +169,6 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         }
     }
     if ((int32_t)queue.size() != n) { set_error("the graph has a cycle"); return TICTAC_ERR_CYCLE; }
-    std::vector<int32_t> lvl_ptr(n_levels + 1, 0), lvl_ops(n);
-    for (int32_t v = 0; v < n; ++v) lvl_ptr[level[v] + 1]++;
-    int32_t max_width = 0;
-    for (int32_t l = 0; l < n_levels; ++l) { max_width = std::max(max_width, lvl_ptr[l + 1]); lvl_ptr[l + 1] += lvl_ptr[l]; }
-    {
-        std::vector<int32_t> fill(lvl_ptr.begin(), lvl_ptr.end() - 1);
-        for (int32_t v = 0; v < n; ++v) lvl_ops[fill[level[v]]++] = v;   // ascending op id inside a level
-    }
     std::vector<int32_t> comp_col(n, -1);
     {
         int32_t j = 0;
@@ -184,18 +176,77 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             if (recv_of_op[v] < 0) comp_col[v] = j++;
     }
 
+    // ---- condensed graph: chains of single-predecessor compute ops collapse onto their head ----
+    // rep[v] = the node whose dep op v has (itself if v is a node); recvs are not nodes, they
+    // enter a node as single bits.
+    std::vector<int32_t> rep(n, -1), node_level(n, 0);
+    std::vector<std::vector<int32_t>> node_in(0);
+    std::vector<int32_t> node_ops;                       // in topological order
+    std::vector<int32_t> node_index(n, -1);              // op -> index into node_ops
+    std::vector<int32_t> tmp;
+    for (int32_t v : queue) {
+        if (recv_of_op[v] >= 0) continue;
+        tmp.assign(col_idx + row_ptr[v], col_idx + row_ptr[v + 1]);
+        std::sort(tmp.begin(), tmp.end());
+        tmp.erase(std::unique(tmp.begin(), tmp.end()), tmp.end());
+        if (tmp.size() == 1 && recv_of_op[tmp[0]] < 0) { rep[v] = rep[tmp[0]]; continue; }
+        rep[v] = v;
+        node_index[v] = (int32_t)node_ops.size();
+        node_ops.push_back(v);
+        std::vector<int32_t> in;                         // ~i for recv i, else index of the input node
+        int32_t lv = 0;
+        for (int32_t u : tmp) {
+            if (recv_of_op[u] >= 0) { in.push_back(~recv_of_op[u]); continue; }
+            const int32_t q = node_index[rep[u]];
+            in.push_back(q);
+            lv = std::max(lv, node_level[rep[u]] + 1);
+        }
+        std::sort(in.begin(), in.end());
+        in.erase(std::unique(in.begin(), in.end()), in.end());
+        node_level[v] = lv;
+        node_in.push_back(std::move(in));
+    }
+    const int32_t M = (int32_t)node_ops.size();
+    int32_t n_node_levels = 0;
+    for (int32_t v : node_ops) n_node_levels = std::max(n_node_levels, node_level[v] + 1);
+    std::vector<int32_t> nlvl_ptr(n_node_levels + 1, 0), pos_of_index(M);
+    for (int32_t v : node_ops) nlvl_ptr[node_level[v] + 1]++;
+    int32_t max_width = 0;
+    for (int32_t l = 0; l < n_node_levels; ++l) { max_width = std::max(max_width, nlvl_ptr[l + 1]); nlvl_ptr[l + 1] += nlvl_ptr[l]; }
+    {
+        std::vector<int32_t> fill(nlvl_ptr.begin(), nlvl_ptr.end() - 1);
+        for (int32_t k = 0; k < M; ++k) pos_of_index[k] = fill[node_level[node_ops[k]]]++;
+    }
+    std::vector<Dag::NodeRec> nodes(M);
+    std::vector<int32_t> ovf_idx;
+    for (int32_t k = 0; k < M; ++k) {
+        Dag::NodeRec &r = nodes[pos_of_index[k]];
+        r.op = node_ops[k];
+        r.ovf_beg = (int32_t)ovf_idx.size();
+        r.ovf_cnt = 0;
+        r.pad = 0;
+        for (int j = 0; j < 4; ++j) r.in[j] = INT32_MIN;
+        int j = 0;
+        for (int32_t x : node_in[k]) {
+            const int32_t y = x < 0 ? x : pos_of_index[x];
+            if (j < 4) r.in[j] = y; else { ovf_idx.push_back(y); r.ovf_cnt++; }
+            ++j;
+        }
+    }
+    std::vector<int32_t> src(n);
+    for (int32_t v = 0; v < n; ++v) src[v] = recv_of_op[v] >= 0 ? ~recv_of_op[v] : rep[v];
+
     d->n = n; d->R = R; d->W = (R + 63) / 64; d->N = n - R; d->E = E;
-    d->n_levels = n_levels; d->max_level_width = max_width;
+    d->n_levels = n_levels;
+    d->M = M; d->n_node_levels = n_node_levels; d->max_node_level_width = max_width;
     HIP_TRY(hipGetDevice(&d->device));
 
     // ---- upload and propagate ----
-    std::vector<int32_t> rp(row_ptr, row_ptr + n + 1), ci(col_idx, col_idx + E);
-    HIP_TRY(upload(&d->d_row_ptr, rp, s));
-    HIP_TRY(upload(&d->d_col_idx, ci, s));
     HIP_TRY(upload(&d->d_recv_of_op, recv_of_op, s));
-    HIP_TRY(upload(&d->d_comp_col, comp_col, s));
-    HIP_TRY(upload(&d->d_lvl_ptr, lvl_ptr, s));
-    HIP_TRY(upload(&d->d_lvl_ops, lvl_ops, s));
+    HIP_TRY(upload(&d->d_nodes, nodes, s));
+    HIP_TRY(upload(&d->d_ovf_idx, ovf_idx, s));
+    HIP_TRY(upload(&d->d_nlvl_ptr, nlvl_ptr, s));
+    HIP_TRY(upload(&d->d_src, src, s));
     const size_t dep_words = (size_t)n * d->W;
     if (dep_words) {
         HIP_TRY(hipMalloc((void **)&d->d_dep, dep_words * 8));

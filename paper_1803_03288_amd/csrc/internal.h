@@ -20,14 +20,24 @@ struct Dag {
     int32_t max_level_width = 0;
     int device = 0;
 
-    // graph, by op id
-    int32_t *d_row_ptr = nullptr;   // [n+1]
-    int32_t *d_col_idx = nullptr;   // [E]
     int32_t *d_recv_of_op = nullptr;// [n]  recv index or -1
-    int32_t *d_comp_col = nullptr;  // [n]  column in op_time, or -1 for a recv
-    // level structure: ops sorted by level (longest path from a root)
-    int32_t *d_lvl_ptr = nullptr;   // [n_levels+1]
-    int32_t *d_lvl_ops = nullptr;   // [n]
+
+    // Condensed graph used by the propagation.  A compute op whose only predecessor is a
+    // compute op has that op's dep; every other compute op is a *node*.  Nodes are sorted
+    // by level (longest path counted in nodes) into positions 0..M-1.
+    int32_t M = 0;                  // number of nodes
+    int32_t n_node_levels = 0;
+    int32_t max_node_level_width = 0;
+    struct NodeRec {                // 32 bytes, one per position
+        int32_t in[4];              // first inputs: q >= 0 node position, ~i < 0 recv i, INT32_MIN none
+        int32_t op;                 // op id of the node
+        int32_t ovf_beg, ovf_cnt;   // further inputs in ovf_idx[ovf_beg .. ovf_beg + ovf_cnt)
+        int32_t pad;
+    };
+    NodeRec *d_nodes = nullptr;     // [M]
+    int32_t *d_ovf_idx = nullptr;   // inputs beyond the fourth
+    int32_t *d_nlvl_ptr = nullptr;  // [n_node_levels + 1] positions of each level
+    int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]
 
