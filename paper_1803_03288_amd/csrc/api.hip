@@ -194,21 +194,25 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         node_index[v] = (int32_t)node_ops.size();
         node_ops.push_back(v);
         std::vector<int32_t> in;                         // ~i for recv i, else index of the input node
-        int32_t lv = 0;
         for (int32_t u : tmp) {
-            if (recv_of_op[u] >= 0) { in.push_back(~recv_of_op[u]); continue; }
-            const int32_t q = node_index[rep[u]];
-            in.push_back(q);
-            lv = std::max(lv, node_level[rep[u]] + 1);
+            if (recv_of_op[u] >= 0) in.push_back(~recv_of_op[u]);
+            else in.push_back(node_index[rep[u]]);
         }
         std::sort(in.begin(), in.end());
         in.erase(std::unique(in.begin(), in.end()), in.end());
-        node_level[v] = lv;
         node_in.push_back(std::move(in));
     }
     const int32_t M = (int32_t)node_ops.size();
+    // Nodes are grouped by the level of their op in the full graph (an input of a node lies on a
+    // strictly lower level, and close to it, which keeps inputs inside the kernel's LDS ring);
+    // levels without nodes are dropped.
     int32_t n_node_levels = 0;
-    for (int32_t v : node_ops) n_node_levels = std::max(n_node_levels, node_level[v] + 1);
+    {
+        std::vector<int32_t> used(n_levels + 1, 0);
+        for (int32_t v : node_ops) used[level[v]] = 1;
+        for (int32_t l = 0; l < n_levels; ++l) { const int32_t u = used[l]; used[l] = n_node_levels; n_node_levels += u; }
+        for (int32_t v : node_ops) node_level[v] = used[level[v]];
+    }
     std::vector<int32_t> nlvl_ptr(n_node_levels + 1, 0), pos_of_index(M);
     for (int32_t v : node_ops) nlvl_ptr[node_level[v] + 1]++;
     int32_t max_width = 0;
@@ -222,14 +226,18 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     for (int32_t k = 0; k < M; ++k) {
         Dag::NodeRec &r = nodes[pos_of_index[k]];
         r.op = node_ops[k];
-        r.ovf_beg = (int32_t)ovf_idx.size();
-        r.ovf_cnt = 0;
-        r.pad = 0;
-        for (int j = 0; j < 4; ++j) r.in[j] = INT32_MIN;
+        r.ovf_beg = -1;
+        for (int j = 0; j < 6; ++j) r.in[j] = INT32_MIN;
         int j = 0;
         for (int32_t x : node_in[k]) {
             const int32_t y = x < 0 ? x : pos_of_index[x];
-            if (j < 4) r.in[j] = y; else { ovf_idx.push_back(y); r.ovf_cnt++; }
+            if (j < 6) {
+                r.in[j] = y;
+            } else {
+                if (r.ovf_beg < 0) { r.ovf_beg = (int32_t)ovf_idx.size(); ovf_idx.push_back(0); }
+                ovf_idx.push_back(y);
+                ovf_idx[r.ovf_beg]++;
+            }
             ++j;
         }
     }

@@ -29,10 +29,9 @@ struct Dag {
     int32_t n_node_levels = 0;
     int32_t max_node_level_width = 0;
     struct NodeRec {                // 32 bytes, one per position
-        int32_t in[4];              // first inputs: q >= 0 node position, ~i < 0 recv i, INT32_MIN none
+        int32_t in[6];              // first inputs: q >= 0 node position, ~i < 0 recv i, INT32_MIN none
         int32_t op;                 // op id of the node
-        int32_t ovf_beg, ovf_cnt;   // further inputs in ovf_idx[ovf_beg .. ovf_beg + ovf_cnt)
-        int32_t pad;
+        int32_t ovf_beg;            // -1, or: ovf_idx[ovf_beg] further inputs follow at ovf_idx[ovf_beg + 1 ..]
     };
     NodeRec *d_nodes = nullptr;     // [M]
     int32_t *d_ovf_idx = nullptr;   // inputs beyond the fourth
