@@ -15,11 +15,12 @@
 //     anything else has to happen), and once the count is 1 the index sum *is* the last
 //     outstanding recv of the class, to whose P the class time is then added;
 //   * Q is tracked by its size and the sum of its members (one member: the sum is the
-//     member, the common case on layered models), next to a bitset used by the scan when it
-//     has several;
+//     member, the common case on layered models); a recv is in Q exactly when its P is
+//     positive (P of a selected recv is reset), which is what the scan enumerates when Q has
+//     several members;
 //   * M of a class is initialised from prefix sums T of the transfer times: the sum over the
 //     runs [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo];
-//   * the step at which a class's count reaches 0 is its release position kappa; after the
+//   * the last step at which a class's count is decremented is its release position kappa; after the
 //     loop the class times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
 //     the end of the k-th transfer, S_k the time of the classes with kappa >= k (the closed
 //     form of the work-conserving device described in k4_simulate.hip);
@@ -98,7 +99,7 @@ tac_reg_kernel(const TacRegParams p)
     double *A = P + (R + 1);                // [R+1]  class time by release position
     int32_t *ordl = reinterpret_cast<int32_t *>(A + (R + 1));       // [R] order built so far
     uint32_t *aliveh = reinterpret_cast<uint32_t *>(ordl + R);      // [2W] outstanding recvs
-    uint32_t *Qh = aliveh + 2 * W;                                  // [2W] Q
+    uint32_t *Qh = aliveh + 2 * W;                                  // [2W] spare
     double *X = reinterpret_cast<double *>(Qh + 2 * W + ((R + 4 * W) & 1));   // [N] op_time row (STAGE)
 
     for (int idx = threadIdx.x; idx < 2 * W * 64 * KT; idx += blockDim.x) {
@@ -178,29 +179,33 @@ tac_reg_kernel(const TacRegParams p)
         for (int r = lane; r < R; r += 64) P[r] = 0.0;
         if (p.simulate)
             for (int j = lane; j <= R; j += 64) A[j] = 0.0;
-        if (lane < 2 * W) {
-            const int nb = R - lane * 32;
-            aliveh[lane] = nb >= 32 ? ~0u : (nb > 0 ? ((1u << nb) - 1u) : 0u);
-            Qh[lane] = 0u;
-        }
+        uint32_t alive_l = 0;               // bit j: recv 64 j + lane is outstanding
+        for (int j = 0; j * 64 + lane < R; ++j) alive_l |= 1u << j;
         wave_sync();
         int qcount = 0, qsum = 0;           // size of Q and sum of its members (wave-uniform)
 
-        // a class with one outstanding recv: its time goes to P of that recv, which joins Q
-        // when the time is positive
+        // outstanding recvs as 32-bit halves in LDS, for the rare paths that need them by index
+        auto publish_alive = [&]() {
+            for (int j = 0; j < W; ++j) {
+                const uint64_t m = __ballot((alive_l >> j) & 1u);
+                if (lane == 0) { aliveh[2 * j] = (uint32_t)m; aliveh[2 * j + 1] = (uint32_t)(m >> 32); }
+            }
+            wave_sync();
+        };
+
+        // A class with one outstanding recv left: its time goes to P of that recv.  The recv
+        // joins Q when that makes P positive for the first time; the value P had before the
+        // addition (returned by the LDS atomic) tells.
 #define TT_TO_P(k, hit1)                                                                  \
         {                                                                                 \
-            if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
-            uint64_t qm = __ballot((hit1) && ct_##k > 0.0);                               \
-            while (qm) {                                                                  \
-                const int l = __builtin_ctzll(qm);                                        \
-                qm &= qm - 1;                                                             \
-                const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
-                const uint32_t old = __builtin_amdgcn_readfirstlane(Qh[sole >> 5]);       \
-                const uint32_t bit = 1u << (sole & 31);                                   \
-                if (!(old & bit)) { qcount += 1; qsum += sole; }                          \
-                if (lane == 0) Qh[sole >> 5] = old | bit;                                 \
-                wave_sync();                                                              \
+            double oldp = 1.0;                                                            \
+            if (hit1) oldp = atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                    \
+            uint64_t nm = __ballot((hit1) && ct_##k > 0.0 && oldp == 0.0);                \
+            while (nm) {                                                                  \
+                const int l = __builtin_ctzll(nm);                                        \
+                nm &= nm - 1;                                                             \
+                qcount += 1;                                                              \
+                qsum += __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;                  \
             }                                                                             \
         }
 #define TT_INIT_P(k)                                                                      \
@@ -216,11 +221,11 @@ tac_reg_kernel(const TacRegParams p)
             qcount = __builtin_amdgcn_readfirstlane(qcount);
             qsum = __builtin_amdgcn_readfirstlane(qsum);
             int best;
-            const bool from_q = qcount > 0;
             if (qcount == 1) {
                 best = qsum;
             } else if (qcount == 0) {
                 // every outstanding recv has P = 0: lowest index among those of minimal M+
+                publish_alive();
                 double lmin = TT_INF;
 #define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
                 TT_EACH_K(TT_LMIN)
@@ -238,13 +243,16 @@ tac_reg_kernel(const TacRegParams p)
                     }
                 }
             } else {
-                // ascending scan over Q with the comparator
+                // ascending scan over Q = {r : P[r] > 0} with the comparator
                 double mp_best = -1.0;
                 best = -1;
-                for (int h = 0; h < 2 * W; ++h) {
-                    uint32_t x = __builtin_amdgcn_readfirstlane(Qh[h]);
+                wave_sync();
+                for (int j = 0; j < W; ++j) {
+                    const int r = j * 64 + lane;
+                    const double pv = r < R ? P[r] : 0.0;
+                    uint64_t x = __ballot(pv > 0.0);
                     while (x) {
-                        const int a = h * 32 + __builtin_ctz(x);
+                        const int a = j * 64 + __builtin_ctzll(x);
                         x &= x - 1;
                         if (best < 0) { best = a; continue; }
                         const double xa = fmin(P[best], t[a]);
@@ -274,42 +282,36 @@ tac_reg_kernel(const TacRegParams p)
             best = __builtin_amdgcn_readfirstlane(best);
             const double tb = t[best];
             F += tb;
-            const int bh = best >> 5;
-            const uint32_t bbit = 1u << (best & 31);
-            if (lane == 0) {
-                ordl[step] = best;
-                aliveh[bh] &= ~bbit;
-                if (from_q) Qh[bh] &= ~bbit;
-            }
-            if (from_q) { qcount -= 1; qsum -= best; }
+            ordl[step] = best;                  // every lane writes the same value
+            P[best] = 0.0;                      // leaves Q (if it was in it)
+            const int fq = qcount > 0 ? 1 : 0;
+            qcount -= fq;
+            qsum -= fq ? best : 0;
+            alive_l &= ~((uint32_t)(lane == (best & 63)) << (best >> 6));
 
             // ---- incremental property update, straight-line per class ----
-            const uint32_t *rb = rows + (bh * 64 + lane) * KT;
+            const uint32_t *rb = rows + ((best >> 5) * 64 + lane) * KT;
             const int sh = best & 31;
             const int delta = CNT1 + best;
-            const long long tb_bits = __double_as_longlong(tb);
-            int evacc = 0;
+            const int step1 = step + 1;
+            const int tb_lo = __double2loint(tb), tb_hi = __double2hiint(tb);
+            uint32_t hacc = 0xffffffffu;
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
                 pk_##k -= mk_##k & delta;                                                 \
-                M_##k -= __longlong_as_double(tb_bits & (long long)mk_##k);               \
-                evacc |= pk_##k & mk_##k;            /* negative: count fell to 1 or 0 */ \
+                M_##k -= __hiloint2double(tb_hi & mk_##k, tb_lo & mk_##k);                \
+                kap_##k = (kap_##k & ~mk_##k) | (step1 & mk_##k);  /* last decrement = release */ \
+                hacc = min(hacc, (uint32_t)((pk_##k & mk_##k) + CNT1));  /* < CNT1: count fell to 1 */ \
             }
             TT_EACH_K(TT_UPDATE)
-            if (__ballot(evacc < 0) == 0ull) continue;
+            if (__ballot(hacc < (uint32_t)CNT1) == 0ull) continue;
 
-            // ---- some class fell to one outstanding recv, or to none ----
-            wave_sync();
+            // ---- some class fell to one outstanding recv ----
 #define TT_EVENT(k)                                                                       \
             if constexpr (k < KT) {                                                       \
-                const bool ev = (pk_##k & mk_##k) < 0;                                    \
-                if (__ballot(ev) != 0ull) {                                               \
-                    const bool hit0 = ev && pk_##k < -CNT1;                               \
-                    const bool hit1 = ev && !hit0;                                        \
-                    kap_##k = hit0 ? step + 1 : kap_##k;                                  \
-                    TT_TO_P(k, hit1)                                                      \
-                }                                                                         \
+                const bool hit1 = (uint32_t)((pk_##k & mk_##k) + CNT1) < (uint32_t)CNT1;  \
+                if (__ballot(hit1) != 0ull) TT_TO_P(k, hit1)                              \
             }
             TT_EACH_K(TT_EVENT)
         }
