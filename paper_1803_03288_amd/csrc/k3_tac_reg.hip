@@ -15,9 +15,9 @@
 //     anything else has to happen), and once the count is 1 the index sum *is* the last
 //     outstanding recv of the class, to whose P the class time is then added;
 //   * Q is tracked by its size and the sum of its members (one member: the sum is the
-//     member, the common case on layered models); a recv is in Q exactly when its P is
-//     positive (P of a selected recv is reset), which is what the scan enumerates when Q has
-//     several members;
+//     member, the common case on layered models); the bitsets of outstanding recvs and of
+//     Q are spread over the lanes (bit j of lane l stands for recv 64 j + l) and are only
+//     gathered by ballots on the paths that need them;
 //   * M of a class is initialised from prefix sums T of the transfer times: the sum over the
 //     runs [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo];
 //   * the last step at which a class's count is decremented is its release position kappa; after the
@@ -193,19 +193,21 @@ tac_reg_kernel(const TacRegParams p)
             wave_sync();
         };
 
-        // A class with one outstanding recv left: its time goes to P of that recv.  The recv
-        // joins Q when that makes P positive for the first time; the value P had before the
-        // addition (returned by the LDS atomic) tells.
+        // A class with one outstanding recv left: its time goes to P of that recv, which joins Q
+        // when that time is positive.  inq_l mirrors alive_l for membership in Q.
+        uint32_t inq_l = 0;
 #define TT_TO_P(k, hit1)                                                                  \
         {                                                                                 \
-            double oldp = 1.0;                                                            \
-            if (hit1) oldp = atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                    \
-            uint64_t nm = __ballot((hit1) && ct_##k > 0.0 && oldp == 0.0);                \
+            if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
+            uint64_t nm = __ballot((hit1) && ct_##k > 0.0);                               \
             while (nm) {                                                                  \
                 const int l = __builtin_ctzll(nm);                                        \
                 nm &= nm - 1;                                                             \
-                qcount += 1;                                                              \
-                qsum += __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;                  \
+                const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
+                const uint32_t had = (__builtin_amdgcn_readlane(inq_l, sole & 63) >> (sole >> 6)) & 1u; \
+                qcount += 1 - (int)had;                                                   \
+                qsum += had ? 0 : sole;                                                   \
+                inq_l |= (uint32_t)(lane == (sole & 63)) << (sole >> 6);                  \
             }                                                                             \
         }
 #define TT_INIT_P(k)                                                                      \
@@ -243,14 +245,12 @@ tac_reg_kernel(const TacRegParams p)
                     }
                 }
             } else {
-                // ascending scan over Q = {r : P[r] > 0} with the comparator
+                // ascending scan over Q with the comparator
                 double mp_best = -1.0;
                 best = -1;
                 wave_sync();
                 for (int j = 0; j < W; ++j) {
-                    const int r = j * 64 + lane;
-                    const double pv = r < R ? P[r] : 0.0;
-                    uint64_t x = __ballot(pv > 0.0);
+                    uint64_t x = __ballot((inq_l >> j) & 1u);
                     while (x) {
                         const int a = j * 64 + __builtin_ctzll(x);
                         x &= x - 1;
@@ -283,11 +283,12 @@ tac_reg_kernel(const TacRegParams p)
             const double tb = t[best];
             F += tb;
             ordl[step] = best;                  // every lane writes the same value
-            P[best] = 0.0;                      // leaves Q (if it was in it)
-            const int fq = qcount > 0 ? 1 : 0;
+            const int fq = qcount > 0 ? 1 : 0;  // the selected recv is a member of Q whenever Q is not empty
             qcount -= fq;
             qsum -= fq ? best : 0;
-            alive_l &= ~((uint32_t)(lane == (best & 63)) << (best >> 6));
+            const uint32_t gone = ~((uint32_t)(lane == (best & 63)) << (best >> 6));
+            alive_l &= gone;
+            inq_l &= gone;
 
             // ---- incremental property update, straight-line per class ----
             const uint32_t *rb = rows + ((best >> 5) * 64 + lane) * KT;
