@@ -83,7 +83,7 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
 #define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
 template <int KT, bool STAGE>
-__global__ void __launch_bounds__(64 * kRegWaves)
+__global__ void __launch_bounds__(64 * kRegWaves, (KT <= 4 ? 5 : 2))
 tac_reg_kernel(const TacRegParams p)
 {
     extern __shared__ double smem[];
@@ -111,20 +111,13 @@ tac_reg_kernel(const TacRegParams p)
     }
     __syncthreads();                        // the only workgroup barrier
 
-    // ---- per-lane constants of the class slots ----
-#define TT_DECL_CONST(k) int pk0_##k = -2 * CNT1, mbeg_##k = 0, mcnt_##k = 0, mmax_##k = 0, rbeg_##k = 0, rend_##k = 0;
+    // ---- wave-uniform bounds of the member loops of the class slots ----
+#define TT_DECL_CONST(k) int mmax_##k = 0;
     TT_EACH_K(TT_DECL_CONST)
 #define TT_INIT_CONST(k)                                                                  \
     if constexpr (k < KT) {                                                               \
         const int c = k * 64 + lane;                                                      \
-        if (c < C) {                                                                      \
-            pk0_##k = (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c];                         \
-            mbeg_##k = p.cls_ptr[c];                                                      \
-            mcnt_##k = p.cls_ptr[c + 1] - mbeg_##k;                                       \
-            rbeg_##k = p.run_ptr[c];                                                      \
-            rend_##k = p.run_ptr[c + 1];                                                  \
-        }                                                                                 \
-        int mx = mcnt_##k;                                                                \
+        int mx = c < C ? p.cls_ptr[c + 1] - p.cls_ptr[c] : 0;                             \
         for (int off = 32; off > 0; off >>= 1) mx = max(mx, __shfl_xor(mx, off));         \
         mmax_##k = __builtin_amdgcn_readfirstlane(mx);                                    \
     }
@@ -161,15 +154,21 @@ tac_reg_kernel(const TacRegParams p)
         double ct_sum = 0.0;
 #define TT_INIT_STATE(k)                                                                  \
         if constexpr (k < KT) {                                                           \
+            const int c = k * 64 + lane;                                                  \
             double s = 0.0, Mk = 0.0;                                                     \
-            _Pragma("unroll 4")                                                           \
-            for (int m = 0; m < mmax_##k; ++m)                                            \
-                if (m < mcnt_##k) {                                                       \
-                    const int col = p.cls_cols[mbeg_##k + m];                             \
-                    s += STAGE ? X[col] : ot[col];                                        \
-                }                                                                         \
-            for (int q = rbeg_##k; q < rend_##k; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]]; \
-            ct_##k = s; M_##k = Mk; pk_##k = pk0_##k;                                     \
+            if (c < C) {                                                                  \
+                const int mbeg = p.cls_ptr[c], mcnt = p.cls_ptr[c + 1] - mbeg;            \
+                _Pragma("unroll 4")                                                       \
+                for (int m = 0; m < mmax_##k; ++m)                                        \
+                    if (m < mcnt) {                                                       \
+                        const int col = p.cls_cols[mbeg + m];                             \
+                        s += STAGE ? X[col] : ot[col];                                    \
+                    }                                                                     \
+                const int rend = p.run_ptr[c + 1];                                        \
+                for (int q = p.run_ptr[c]; q < rend; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]]; \
+                pk_##k = (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c];                      \
+            }                                                                             \
+            ct_##k = s; M_##k = Mk;                                                       \
             ct_sum += s;                                                                  \
         }
         TT_EACH_K(TT_INIT_STATE)
