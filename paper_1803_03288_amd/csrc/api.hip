@@ -60,7 +60,7 @@ hipError_t ensure_workspace(Dag *d, size_t bytes)
 static void free_dag(Dag *d)
 {
     if (!d) return;
-    void *ptrs[] = {d->d_recv_of_op, d->d_nodes, d->d_ovf_idx, d->d_nlvl_ptr, d->d_src,
+    void *ptrs[] = {d->d_recv_of_op, d->d_nodes, d->d_ovf_idx, d->d_nlvl_ptr, d->d_src, d->d_chunk_end,
                     d->d_dep, d->d_cls_dep, d->d_cls_depT, d->d_cls_cnt0, d->d_cls_ptr, d->d_cls_cols,
                     d->d_run_ptr, d->d_run_lo, d->d_run_hi, d->d_cls_isum, d->d_work};
     for (void *p : ptrs)
@@ -254,6 +254,23 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     HIP_TRY(upload(&d->d_nodes, nodes, s));
     HIP_TRY(upload(&d->d_ovf_idx, ovf_idx, s));
     HIP_TRY(upload(&d->d_nlvl_ptr, nlvl_ptr, s));
+    {
+        // words per workgroup slice, threads, and the chunks of levels of the node kernel
+        // a workgroup's LDS traffic per level grows with its slice, so wide bitsets get many narrow slices
+        d->k1_wc = d->W <= 1 ? 1 : (d->W <= 2 ? 2 : (d->W >= 16 ? 1 : 4));
+        int threads = max_width * d->k1_wc;
+        threads = threads < 64 ? 64 : (threads > 1024 ? 1024 : (threads + 63) / 64 * 64);
+        d->k1_threads = threads;
+        const int32_t per_pass = threads / d->k1_wc;
+        std::vector<int32_t> chunk_end(n_node_levels, 0);
+        for (int32_t l0 = 0; l0 < n_node_levels;) {
+            int32_t l1 = l0 + 1;
+            while (l1 < n_node_levels && l1 - l0 < 64 && nlvl_ptr[l1 + 1] - nlvl_ptr[l0] <= 4 * per_pass) ++l1;
+            chunk_end[l0] = l1;
+            l0 = l1;
+        }
+        HIP_TRY(upload(&d->d_chunk_end, chunk_end, s));
+    }
     HIP_TRY(upload(&d->d_src, src, s));
     const size_t dep_words = (size_t)n * d->W;
     if (dep_words) {

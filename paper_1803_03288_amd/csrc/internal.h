@@ -36,6 +36,10 @@ struct Dag {
     NodeRec *d_nodes = nullptr;     // [M]
     int32_t *d_ovf_idx = nullptr;   // inputs beyond the fourth
     int32_t *d_nlvl_ptr = nullptr;  // [n_node_levels + 1] positions of each level
+    // launch shape of the node kernel and its chunks of consecutive levels (at most 4 k1_threads / k1_wc
+    // positions and 64 levels each): chunk_end[lv] = first level after the chunk that starts at lv
+    int32_t k1_wc = 0, k1_threads = 0;
+    int32_t *d_chunk_end = nullptr; // [n_node_levels]
     int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]

@@ -43,7 +43,7 @@ __device__ __forceinline__ void drain_barrier() { asm volatile("s_waitcnt vmcnt(
 
 template <int WC>
 __global__ void __launch_bounds__(1024)
-propagate_nodes(const PropParams p)
+propagate_nodes_wide(const PropParams p)
 {
     extern __shared__ uint64_t ring[];                  // [ring][WC], then records, then level bounds
     const int W = p.W;
@@ -162,6 +162,177 @@ propagate_nodes(const PropParams p)
     }
 }
 
+// Main node kernel, for graphs whose widest level fits one pass of the workgroup (one
+// thread per node and word).  Nothing on the per-level path touches memory:
+//   * levels are processed in chunks made by the host (at most RPT positions per thread
+//     group, at most 64 levels).  The records of a chunk sit in LDS.  At a chunk boundary a
+//     thread writes the records it loaded one chunk earlier into the other LDS buffer,
+//     stores the words it computed in the chunk just finished, and starts the loads of the
+//     records of the chunk after the next; so loads and stores have a whole chunk to
+//     complete, and the barrier between two levels waits for LDS only;
+//   * the wait for those loads at the next boundary also covers the stores, so the rows of
+//     a chunk are in memory two chunks later.  The ring holds at least two chunks (or every
+//     node), hence any input that has left the ring is in memory.
+constexpr int WIN_LEVELS = 512;                 // levels per refill of the bounds window
+constexpr int WIN_MARGIN = 200;                 // three chunks ahead (64 levels each) and slack
+constexpr int RPT = 4;                          // positions per thread group and chunk
+
+template <int WC>
+__global__ void __launch_bounds__(1024)
+propagate_nodes(const PropParams p, const int32_t *__restrict__ chunk_end)
+{
+    extern __shared__ uint64_t ring[];                  // [ring][WC], records [2][CH], level windows
+    const int W = p.W, L = p.n_levels;
+    const int w = threadIdx.x % WC;
+    const int gw = blockIdx.x * WC + w;
+    const int sub = threadIdx.x / WC;
+    const int per_pass = blockDim.x / WC;
+    const int CH = RPT * per_pass;                      // most positions of a chunk
+    const uint32_t rmask = (uint32_t)p.ring - 1u;
+    // row p.ring of the ring is all zero; two rows are reserved so that what follows stays 16-byte aligned
+    int4 *recbuf = reinterpret_cast<int4 *>(ring + (size_t)(p.ring + 2) * WC);  // [2][CH][2]
+    if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
+    int32_t *lvl = reinterpret_cast<int32_t *>(recbuf + (size_t)4 * CH);        // [WIN_LEVELS + WIN_MARGIN]
+    int32_t *cend = lvl + WIN_LEVELS + WIN_MARGIN;                               // [WIN_LEVELS + WIN_MARGIN]
+
+    int base = 0;
+    auto fill_window = [&](int b0) {
+        for (int i = threadIdx.x; i < WIN_LEVELS + WIN_MARGIN; i += blockDim.x) {
+            lvl[i] = p.nlvl_ptr[min(b0 + i, L)];
+            cend[i] = b0 + i < L ? chunk_end[b0 + i] : L;
+        }
+    };
+    fill_window(0);
+    __syncthreads();
+    if (L == 0) return;
+
+    // chunk c: levels [L0, L1), positions [c0, c1); chunk c+1: levels [L1, L2), positions [c1, c2)
+    int L0 = 0, L1 = cend[0];
+    int c0 = lvl[0], c1 = lvl[L1];
+    int L2 = L1 < L ? cend[L1] : L1;
+    int c2 = lvl[L2];
+    int4 na[RPT], nb[RPT];                              // records of the next chunk, in flight
+    // prologue: records of chunk 0 straight into buffer 0, records of chunk 1 into registers
+    for (int j = 0; j < RPT; ++j) {
+        const int i = sub + j * per_pass;
+        if (w == 0 && c0 + i < c1) {
+            const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c0 + i);
+            recbuf[(size_t)i * 2] = q[0];
+            recbuf[(size_t)i * 2 + 1] = q[1];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RPT; ++j) {
+        na[j] = make_int4(0, 0, 0, 0); nb[j] = na[j];
+        const int i = sub + j * per_pass;
+        if (c1 + i < c2) {
+            const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c1 + i);
+            na[j] = q[0]; nb[j] = q[1];
+        }
+    }
+    __syncthreads();
+
+    int cur = 0;
+    while (L0 < L) {
+        const int4 *rec = recbuf + (size_t)cur * 2 * CH;
+        // A level is at most per_pass wide, so a thread group meets at most one of its positions
+        // c0 + sub + j per_pass per level, in ascending j.  The record of the next one is read
+        // from LDS a level ahead; so is the upper bound of the next level.
+        int mypos = c0 + sub;
+        int4 ra = make_int4(0, 0, 0, 0), rb = ra;
+        if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }
+        int end_next = lvl[L0 + 1 - base];
+        for (int lv = L0; lv < L1; ++lv) {
+            const int end = end_next;
+            if (lv + 1 < L1) end_next = lvl[lv + 2 - base];
+            if (mypos < end) {
+                const int safe_from = max(end - p.ring, 0);   // older positions: read from memory
+                const int in[6] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y};
+                const int ovf_beg = rb.w;
+                // all inputs at once: a recv contributes a bit, a position in the ring its word, and
+                // anything else reads the zero row kept after the ring
+                uint64_t bits = 0, v[6];
+                bool slow = ovf_beg >= 0;
+#pragma unroll
+                for (int j = 0; j < 6; ++j) {
+                    const int x = in[j];
+                    const int i = ~x;
+                    const bool is_recv = x < 0 && x != INT32_MIN;
+                    bits |= (is_recv && (i >> 6) == gw) ? 1ull << (i & 63) : 0ull;
+                    const bool in_ring = x >= safe_from;
+                    slow |= x >= 0 && !in_ring;
+                    const uint32_t slot = in_ring ? ((uint32_t)x & rmask) : (uint32_t)p.ring;
+                    v[j] = ring[slot * WC + w];
+                }
+                uint64_t val = bits | v[0] | v[1] | v[2] | v[3] | v[4] | v[5];
+                if (slow && gw < W) {                         // long edges and overflow inputs (rare)
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) {
+                        const int x = in[j];
+                        if (x >= 0 && x < safe_from) val |= p.dep[(size_t)p.nodes[x].op * W + gw];
+                    }
+                    const int ovf_cnt = ovf_beg >= 0 ? p.ovf_idx[ovf_beg] : 0;
+                    for (int e = 1; e <= ovf_cnt; ++e) {
+                        const int x = p.ovf_idx[ovf_beg + e];
+                        if (x < 0) {
+                            const int i = ~x;
+                            if ((i >> 6) == gw) val |= 1ull << (i & 63);
+                        } else if (x >= safe_from) {
+                            val |= ring[((uint32_t)x & rmask) * WC + w];
+                        } else {
+                            val |= p.dep[(size_t)p.nodes[x].op * W + gw];
+                        }
+                    }
+                }
+                if (gw >= W) val = 0;
+                ring[((uint32_t)mypos & rmask) * WC + w] = val;
+                mypos += per_pass;
+                if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }
+            }
+            if (lv + 1 < L1) lds_barrier();
+        }
+        // ---- chunk boundary ----
+        // every thread waits for what it issued at the previous boundary (one chunk ago): the
+        // record loads used next, and the stores of the chunk before this one
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // records of chunk c+1 into the other buffer
+        int4 *other = recbuf + (size_t)(cur ^ 1) * 2 * CH;
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            const int i = sub + j * per_pass;
+            if (w == 0 && c1 + i < c2) { other[(size_t)i * 2] = na[j]; other[(size_t)i * 2 + 1] = nb[j]; }
+        }
+        // words of chunk c to memory (each thread stores what it computed itself)
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            const int pos = c0 + sub + j * per_pass;
+            if (pos < c1 && gw < W) {
+                const int op = reinterpret_cast<const int32_t *>(rec + (size_t)(pos - c0) * 2 + 1)[2];
+                p.dep[(size_t)op * W + gw] = ring[((uint32_t)pos & rmask) * WC + w];
+            }
+        }
+        // records of chunk c+2
+        const int L3 = L2 < L ? cend[L2 - base] : L2;
+        const int c3 = lvl[L3 - base];
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            const int i = sub + j * per_pass;
+            if (c2 + i < c3) {
+                const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c2 + i);
+                na[j] = q[0]; nb[j] = q[1];
+            }
+        }
+        lds_barrier();
+        cur ^= 1;
+        L0 = L1; L1 = L2; L2 = L3; c0 = c1; c1 = c2; c2 = c3;
+        if (L0 < L && L0 - base >= WIN_LEVELS) {         // slide the windows (uniform)
+            base = L0;
+            fill_window(base);
+            __syncthreads();
+        }
+    }
+}
+
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto
 __global__ void __launch_bounds__(256)
 expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep)
@@ -184,22 +355,28 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     PropParams p;
     p.n_levels = d.n_node_levels; p.W = d.W; p.M = d.M;
     p.nodes = d.d_nodes; p.ovf_idx = d.d_ovf_idx; p.nlvl_ptr = d.d_nlvl_ptr; p.dep = d.d_dep;
-    // ring: the largest power of two of positions within 96 KB, no larger than needed
+    const int threads = d.k1_threads;
+    const int per_pass = threads / WC;
+    const int blocks = (d.W + WC - 1) / WC;
+    const bool wide = d.max_node_level_width > per_pass;
+    // ring: a power of two of positions; at least two chunks (or all nodes), at most 64 KB beyond that
     int ring = 64;
-    while (ring < d.M && (size_t)ring * 2 * WC * 8 <= 96 * 1024) ring *= 2;
+    while (ring < d.M && (ring < 2 * RPT * per_pass || (size_t)ring * 2 * WC * 8 <= 64 * 1024)) ring *= 2;
     p.ring = ring;
-    int threads = d.max_node_level_width * WC;
-    threads = threads < 64 ? 64 : (threads > 1024 ? 1024 : (threads + 63) / 64 * 64);
-    const size_t lds = (size_t)ring * WC * 8 + (size_t)4 * (threads / WC) * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
-    // threads must be a multiple of WC so that a thread keeps its word: 64 | threads and WC | 64
-    auto kern = propagate_nodes<WC>;
+    size_t lds = (size_t)ring * WC * 8;
+    if (wide) lds += (size_t)4 * per_pass * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
+    else lds += (size_t)2 * WC * 8 + (size_t)4 * RPT * per_pass * 16 + (size_t)2 * (WIN_LEVELS + WIN_MARGIN) * 4;
+    if (lds > 150 * 1024) return hipErrorInvalidValue;
+    const void *kern = wide ? reinterpret_cast<const void *>(propagate_nodes_wide<WC>)
+                            : reinterpret_cast<const void *>(propagate_nodes<WC>);
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int blocks = (d.W + WC - 1) / WC;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(threads), lds, s, p);
+    if (wide)
+        hipLaunchKernelGGL(propagate_nodes_wide<WC>, dim3(blocks), dim3(threads), lds, s, p);
+    else
+        hipLaunchKernelGGL(propagate_nodes<WC>, dim3(blocks), dim3(threads), lds, s, p, d.d_chunk_end);
     return hipGetLastError();
 }
 
@@ -208,8 +385,8 @@ hipError_t launch_propagate(const Dag &d, hipStream_t s)
     if (d.n == 0 || d.W == 0) return hipSuccess;
     hipError_t e = hipSuccess;
     if (d.M > 0) {
-        if (d.W <= 1) e = launch_nodes<1>(d, s);
-        else if (d.W <= 2) e = launch_nodes<2>(d, s);
+        if (d.k1_wc == 1) e = launch_nodes<1>(d, s);
+        else if (d.k1_wc == 2) e = launch_nodes<2>(d, s);
         else e = launch_nodes<4>(d, s);
         if (e != hipSuccess) return e;
     }
