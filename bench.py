@@ -37,6 +37,9 @@ def parse() -> argparse.Namespace:
     ap.add_argument("--batch", type=int, default=0, help="override B of the preset (0 = preset's)")
     ap.add_argument("--cpu-samples", type=int, default=256, help="samples the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-deps-bench", action="store_true", help="skip the propagation timing on the stress preset")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB, the known-size "
+                         "reference that hardware byte counters of a profiler run are scaled by")
     return ap.parse_args()
 
 
@@ -153,6 +156,13 @@ def main() -> int:
                       "us_per_launch": k1_s * 1e6, "GB/s": alg_bytes / k1_s / 1e9,
                       "frac_of_hbm_peak": alg_bytes / k1_s / 1e9 / HBM_PEAK_GBS}
         hs.close()
+
+    if args.copy_probe:
+        x = torch.zeros(1 << 27, dtype=torch.float64, device="cuda")
+        y = torch.empty_like(x)
+        torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        del x, y
 
     # ---- the oracle on the host cores, bounded sample of the same workload ----
     cpu = None
