@@ -31,15 +31,47 @@ void set_error(const char *fmt, ...)
         }                                                                                    \
     } while (0)
 
-template <typename T>
-static hipError_t upload(T **dst, const std::vector<T> &src, hipStream_t s)
-{
-    *dst = nullptr;
-    if (src.empty()) return hipSuccess;
-    hipError_t e = hipMalloc((void **)dst, src.size() * sizeof(T));
-    if (e != hipSuccess) return e;
-    return hipMemcpyAsync(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, s);
-}
+// Collects host arrays (and device-only reservations) into one device block: one
+// allocation and one host-to-device copy instead of one of each per array.
+struct Packer {
+    std::vector<char> host;
+    struct Fix { void **dst; size_t off; };
+    std::vector<Fix> fixes;
+    size_t device_only = 0;
+
+    static size_t align(size_t x) { return (x + 255) & ~(size_t)255; }
+
+    template <typename T>
+    void add(T **dst, const std::vector<T> &src)
+    {
+        *dst = nullptr;
+        if (src.empty()) return;
+        const size_t off = align(host.size());
+        host.resize(off + src.size() * sizeof(T));
+        memcpy(host.data() + off, src.data(), src.size() * sizeof(T));
+        fixes.push_back({reinterpret_cast<void **>(dst), off});
+    }
+    // space after the copied part that only kernels write; call after the last add()
+    template <typename T>
+    void reserve(T **dst, size_t bytes)
+    {
+        *dst = nullptr;
+        if (!bytes) return;
+        fixes.push_back({reinterpret_cast<void **>(dst), align(host.size()) + device_only});
+        device_only += align(bytes);
+    }
+    hipError_t commit(void **block, hipStream_t s)
+    {
+        *block = nullptr;
+        const size_t total = align(host.size()) + device_only;
+        if (!total) return hipSuccess;
+        hipError_t e = hipMalloc(block, total);
+        if (e != hipSuccess) return e;
+        for (const Fix &f : fixes) *f.dst = static_cast<char *>(*block) + f.off;
+        if (host.empty()) return hipSuccess;
+        return hipMemcpyAsync(*block, host.data(), host.size(), hipMemcpyHostToDevice, s);
+    }
+};
 
 hipError_t ensure_workspace(Dag *d, size_t bytes)
 {
@@ -60,9 +92,7 @@ hipError_t ensure_workspace(Dag *d, size_t bytes)
 static void free_dag(Dag *d)
 {
     if (!d) return;
-    void *ptrs[] = {d->d_recv_of_op, d->d_nodes, d->d_ovf_idx, d->d_nlvl_ptr, d->d_src, d->d_chunk_end,
-                    d->d_dep, d->d_cls_dep, d->d_cls_depT, d->d_cls_cnt0, d->d_cls_ptr, d->d_cls_cols,
-                    d->d_run_ptr, d->d_run_lo, d->d_run_hi, d->d_cls_isum, d->d_work};
+    void *ptrs[] = {d->d_graph_block, d->d_class_block, d->d_work};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete d;
@@ -250,10 +280,11 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     HIP_TRY(hipGetDevice(&d->device));
 
     // ---- upload and propagate ----
-    HIP_TRY(upload(&d->d_recv_of_op, recv_of_op, s));
-    HIP_TRY(upload(&d->d_nodes, nodes, s));
-    HIP_TRY(upload(&d->d_ovf_idx, ovf_idx, s));
-    HIP_TRY(upload(&d->d_nlvl_ptr, nlvl_ptr, s));
+    Packer graph;
+    graph.add(&d->d_recv_of_op, recv_of_op);
+    graph.add(&d->d_nodes, nodes);
+    graph.add(&d->d_ovf_idx, ovf_idx);
+    graph.add(&d->d_nlvl_ptr, nlvl_ptr);
     {
         // words per workgroup slice, threads, and the chunks of levels of the node kernel
         // a workgroup's LDS traffic per level grows with its slice, so wide bitsets get many narrow slices
@@ -269,14 +300,13 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             chunk_end[l0] = l1;
             l0 = l1;
         }
-        HIP_TRY(upload(&d->d_chunk_end, chunk_end, s));
+        graph.add(&d->d_chunk_end, chunk_end);
     }
-    HIP_TRY(upload(&d->d_src, src, s));
+    graph.add(&d->d_src, src);
     const size_t dep_words = (size_t)n * d->W;
-    if (dep_words) {
-        HIP_TRY(hipMalloc((void **)&d->d_dep, dep_words * 8));
-        HIP_TRY(launch_propagate(*d, s));
-    }
+    graph.reserve(&d->d_dep, dep_words * 8);
+    HIP_TRY(graph.commit(&d->d_graph_block, s));
+    if (dep_words) HIP_TRY(launch_propagate(*d, s));
 
     // ---- classes of identical rows among the compute ops ----
     std::vector<uint64_t> rows((size_t)d->N * d->W);
@@ -316,23 +346,25 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         }
         run_ptr.push_back((int32_t)run_lo.size());
     }
+    Packer cls;
     if (d->R <= 1024) {   // index sums stay below 2^20
         std::vector<int32_t> isum(d->C, 0);
         for (int32_t c = 0; c < d->C; ++c)
             for (int32_t i = 0; i < d->R; ++i)
                 if ((cls_dep[(size_t)c * d->W + (i >> 6)] >> (i & 63)) & 1ull) isum[c] += i;
-        HIP_TRY(upload(&d->d_cls_isum, isum, s));
+        cls.add(&d->d_cls_isum, isum);
     }
     d->max_members = 0;
     for (int32_t c = 0; c < d->C; ++c) d->max_members = std::max(d->max_members, cls_ptr[c + 1] - cls_ptr[c]);
-    HIP_TRY(upload(&d->d_run_ptr, run_ptr, s));
-    HIP_TRY(upload(&d->d_run_lo, run_lo, s));
-    HIP_TRY(upload(&d->d_run_hi, run_hi, s));
-    HIP_TRY(upload(&d->d_cls_dep, cls_dep, s));
-    HIP_TRY(upload(&d->d_cls_depT, depT, s));
-    HIP_TRY(upload(&d->d_cls_cnt0, cnt0, s));
-    HIP_TRY(upload(&d->d_cls_ptr, cls_ptr, s));
-    HIP_TRY(upload(&d->d_cls_cols, cls_cols, s));
+    cls.add(&d->d_run_ptr, run_ptr);
+    cls.add(&d->d_run_lo, run_lo);
+    cls.add(&d->d_run_hi, run_hi);
+    cls.add(&d->d_cls_dep, cls_dep);
+    cls.add(&d->d_cls_depT, depT);
+    cls.add(&d->d_cls_cnt0, cnt0);
+    cls.add(&d->d_cls_ptr, cls_ptr);
+    cls.add(&d->d_cls_cols, cls_cols);
+    HIP_TRY(cls.commit(&d->d_class_block, s));
     HIP_TRY(hipStreamSynchronize(s));   // host vectors go out of scope; the handle is complete
     return TICTAC_OK;
 }

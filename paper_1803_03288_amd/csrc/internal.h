@@ -62,6 +62,8 @@ struct Dag {
     int32_t max_members = 0;        // largest class (ops)
 
     // scratch owned by the handle (grown on demand, stream-ordered use)
+    // the two allocations that hold every array above (graph tables + dep; class tables)
+    void *d_graph_block = nullptr, *d_class_block = nullptr;
     void *d_work = nullptr;
     size_t work_bytes = 0;
 };
