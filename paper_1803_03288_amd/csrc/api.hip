@@ -364,6 +364,10 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     cls.add(&d->d_cls_cnt0, cnt0);
     cls.add(&d->d_cls_ptr, cls_ptr);
     cls.add(&d->d_cls_cols, cls_cols);
+    std::vector<int32_t> col_cls(d->N, 0);
+    for (int32_t c = 0; c < d->C; ++c)
+        for (int32_t m = cls_ptr[c]; m < cls_ptr[c + 1]; ++m) col_cls[cls_cols[m]] = c;
+    cls.add(&d->d_col_cls, col_cls);
     HIP_TRY(cls.commit(&d->d_class_block, s));
     HIP_TRY(hipStreamSynchronize(s));   // host vectors go out of scope; the handle is complete
     return TICTAC_OK;

@@ -55,6 +55,7 @@ struct Dag {
     int32_t *d_cls_isum = nullptr;  // [C]   sum of the recv indices in dep of the class (R <= 1024 only)
     int32_t *d_cls_ptr = nullptr;   // [C+1] members of class c: cls_cols[cls_ptr[c] .. cls_ptr[c+1])
     int32_t *d_cls_cols = nullptr;  // [N]   op_time columns, grouped by class
+    int32_t *d_col_cls = nullptr;   // [N]   class of every op_time column
     // every class row as runs of consecutive recv indices [lo, hi): row c = runs run_ptr[c] .. run_ptr[c+1])
     int32_t *d_run_ptr = nullptr;   // [C+1]
     int32_t *d_run_lo = nullptr;    // [n_runs]

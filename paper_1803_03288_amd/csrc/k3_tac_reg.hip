@@ -16,10 +16,16 @@
 //     outstanding recv of the class, to whose P the class time is then added;
 //   * Q is tracked by its size and the sum of its members (one member: the sum is the
 //     member, the common case on layered models); the bitsets of outstanding recvs and of
-//     Q are spread over the lanes (bit j of lane l stands for recv 64 j + l) and are only
-//     gathered by ballots on the paths that need them;
-//   * M of a class is initialised from prefix sums T of the transfer times: the sum over the
-//     runs [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo];
+//     Q are spread over the lanes (bits j and 16 + j of lane l stand for recv 64 j + l) and
+//     are only gathered by ballots on the paths that need them;
+//   * M of a class is needed only when Q is empty or the comparator ties.  It is formed at the
+//     first such round from prefix sums T of the transfer times (the sum over the runs
+//     [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo]) and brought up to date
+//     from the order built so far; rounds that do not need it do not touch it;
+//   * the class totals of a sample are formed by one coalesced pass over its op_time row,
+//     each column adding itself to its class's total in LDS;
+//   * the order is collected in a register (one lane per step) and written to LDS once per
+//     64 steps, or when a path needs it;
 //   * the last step at which a class's count is decremented is its release position kappa; after the
 //     loop the class times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
 //     the end of the k-th transfer, S_k the time of the classes with kappa >= k (the closed
@@ -42,6 +48,7 @@ struct TacRegParams {
     const int32_t *cls_isum;    // [C]   sum of the recv indices of the row
     const int32_t *cls_ptr;     // [C+1]
     const int32_t *cls_cols;    // [N]
+    const int32_t *col_cls;     // [N]   class of every op_time column; NULL: gather by member lists
     const int32_t *run_ptr;     // [C+1]
     const int32_t *run_lo, *run_hi;
     const double *op_time, *recv_time;
@@ -82,7 +89,7 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
 // class slots 0..7; a slot beyond KT compiles to nothing.
 #define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
-template <int KT, bool STAGE>
+template <int KT>
 __global__ void __launch_bounds__(64 * kRegWaves, (KT <= 3 ? 6 : (KT <= 4 ? 5 : 2)))
 tac_reg_kernel(const TacRegParams p)
 {
@@ -99,8 +106,6 @@ tac_reg_kernel(const TacRegParams p)
     double *A = P + (R + 1);                // [R+1]  class time by release position
     int32_t *ordl = reinterpret_cast<int32_t *>(A + (R + 1));       // [R] order built so far
     uint32_t *aliveh = reinterpret_cast<uint32_t *>(ordl + R);      // [2W] outstanding recvs
-    uint32_t *Qh = aliveh + 2 * W;                                  // [2W] spare
-    double *X = reinterpret_cast<double *>(Qh + 2 * W + ((R + 4 * W) & 1));   // [N] op_time row (STAGE)
 
     for (int idx = threadIdx.x; idx < 2 * W * 64 * KT; idx += blockDim.x) {
         const int h = idx / (64 * KT), rem = idx % (64 * KT);
@@ -123,78 +128,136 @@ tac_reg_kernel(const TacRegParams p)
     }
     TT_EACH_K(TT_INIT_CONST)
 
+    const uint32_t *rows_lane = rows + lane * KT;      // this lane's KT words of half-row 0
+    double *csum = P;                                  // [64 KT] class totals while they are summed (spans P and A)
+
     const int gwave = blockIdx.x * kRegWaves + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
         const double *rt = p.recv_time + (size_t)b * R;
         const double *ot = p.op_time + (size_t)b * N;
         wave_sync();                        // LDS of the previous sample is no longer read
 
-        // ---- a. transfer times, their prefix sums T (in P), the op_time row ----
+        // ---- a. transfer times ----
         bool zero_seen = false;
-        double carry = 0.0;
-        for (int base = 0; base < R; base += 64) {
-            const int r = base + lane;
-            const double x = r < R ? rt[r] : 0.0;
-            if (r < R) { t[r] = x; zero_seen |= !(x > 0.0); }
-            const double inc = wave_incl_scan_f64(x);
-            if (r < R) P[r + 1] = carry + inc;
-            carry += __shfl(inc, 63);
+        for (int r = lane; r < R; r += 64) {
+            const double x = rt[r];
+            t[r] = x;
+            zero_seen |= !(x > 0.0);
         }
-        if (lane == 0) P[0] = 0.0;
         const bool skip = __ballot(zero_seen) != 0ull;
         if (lane == 0) p.flags[b] = skip ? 1 : 0;
         if (skip) continue;
-        if (STAGE)
-            for (int j = lane; j < N; j += 64) X[j] = ot[j];
-        wave_sync();
 
-        // ---- b. class totals and initial M ----
+        // ---- b. class totals ----
 #define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, kap_##k = 0, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
         TT_EACH_K(TT_DECL_STATE)
         double ct_sum = 0.0;
+        if (p.col_cls) {
+            // the row is read once, coalesced; every column adds itself to the total of its class
+            for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
+            wave_sync();
+            _Pragma("unroll 4")
+            for (int j = lane; j < N; j += 64) atomicAdd(&csum[p.col_cls[j]], ot[j]);
+            wave_sync();
+#define TT_READ_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; ct_sum += ct_##k; }
+            TT_EACH_K(TT_READ_TOTAL)
+            wave_sync();
+        } else {
+#define TT_GATHER_TOTAL(k)                                                                \
+            if constexpr (k < KT) {                                                       \
+                const int c = k * 64 + lane;                                              \
+                double s = 0.0;                                                           \
+                if (c < C) {                                                              \
+                    const int mbeg = p.cls_ptr[c], mcnt = p.cls_ptr[c + 1] - mbeg;        \
+                    _Pragma("unroll 4")                                                   \
+                    for (int m = 0; m < mmax_##k; ++m)                                    \
+                        if (m < mcnt) s += ot[p.cls_cols[mbeg + m]];                      \
+                }                                                                         \
+                ct_##k = s;                                                               \
+                ct_sum += s;                                                              \
+            }
+            TT_EACH_K(TT_GATHER_TOTAL)
+        }
 #define TT_INIT_STATE(k)                                                                  \
         if constexpr (k < KT) {                                                           \
             const int c = k * 64 + lane;                                                  \
-            double s = 0.0, Mk = 0.0;                                                     \
-            if (c < C) {                                                                  \
-                const int mbeg = p.cls_ptr[c], mcnt = p.cls_ptr[c + 1] - mbeg;            \
-                _Pragma("unroll 4")                                                       \
-                for (int m = 0; m < mmax_##k; ++m)                                        \
-                    if (m < mcnt) {                                                       \
-                        const int col = p.cls_cols[mbeg + m];                             \
-                        s += STAGE ? X[col] : ot[col];                                    \
-                    }                                                                     \
-                const int rend = p.run_ptr[c + 1];                                        \
-                for (int q = p.run_ptr[c]; q < rend; ++q) Mk += P[p.run_hi[q]] - P[p.run_lo[q]]; \
-                pk_##k = (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c];                      \
-            }                                                                             \
-            ct_##k = s; M_##k = Mk;                                                       \
-            ct_sum += s;                                                                  \
+            if (c < C) pk_##k = (p.cls_cnt0[c] - 2) * CNT1 + p.cls_isum[c];               \
         }
         TT_EACH_K(TT_INIT_STATE)
-        wave_sync();                        // T and the staged row are consumed
 
-        // ---- c. P, A, the bitsets of outstanding recvs and of Q ----
+        // ---- c. P, the bitsets of outstanding recvs and of Q ----
         for (int r = lane; r < R; r += 64) P[r] = 0.0;
-        if (p.simulate)
-            for (int j = lane; j <= R; j += 64) A[j] = 0.0;
-        uint32_t alive_l = 0;               // bit j: recv 64 j + lane is outstanding
-        for (int j = 0; j * 64 + lane < R; ++j) alive_l |= 1u << j;
+        // bit j: recv 64 j + lane is outstanding; bit 16 + j: it is a member of Q
+        uint32_t sets_l = 0;
+        for (int j = 0; j * 64 + lane < R; ++j) sets_l |= 1u << j;
         wave_sync();
         int qcount = 0, qsum = 0;           // size of Q and sum of its members (wave-uniform)
+        int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
+        int ord_reg = 0;                    // lane i: the recv selected at step (step & ~63) + i
 
         // outstanding recvs as 32-bit halves in LDS, for the rare paths that need them by index
         auto publish_alive = [&]() {
             for (int j = 0; j < W; ++j) {
-                const uint64_t m = __ballot((alive_l >> j) & 1u);
+                const uint64_t m = __ballot((sets_l >> j) & 1u);
                 if (lane == 0) { aliveh[2 * j] = (uint32_t)m; aliveh[2 * j + 1] = (uint32_t)(m >> 32); }
             }
             wave_sync();
         };
 
+        // M of the classes is only needed when Q is empty or the comparator ties, so its
+        // updates are deferred: formed from prefix sums T of the transfer times (the sum over
+        // the runs [lo, hi) of consecutive recv indices of a row of T[hi] - T[lo]; T sits in A,
+        // which is free until the loop ends) and then brought up to `upto` by the
+        // subtractions of the rounds since m_sync, in their order.  ordl holds those rounds.
+#define TT_M_FORM(k)                                                                      \
+        if constexpr (k < KT) {                                                           \
+            const int c = k * 64 + lane;                                                  \
+            double Mk = 0.0;                                                              \
+            if (c < C) {                                                                  \
+                const int rend = p.run_ptr[c + 1];                                        \
+                for (int q = p.run_ptr[c]; q < rend; ++q) Mk += A[p.run_hi[q]] - A[p.run_lo[q]]; \
+            }                                                                             \
+            M_##k = Mk;                                                                   \
+        }
+#define TT_M_SUB(k)                                                                       \
+        if constexpr (k < KT) {                                                           \
+            const int m_ = __builtin_amdgcn_sbfe(rbm[k], shm, 1);                         \
+            M_##k -= __hiloint2double(thi & m_, tlo & m_);                                \
+        }
+#define TT_ENSURE_M(upto)                                                                 \
+        {                                                                                 \
+            if (m_sync < 0) {                                                             \
+                double carry = 0.0;                                                       \
+                for (int base = 0; base < R; base += 64) {                                \
+                    const int r = base + lane;                                            \
+                    const double x = r < R ? t[r] : 0.0;                                  \
+                    const double inc = wave_incl_scan_f64(x);                             \
+                    if (r < R) A[r + 1] = carry + inc;                                    \
+                    carry += __shfl(inc, 63);                                             \
+                }                                                                         \
+                if (lane == 0) A[0] = 0.0;                                                \
+                wave_sync();                                                              \
+                TT_EACH_K(TT_M_FORM)                                                      \
+                m_sync = 0;                                                               \
+            }                                                                             \
+            for (int s0 = m_sync; s0 < (upto); s0 += 64) {                                \
+                const int n_ = min(64, (upto) - s0);                                      \
+                const int r_l = lane < n_ ? ordl[s0 + lane] : 0;                          \
+                const double t_l = t[r_l];                                                \
+                for (int i = 0; i < n_; ++i) {                                            \
+                    const int r_ = __builtin_amdgcn_readlane(r_l, i);                     \
+                    const int tlo = __builtin_amdgcn_readlane(__double2loint(t_l), i);    \
+                    const int thi = __builtin_amdgcn_readlane(__double2hiint(t_l), i);    \
+                    const uint32_t *rbm = rows_lane + (r_ >> 5) * (64 * KT);              \
+                    const int shm = r_ & 31;                                              \
+                    TT_EACH_K(TT_M_SUB)                                                   \
+                }                                                                         \
+            }                                                                             \
+            m_sync = (upto);                                                              \
+        }
+
         // A class with one outstanding recv left: its time goes to P of that recv, which joins Q
-        // when that time is positive.  inq_l mirrors alive_l for membership in Q.
-        uint32_t inq_l = 0;
+        // when that time is positive.
 #define TT_TO_P(k, hit1)                                                                  \
         {                                                                                 \
             if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
@@ -203,10 +266,10 @@ tac_reg_kernel(const TacRegParams p)
                 const int l = __builtin_ctzll(nm);                                        \
                 nm &= nm - 1;                                                             \
                 const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
-                const uint32_t had = (__builtin_amdgcn_readlane(inq_l, sole & 63) >> (sole >> 6)) & 1u; \
+                const uint32_t had = (__builtin_amdgcn_readlane(sets_l, sole & 63) >> (16 + (sole >> 6))) & 1u; \
                 qcount += 1 - (int)had;                                                   \
                 qsum += had ? 0 : sole;                                                   \
-                inq_l |= (uint32_t)(lane == (sole & 63)) << (sole >> 6);                  \
+                sets_l |= (uint32_t)(lane == (sole & 63)) << (16 + (sole >> 6));          \
             }                                                                             \
         }
 #define TT_INIT_P(k)                                                                      \
@@ -217,104 +280,103 @@ tac_reg_kernel(const TacRegParams p)
         TT_EACH_K(TT_INIT_P)
 
         // ---- d. selection loop ----
-        double F = 0.0;
         for (int step = 0; step < R; ++step) {
             qcount = __builtin_amdgcn_readfirstlane(qcount);
             qsum = __builtin_amdgcn_readfirstlane(qsum);
-            int best;
-            if (qcount == 1) {
-                best = qsum;
-            } else if (qcount == 0) {
-                // every outstanding recv has P = 0: lowest index among those of minimal M+
-                publish_alive();
-                double lmin = TT_INF;
-#define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
-                TT_EACH_K(TT_LMIN)
-                const double g = wave_min_f64(lmin);
-                int cand = INT32_MAX;
-                if (g != TT_INF) {
-#define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
-                    TT_EACH_K(TT_CAND)
-                }
-                best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
-                if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
-                    for (int h = 2 * W - 1; h >= 0; --h) {
-                        const uint32_t x = aliveh[h];
-                        if (x) best = h * 32 + __builtin_ctz(x);
-                    }
-                }
-            } else {
-                // ascending scan over Q with the comparator
-                double mp_best = -1.0;
-                best = -1;
+            int best = qsum;                // |Q| = 1: its member precedes every recv with P = 0
+            if (qcount != 1) {
+                // the steps of the current block of 64 so far, for the paths that read ordl
+                if (lane < (step & 63)) ordl[(step & ~63) + lane] = ord_reg;
                 wave_sync();
-                for (int j = 0; j < W; ++j) {
-                    uint64_t x = __ballot((inq_l >> j) & 1u);
-                    while (x) {
-                        const int a = j * 64 + __builtin_ctzll(x);
-                        x &= x - 1;
-                        if (best < 0) { best = a; continue; }
-                        const double xa = fmin(P[best], t[a]);
-                        const double ya = fmin(P[a], t[best]);
-                        bool prec;
-                        double mp_a = -1.0;
-                        if (xa != ya) {
-                            prec = xa < ya;
-                        } else {
-                            double v = TT_INF, u = TT_INF;
-#define TT_MPLUS(k)                                                                       \
-                            if constexpr (k < KT) {                                       \
-                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
-                                const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
-                                if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);         \
-                                if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);        \
-                            }
-                            TT_EACH_K(TT_MPLUS)
-                            mp_a = wave_min_f64(v);
-                            if (mp_best < 0.0) mp_best = wave_min_f64(u);
-                            prec = mp_a < mp_best;
+                if (qcount == 0) {
+                    // every outstanding recv has P = 0: lowest index among those of minimal M+
+                    TT_ENSURE_M(step)
+                    publish_alive();
+                    double lmin = TT_INF;
+#define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
+                    TT_EACH_K(TT_LMIN)
+                    const double g = wave_min_f64(lmin);
+                    int cand = INT32_MAX;
+                    if (g != TT_INF) {
+#define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
+                        TT_EACH_K(TT_CAND)
+                    }
+                    best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
+                    if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
+                        for (int h = 2 * W - 1; h >= 0; --h) {
+                            const uint32_t x = aliveh[h];
+                            if (x) best = h * 32 + __builtin_ctz(x);
                         }
-                        if (prec) { best = a; mp_best = mp_a; }
+                    }
+                } else {
+                    // ascending scan over Q with the comparator
+                    double mp_best = -1.0;
+                    best = -1;
+                    for (int j = 0; j < W; ++j) {
+                        uint64_t x = __ballot((sets_l >> (16 + j)) & 1u);
+                        while (x) {
+                            const int a = j * 64 + __builtin_ctzll(x);
+                            x &= x - 1;
+                            if (best < 0) { best = a; continue; }
+                            const double xa = fmin(P[best], t[a]);
+                            const double ya = fmin(P[a], t[best]);
+                            bool prec;
+                            double mp_a = -1.0;
+                            if (xa != ya) {
+                                prec = xa < ya;
+                            } else {
+                                TT_ENSURE_M(step)
+                                double v = TT_INF, u = TT_INF;
+#define TT_MPLUS(k)                                                                       \
+                                if constexpr (k < KT) {                                   \
+                                    const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
+                                    const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
+                                    if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);     \
+                                    if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);    \
+                                }
+                                TT_EACH_K(TT_MPLUS)
+                                mp_a = wave_min_f64(v);
+                                if (mp_best < 0.0) mp_best = wave_min_f64(u);
+                                prec = mp_a < mp_best;
+                            }
+                            if (prec) { best = a; mp_best = mp_a; }
+                        }
                     }
                 }
+                best = __builtin_amdgcn_readfirstlane(best);
             }
-            best = __builtin_amdgcn_readfirstlane(best);
-            const double tb = t[best];
-            F += tb;
-            ordl[step] = best;                  // every lane writes the same value
+            ord_reg = lane == (step & 63) ? best : ord_reg;
+            if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;
             const int fq = qcount > 0 ? 1 : 0;  // the selected recv is a member of Q whenever Q is not empty
             qcount -= fq;
             qsum -= fq ? best : 0;
-            const uint32_t gone = ~((uint32_t)(lane == (best & 63)) << (best >> 6));
-            alive_l &= gone;
-            inq_l &= gone;
+            if (lane == (best & 63)) sets_l &= ~(0x10001u << (best >> 6));
 
             // ---- incremental property update, straight-line per class ----
-            const uint32_t *rb = rows + ((best >> 5) * 64 + lane) * KT;
+            const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);
             const int sh = best & 31;
             const int delta = CNT1 + best;
             const int step1 = step + 1;
-            const int tb_lo = __double2loint(tb), tb_hi = __double2hiint(tb);
-            uint32_t hacc = 0xffffffffu;
+            uint32_t hmax = 0;
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
                 pk_##k -= mk_##k & delta;                                                 \
-                M_##k -= __hiloint2double(tb_hi & mk_##k, tb_lo & mk_##k);                \
                 kap_##k = (kap_##k & ~mk_##k) | (step1 & mk_##k);  /* last decrement = release */ \
-                hacc = min(hacc, (uint32_t)((pk_##k & mk_##k) + CNT1));  /* < CNT1: count fell to 1 */ \
+                hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
             TT_EACH_K(TT_UPDATE)
-            if (__ballot(hacc < (uint32_t)CNT1) == 0ull) continue;
+            if (__ballot(hmax >= (uint32_t)-CNT1) == 0ull) continue;
 
             // ---- some class fell to one outstanding recv ----
 #define TT_EVENT(k)                                                                       \
             if constexpr (k < KT) {                                                       \
-                const bool hit1 = (uint32_t)((pk_##k & mk_##k) + CNT1) < (uint32_t)CNT1;  \
+                const bool hit1 = (uint32_t)(pk_##k & mk_##k) >= (uint32_t)-CNT1;         \
                 if (__ballot(hit1) != 0ull) TT_TO_P(k, hit1)                              \
             }
             TT_EACH_K(TT_EVENT)
         }
+        if ((R & 63) && lane < (R & 63)) ordl[(R & ~63) + lane] = ord_reg;
         wave_sync();
 
         // ---- e. outputs ----
@@ -326,6 +388,8 @@ tac_reg_kernel(const TacRegParams p)
         if (p.simulate) {
             // A[k] = time of the classes released after k transfers; F_k = end of the k-th transfer;
             // makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
+            for (int j = lane; j <= R; j += 64) A[j] = 0.0;
+            wave_sync();
 #define TT_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); }
             TT_EACH_K(TT_RELEASE)
             // F_k into P[k - 1] (P is free now): prefix sums of the transfer times in TAC order
@@ -337,6 +401,7 @@ tac_reg_kernel(const TacRegParams p)
                 if (s < R) P[s] = fc + inc;
                 fc += __shfl(inc, 63);
             }
+            const double F = fc;
             wave_sync();
             const double sum_c = wave_sum_f64(ct_sum);
             double sfx = 0.0, mloc = sum_c;               // k = 0: F_0 + S_0 = all class time
@@ -365,30 +430,22 @@ tac_reg_kernel(const TacRegParams p)
 template <int KT>
 static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
 {
-    // LDS: shared rows + per wave t [R], P [R+1], A [R+1], ordl [R] i32, two bitsets [2W] u32, row [N]
+    // LDS: shared rows + per wave t [R], P [R+1], A [R+1], ordl [R] i32, outstanding set [2W] u32
     const size_t rows_doubles = ((size_t)2 * d.W * 64 * KT + 1) / 2;
-    const size_t wave_fixed = (size_t)d.R + 2 * (d.R + 1) + ((size_t)d.R + 4 * d.W + 1) / 2 + 1;
-    size_t per_wave = wave_fixed + d.N;
-    bool stage = true;
-    auto lds_of = [&](size_t pw) { return (rows_doubles + pw * kRegWaves) * 8; };
-    // stage the op_time row only while six workgroups (24 waves) still fit a compute unit
-    if (lds_of(per_wave) > (160 * 1024) / 6) { stage = false; per_wave = wave_fixed; }
-    const size_t lds = lds_of(per_wave);
+    const size_t per_wave = (size_t)d.R + 2 * (d.R + 1) + ((size_t)d.R + 2 * d.W + 1) / 2 + 1;
+    const size_t lds = (rows_doubles + per_wave * kRegWaves) * 8;
     if (lds > 80 * 1024) return hipErrorNotSupported;
     p.wave_doubles = (int32_t)per_wave;
+    // the class totals are summed in the space of P and A when that holds one double per class slot
+    p.col_cls = (size_t)64 * KT <= 2 * ((size_t)d.R + 1) ? d.d_col_cls : nullptr;
     int per_cu = 0;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = stage ? hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                  : hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT, false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    if (stage)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT, true>, 64 * kRegWaves, lds);
-    else
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT, false>, 64 * kRegWaves, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT>, 64 * kRegWaves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
     int n_cu = 256;
@@ -399,10 +456,7 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
     const int need = (p.B + kRegWaves - 1) / kRegWaves;
     if (grid > need) grid = need;
     p.n_waves = grid * kRegWaves;
-    if (stage)
-        hipLaunchKernelGGL((tac_reg_kernel<KT, true>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
-    else
-        hipLaunchKernelGGL((tac_reg_kernel<KT, false>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
+    hipLaunchKernelGGL((tac_reg_kernel<KT>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
     return hipGetLastError();
 }
 
