@@ -280,84 +280,9 @@ tac_reg_kernel(const TacRegParams p)
         TT_EACH_K(TT_INIT_P)
 
         // ---- d. selection loop ----
-        for (int step = 0; step < R; ++step) {
-            qcount = __builtin_amdgcn_readfirstlane(qcount);
-            qsum = __builtin_amdgcn_readfirstlane(qsum);
-            int best = qsum;                // |Q| = 1: its member precedes every recv with P = 0
-            if (qcount != 1) {
-                // the steps of the current block of 64 so far, for the paths that read ordl
-                if (lane < (step & 63)) ordl[(step & ~63) + lane] = ord_reg;
-                wave_sync();
-                if (qcount == 0) {
-                    // every outstanding recv has P = 0: lowest index among those of minimal M+
-                    TT_ENSURE_M(step)
-                    publish_alive();
-                    double lmin = TT_INF;
-#define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
-                    TT_EACH_K(TT_LMIN)
-                    const double g = wave_min_f64(lmin);
-                    int cand = INT32_MAX;
-                    if (g != TT_INF) {
-#define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
-                        TT_EACH_K(TT_CAND)
-                    }
-                    best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
-                    if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
-                        for (int h = 2 * W - 1; h >= 0; --h) {
-                            const uint32_t x = aliveh[h];
-                            if (x) best = h * 32 + __builtin_ctz(x);
-                        }
-                    }
-                } else {
-                    // ascending scan over Q with the comparator
-                    double mp_best = -1.0;
-                    best = -1;
-                    for (int j = 0; j < W; ++j) {
-                        uint64_t x = __ballot((sets_l >> (16 + j)) & 1u);
-                        while (x) {
-                            const int a = j * 64 + __builtin_ctzll(x);
-                            x &= x - 1;
-                            if (best < 0) { best = a; continue; }
-                            const double xa = fmin(P[best], t[a]);
-                            const double ya = fmin(P[a], t[best]);
-                            bool prec;
-                            double mp_a = -1.0;
-                            if (xa != ya) {
-                                prec = xa < ya;
-                            } else {
-                                TT_ENSURE_M(step)
-                                double v = TT_INF, u = TT_INF;
-#define TT_MPLUS(k)                                                                       \
-                                if constexpr (k < KT) {                                   \
-                                    const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
-                                    const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
-                                    if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);     \
-                                    if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);    \
-                                }
-                                TT_EACH_K(TT_MPLUS)
-                                mp_a = wave_min_f64(v);
-                                if (mp_best < 0.0) mp_best = wave_min_f64(u);
-                                prec = mp_a < mp_best;
-                            }
-                            if (prec) { best = a; mp_best = mp_a; }
-                        }
-                    }
-                }
-                best = __builtin_amdgcn_readfirstlane(best);
-            }
-            ord_reg = lane == (step & 63) ? best : ord_reg;
-            if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;
-            const int fq = qcount > 0 ? 1 : 0;  // the selected recv is a member of Q whenever Q is not empty
-            qcount -= fq;
-            qsum -= fq ? best : 0;
-            if (lane == (best & 63)) sets_l &= ~(0x10001u << (best >> 6));
-
-            // ---- incremental property update, straight-line per class ----
-            const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);
-            const int sh = best & 31;
-            const int delta = CNT1 + best;
-            const int step1 = step + 1;
-            uint32_t hmax = 0;
+        // What a round does once `best` is chosen: record it, take it out of the sets, and the
+        // straight-line incremental update of every class; then, where a class fell to one
+        // outstanding recv, that class's time goes to P of that recv.
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
@@ -365,16 +290,103 @@ tac_reg_kernel(const TacRegParams p)
                 kap_##k = (kap_##k & ~mk_##k) | (step1 & mk_##k);  /* last decrement = release */ \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
-            TT_EACH_K(TT_UPDATE)
-            if (__ballot(hmax >= (uint32_t)-CNT1) == 0ull) continue;
-
-            // ---- some class fell to one outstanding recv ----
 #define TT_EVENT(k)                                                                       \
             if constexpr (k < KT) {                                                       \
                 const bool hit1 = (uint32_t)(pk_##k & mk_##k) >= (uint32_t)-CNT1;         \
                 if (__ballot(hit1) != 0ull) TT_TO_P(k, hit1)                              \
             }
-            TT_EACH_K(TT_EVENT)
+#define TT_APPLY()                                                                        \
+            {                                                                             \
+                ord_reg = lane == (step & 63) ? best : ord_reg;                           \
+                if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;                  \
+                const int fq = qcount > 0 ? 1 : 0;  /* best is a member of Q whenever Q is not empty */ \
+                qcount -= fq;                                                             \
+                qsum -= fq ? best : 0;                                                    \
+                if (lane == (best & 63)) sets_l &= ~(0x10001u << (best >> 6));            \
+                const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
+                const int sh = best & 31;                                                 \
+                const int delta = CNT1 + best;                                            \
+                const int step1 = step + 1;                                               \
+                uint32_t hmax = 0;                                                        \
+                TT_EACH_K(TT_UPDATE)                                                      \
+                if (__ballot(hmax >= (uint32_t)-CNT1) != 0ull) { TT_EACH_K(TT_EVENT) }    \
+                ++step;                                                                   \
+                qcount = __builtin_amdgcn_readfirstlane(qcount);                          \
+                qsum = __builtin_amdgcn_readfirstlane(qsum);                              \
+            }
+        int step = 0;
+        qcount = __builtin_amdgcn_readfirstlane(qcount);
+        qsum = __builtin_amdgcn_readfirstlane(qsum);
+        while (step < R) {
+            // |Q| = 1: its member precedes every recv with P = 0.  These rounds form the inner
+            // loop; M of the classes is not touched in it.
+            while (qcount == 1) {
+                const int best = qsum;
+                TT_APPLY()
+            }
+            if (step >= R) break;
+            int best;
+            // the steps of the current block of 64 so far, for the paths that read ordl
+            if (lane < (step & 63)) ordl[(step & ~63) + lane] = ord_reg;
+            wave_sync();
+            m_sync = __builtin_amdgcn_readfirstlane(m_sync);
+            if (qcount == 0) {
+                // every outstanding recv has P = 0: lowest index among those of minimal M+
+                TT_ENSURE_M(step)
+                publish_alive();
+                double lmin = TT_INF;
+#define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
+                TT_EACH_K(TT_LMIN)
+                const double g = wave_min_f64(lmin);
+                int cand = INT32_MAX;
+                if (g != TT_INF) {
+#define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
+                    TT_EACH_K(TT_CAND)
+                }
+                best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
+                if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
+                    for (int h = 2 * W - 1; h >= 0; --h) {
+                        const uint32_t x = aliveh[h];
+                        if (x) best = h * 32 + __builtin_ctz(x);
+                    }
+                }
+            } else {
+                // ascending scan over Q with the comparator
+                double mp_best = -1.0;
+                best = -1;
+                for (int j = 0; j < W; ++j) {
+                    uint64_t x = __ballot((sets_l >> (16 + j)) & 1u);
+                    while (x) {
+                        const int a = j * 64 + __builtin_ctzll(x);
+                        x &= x - 1;
+                        if (best < 0) { best = a; continue; }
+                        const double xa = fmin(P[best], t[a]);
+                        const double ya = fmin(P[a], t[best]);
+                        bool prec;
+                        double mp_a = -1.0;
+                        if (xa != ya) {
+                            prec = xa < ya;
+                        } else {
+                            TT_ENSURE_M(step)
+                            double v = TT_INF, u = TT_INF;
+#define TT_MPLUS(k)                                                                       \
+                            if constexpr (k < KT) {                                   \
+                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
+                                const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
+                                if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);     \
+                                if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);    \
+                            }
+                            TT_EACH_K(TT_MPLUS)
+                            mp_a = wave_min_f64(v);
+                            if (mp_best < 0.0) mp_best = wave_min_f64(u);
+                            prec = mp_a < mp_best;
+                        }
+                        if (prec) { best = a; mp_best = mp_a; }
+                    }
+                }
+            }
+            best = __builtin_amdgcn_readfirstlane(best);
+            TT_APPLY()
         }
         if ((R & 63) && lane < (R & 63)) ordl[(R & ~63) + lane] = ord_reg;
         wave_sync();
