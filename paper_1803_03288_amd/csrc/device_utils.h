@@ -56,6 +56,20 @@ __device__ __forceinline__ int wave_min_i32(int v)
     return v;
 }
 
+__device__ __forceinline__ int wave_max_i32(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
 // Block-wide reductions; every thread of the block must call them (uniform control
 // flow).  `red` is LDS scratch of at least BS/64 elements of the reduced type; two
 // barriers make it reusable right after the call.

@@ -187,19 +187,26 @@ tac_reg_kernel(const TacRegParams p)
 
         // ---- c. P, the bitsets of outstanding recvs and of Q ----
         for (int r = lane; r < R; r += 64) P[r] = 0.0;
-        // bit j: recv 64 j + lane is outstanding; bit 16 + j: it is a member of Q
-        uint32_t sets_l = 0;
-        for (int j = 0; j * 64 + lane < R; ++j) sets_l |= 1u << j;
         wave_sync();
-        int qcount = 0, qsum = 0;           // size of Q and sum of its members (wave-uniform)
+        // A class with exactly one outstanding recv left and a positive time "points" at that
+        // recv; Q is the set of recvs pointed at (they are the recvs with P > 0, P of a recv
+        // being reset when it is selected).  Tracked wave-uniformly: the number of pointers, the
+        // sum and the sum of squares of their targets, and the target of the latest one.
+        int qm = 0, qs = 0, qq = 0, qlast = 0;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
         int ord_reg = 0;                    // lane i: the recv selected at step (step & ~63) + i
 
-        // outstanding recvs as 32-bit halves in LDS, for the rare paths that need them by index
-        auto publish_alive = [&]() {
-            for (int j = 0; j < W; ++j) {
-                const uint64_t m = __ballot((sets_l >> j) & 1u);
-                if (lane == 0) { aliveh[2 * j] = (uint32_t)m; aliveh[2 * j + 1] = (uint32_t)(m >> 32); }
+        // outstanding recvs as 32-bit halves in LDS, rebuilt from the order so far on the rare
+        // path that needs them by index
+        auto publish_alive = [&](int upto) {
+            for (int h = lane; h < 2 * W; h += 64) {
+                const int nbits = min(32, max(0, R - 32 * h));
+                aliveh[h] = nbits >= 32 ? 0xffffffffu : ((1u << nbits) - 1u);
+            }
+            wave_sync();
+            for (int s_ = lane; s_ < upto; s_ += 64) {
+                const int r_ = ordl[s_];
+                atomicAnd(&aliveh[r_ >> 5], ~(1u << (r_ & 31)));
             }
             wave_sync();
         };
@@ -256,8 +263,8 @@ tac_reg_kernel(const TacRegParams p)
             m_sync = (upto);                                                              \
         }
 
-        // A class with one outstanding recv left: its time goes to P of that recv, which joins Q
-        // when that time is positive.
+        // A class that fell to one outstanding recv: its time goes to P of that recv, and with a
+        // positive time it becomes a pointer.
 #define TT_TO_P(k, hit1)                                                                  \
         {                                                                                 \
             if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
@@ -266,10 +273,10 @@ tac_reg_kernel(const TacRegParams p)
                 const int l = __builtin_ctzll(nm);                                        \
                 nm &= nm - 1;                                                             \
                 const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
-                const uint32_t had = (__builtin_amdgcn_readlane(sets_l, sole & 63) >> (16 + (sole >> 6))) & 1u; \
-                qcount += 1 - (int)had;                                                   \
-                qsum += had ? 0 : sole;                                                   \
-                sets_l |= (uint32_t)(lane == (sole & 63)) << (16 + (sole >> 6));          \
+                qm += 1;                                                                  \
+                qs += sole;                                                               \
+                qq += sole * sole;                                                        \
+                qlast = sole;                                                             \
             }                                                                             \
         }
 #define TT_INIT_P(k)                                                                      \
@@ -280,13 +287,13 @@ tac_reg_kernel(const TacRegParams p)
         TT_EACH_K(TT_INIT_P)
 
         // ---- d. selection loop ----
-        // What a round does once `best` is chosen: record it, take it out of the sets, and the
-        // straight-line incremental update of every class; then, where a class fell to one
-        // outstanding recv, that class's time goes to P of that recv.
+        // What a round does once `best` is chosen: record it, reset its P, and the straight-line
+        // incremental update of every class; then, where a class fell to one outstanding recv,
+        // that class's time goes to P of that recv.
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
-                pk_##k -= mk_##k & delta;                                                 \
+                pk_##k += __mul24(mk_##k, delta);                                         \
                 kap_##k = (kap_##k & ~mk_##k) | (step1 & mk_##k);  /* last decrement = release */ \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
@@ -299,10 +306,7 @@ tac_reg_kernel(const TacRegParams p)
             {                                                                             \
                 ord_reg = lane == (step & 63) ? best : ord_reg;                           \
                 if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;                  \
-                const int fq = qcount > 0 ? 1 : 0;  /* best is a member of Q whenever Q is not empty */ \
-                qcount -= fq;                                                             \
-                qsum -= fq ? best : 0;                                                    \
-                if (lane == (best & 63)) sets_l &= ~(0x10001u << (best >> 6));            \
+                P[best] = 0.0;                      /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
                 const int delta = CNT1 + best;                                            \
@@ -311,29 +315,59 @@ tac_reg_kernel(const TacRegParams p)
                 TT_EACH_K(TT_UPDATE)                                                      \
                 if (__ballot(hmax >= (uint32_t)-CNT1) != 0ull) { TT_EACH_K(TT_EVENT) }    \
                 ++step;                                                                   \
-                qcount = __builtin_amdgcn_readfirstlane(qcount);                          \
-                qsum = __builtin_amdgcn_readfirstlane(qsum);                              \
+            }
+#define TT_UNIFORM_Q()                                                                    \
+            {                                                                             \
+                qm = __builtin_amdgcn_readfirstlane(qm);                                  \
+                qs = __builtin_amdgcn_readfirstlane(qs);                                  \
+                qq = __builtin_amdgcn_readfirstlane(qq);                                  \
+                qlast = __builtin_amdgcn_readfirstlane(qlast);                            \
+            }
+        // pointers counted afresh from the class registers (after a round that removed an
+        // unknown number of them)
+#define TT_RECOUNT(k)                                                                     \
+            if constexpr (k < KT) {                                                       \
+                uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1 && ct_##k > 0.0); \
+                while (nm) {                                                              \
+                    const int l = __builtin_ctzll(nm);                                    \
+                    nm &= nm - 1;                                                         \
+                    const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;     \
+                    qm += 1;                                                              \
+                    qs += sole;                                                           \
+                    qq += sole * sole;                                                    \
+                    qlast = sole;                                                         \
+                }                                                                         \
             }
         int step = 0;
-        qcount = __builtin_amdgcn_readfirstlane(qcount);
-        qsum = __builtin_amdgcn_readfirstlane(qsum);
+        TT_UNIFORM_Q()
         while (step < R) {
-            // |Q| = 1: its member precedes every recv with P = 0.  These rounds form the inner
-            // loop; M of the classes is not touched in it.
-            while (qcount == 1) {
-                const int best = qsum;
+            // One pointer: its target precedes every recv with P = 0 and is selected; its
+            // pointers (all of them) are gone with it.  These rounds form the inner loop; M of the
+            // classes is not touched in it.
+            while (qm == 1) {
+                const int best = qs;
+                qm = 0; qs = 0; qq = 0;
                 TT_APPLY()
+                TT_UNIFORM_Q()
             }
             if (step >= R) break;
+            if (qm >= 2 && qs == qm * qlast && qq == qm * qlast * qlast) {
+                // several pointers at one recv (both moments agree): |Q| = 1 as well
+                const int best = qlast;
+                qm = 0; qs = 0; qq = 0;
+                TT_APPLY()
+                TT_UNIFORM_Q()
+                continue;
+            }
             int best;
             // the steps of the current block of 64 so far, for the paths that read ordl
             if (lane < (step & 63)) ordl[(step & ~63) + lane] = ord_reg;
             wave_sync();
             m_sync = __builtin_amdgcn_readfirstlane(m_sync);
-            if (qcount == 0) {
+            if (qm == 0) {
                 // every outstanding recv has P = 0: lowest index among those of minimal M+
                 TT_ENSURE_M(step)
-                publish_alive();
+                publish_alive(step);
                 double lmin = TT_INF;
 #define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
                 TT_EACH_K(TT_LMIN)
@@ -355,7 +389,8 @@ tac_reg_kernel(const TacRegParams p)
                 double mp_best = -1.0;
                 best = -1;
                 for (int j = 0; j < W; ++j) {
-                    uint64_t x = __ballot((sets_l >> (16 + j)) & 1u);
+                    const int rj = j * 64 + lane;
+                    uint64_t x = __ballot(rj < R && P[rj] > 0.0);
                     while (x) {
                         const int a = j * 64 + __builtin_ctzll(x);
                         x &= x - 1;
@@ -387,6 +422,9 @@ tac_reg_kernel(const TacRegParams p)
             }
             best = __builtin_amdgcn_readfirstlane(best);
             TT_APPLY()
+            qm = 0; qs = 0; qq = 0;
+            TT_EACH_K(TT_RECOUNT)
+            TT_UNIFORM_Q()
         }
         if ((R & 63) && lane < (R & 63)) ordl[(R & ~63) + lane] = ord_reg;
         wave_sync();
