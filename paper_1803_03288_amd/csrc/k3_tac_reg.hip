@@ -351,6 +351,23 @@ tac_reg_kernel(const TacRegParams p)
                 TT_UNIFORM_Q()
             }
             if (step >= R) break;
+            if (qm == 2 && qs != 2 * qlast) {
+                // two pointers at two recvs a < b: Q = {a, b}, and the scan is one comparison:
+                // b precedes a when min{P_a, Time(b)} < min{P_b, Time(a)}.  A tie is left to
+                // the general path below.
+                const int o_ = qs - qlast;
+                const int a_ = min(o_, qlast), b_ = max(o_, qlast);
+                const double xa = fmin(P[a_], t[b_]);
+                const double ya = fmin(P[b_], t[a_]);
+                if (__builtin_amdgcn_readfirstlane((int)(xa != ya))) {
+                    const int best = __builtin_amdgcn_readfirstlane((int)(xa < ya)) ? b_ : a_;
+                    const int other = a_ + b_ - best;
+                    qm = 1; qs = other; qq = other * other; qlast = other;
+                    TT_APPLY()
+                    TT_UNIFORM_Q()
+                    continue;
+                }
+            }
             if (qm >= 2 && qs == qm * qlast && qq == qm * qlast * qlast) {
                 // several pointers at one recv (both moments agree): |Q| = 1 as well
                 const int best = qlast;
