@@ -106,47 +106,52 @@ static void group_classes(const std::vector<uint64_t> &rows, int32_t N, int32_t 
                           std::vector<uint64_t> &cls_dep, std::vector<int32_t> &cls_ptr,
                           std::vector<int32_t> &cls_cols, int32_t &n_distinct)
 {
-    std::vector<int32_t> idx(N);
-    std::iota(idx.begin(), idx.end(), 0);
-    std::vector<uint64_t> hash(N, 0);
+    // open-addressing table from row hash to the distinct row's number; scanning the ops in
+    // ascending order numbers the distinct rows by first member and keeps members ascending
+    size_t cap = 16;
+    while (cap < (size_t)N * 2) cap <<= 1;
+    std::vector<int32_t> slot(cap, -1);
+    std::vector<int32_t> first;                 // first member of every distinct row
+    std::vector<int32_t> cls_of(N), count;
     for (int32_t j = 0; j < N; ++j) {
         uint64_t h = 0x9E3779B97F4A7C15ull;
         for (int32_t w = 0; w < W; ++w) {
             h ^= rows[(size_t)j * W + w] + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
             h *= 0xFF51AFD7ED558CCDull;
         }
-        hash[j] = h;
-    }
-    auto row_less = [&](int32_t a, int32_t b) {
-        if (hash[a] != hash[b]) return hash[a] < hash[b];
-        int c = W ? memcmp(&rows[(size_t)a * W], &rows[(size_t)b * W], (size_t)W * 8) : 0;
-        if (c != 0) return c < 0;
-        return a < b;
-    };
-    std::sort(idx.begin(), idx.end(), row_less);
-    // runs of equal rows; members ascending inside a run because of the final tie-break
-    struct Run { int32_t first, begin, end; };
-    std::vector<Run> runs;
-    for (int32_t k = 0; k < N;) {
-        int32_t e = k + 1;
-        while (e < N && hash[idx[e]] == hash[idx[k]] &&
-               (W == 0 || memcmp(&rows[(size_t)idx[e] * W], &rows[(size_t)idx[k] * W], (size_t)W * 8) == 0))
-            ++e;
-        runs.push_back({idx[k], k, e});
-        k = e;
-    }
-    std::sort(runs.begin(), runs.end(), [](const Run &a, const Run &b) { return a.first < b.first; });
-    n_distinct = (int32_t)runs.size();
-    cls_dep.clear(); cls_ptr.clear(); cls_cols.clear();
-    cls_ptr.push_back(0);
-    for (const Run &r : runs) {
-        for (int32_t k = r.begin; k < r.end; k += max_members) {
-            int32_t e = std::min(r.end, k + max_members);
-            for (int32_t m = k; m < e; ++m) cls_cols.push_back(idx[m]);
-            cls_ptr.push_back((int32_t)cls_cols.size());
-            for (int32_t w = 0; w < W; ++w) cls_dep.push_back(rows[(size_t)r.first * W + w]);
+        size_t q = (h ^ (h >> 29)) & (cap - 1);
+        for (;;) {
+            const int32_t c = slot[q];
+            if (c < 0) {
+                slot[q] = (int32_t)first.size();
+                cls_of[j] = (int32_t)first.size();
+                first.push_back(j);
+                count.push_back(1);
+                break;
+            }
+            if (W == 0 || memcmp(&rows[(size_t)first[c] * W], &rows[(size_t)j * W], (size_t)W * 8) == 0) {
+                cls_of[j] = c;
+                ++count[c];
+                break;
+            }
+            q = (q + 1) & (cap - 1);
         }
     }
+    n_distinct = (int32_t)first.size();
+    // members of every distinct row, ascending (counting sort by row number)
+    std::vector<int32_t> start(n_distinct + 1, 0);
+    for (int32_t c = 0; c < n_distinct; ++c) start[c + 1] = start[c] + count[c];
+    std::vector<int32_t> members(N), fill(start.begin(), start.end() - 1);
+    for (int32_t j = 0; j < N; ++j) members[fill[cls_of[j]]++] = j;
+    cls_dep.clear(); cls_ptr.clear(); cls_cols.clear();
+    cls_ptr.push_back(0);
+    for (int32_t c = 0; c < n_distinct; ++c)
+        for (int32_t k = start[c]; k < start[c + 1]; k += max_members) {
+            const int32_t e = std::min(start[c + 1], k + max_members);
+            for (int32_t m = k; m < e; ++m) cls_cols.push_back(members[m]);
+            cls_ptr.push_back((int32_t)cls_cols.size());
+            for (int32_t w = 0; w < W; ++w) cls_dep.push_back(rows[(size_t)first[c] * W + w]);
+        }
 }
 
 static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int32_t R, const int32_t *recv_ids,
@@ -335,25 +340,34 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             depT[(size_t)w * d->Cpad + c] = x;
         }
     for (int32_t c = 0; c < d->C; ++c) d->cls_nnz += cnt0[c];
-    // runs of consecutive recv indices of every class row
-    std::vector<int32_t> run_ptr(1, 0), run_lo, run_hi;
+    // runs [lo, hi) of consecutive recv indices of every class row, and the sum of its indices
+    std::vector<int32_t> run_ptr(1, 0), run_lo, run_hi, isum(d->C, 0);
     for (int32_t c = 0; c < d->C; ++c) {
-        int32_t lo = -1;
-        for (int32_t i = 0; i <= d->R; ++i) {
-            const bool set = i < d->R && ((cls_dep[(size_t)c * d->W + (i >> 6)] >> (i & 63)) & 1ull);
-            if (set && lo < 0) lo = i;
-            if (!set && lo >= 0) { run_lo.push_back(lo); run_hi.push_back(i); lo = -1; }
+        const uint64_t *row = &cls_dep[(size_t)c * d->W];
+        int32_t i = 0;
+        int64_t sum = 0;
+        while (i < d->R) {
+            // next set bit at or after i
+            int32_t w = i >> 6;
+            uint64_t x = row[w] & (~0ull << (i & 63));
+            while (!x && ++w < d->W) x = row[w];
+            if (!x) break;
+            const int32_t lo = w * 64 + __builtin_ctzll(x);
+            // next clear bit after lo
+            w = lo >> 6;
+            uint64_t y = ~row[w] & (~0ull << (lo & 63));
+            while (!y && ++w < d->W) y = ~row[w];
+            const int32_t hi = y ? std::min(d->R, w * 64 + __builtin_ctzll(y)) : d->R;
+            run_lo.push_back(lo);
+            run_hi.push_back(hi);
+            sum += (int64_t)(lo + hi - 1) * (hi - lo) / 2;
+            i = hi;
         }
         run_ptr.push_back((int32_t)run_lo.size());
+        isum[c] = (int32_t)sum;
     }
     Packer cls;
-    if (d->R <= 1024) {   // index sums stay below 2^20
-        std::vector<int32_t> isum(d->C, 0);
-        for (int32_t c = 0; c < d->C; ++c)
-            for (int32_t i = 0; i < d->R; ++i)
-                if ((cls_dep[(size_t)c * d->W + (i >> 6)] >> (i & 63)) & 1ull) isum[c] += i;
-        cls.add(&d->d_cls_isum, isum);
-    }
+    if (d->R <= 1024) cls.add(&d->d_cls_isum, isum);   // index sums stay below 2^20
     d->max_members = 0;
     for (int32_t c = 0; c < d->C; ++c) d->max_members = std::max(d->max_members, cls_ptr[c + 1] - cls_ptr[c]);
     cls.add(&d->d_run_ptr, run_ptr);

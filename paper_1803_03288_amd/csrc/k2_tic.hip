@@ -77,10 +77,48 @@ tic_rank_kernel(int32_t R, const int32_t *__restrict__ prio, int32_t *order, int
     }
 }
 
+// Small graphs in one launch of one workgroup: thread i owns recv i, takes the minimum of
+// |dep| over the classes (compute ops with identical rows) whose row holds i, and ranks
+// itself by counting.  depT is the transposed class table [W][Cpad].
+__global__ void __launch_bounds__(1024)
+tic_small_kernel(int32_t R, int32_t C, int32_t Cpad, const uint64_t *__restrict__ depT,
+                 const int32_t *__restrict__ cnt0, int32_t *prio, int32_t *order, int32_t *rank)
+{
+    __shared__ int32_t tile[1024];
+    const int32_t i = threadIdx.x;
+    int32_t m = TICTAC_PRIO_INF;
+    if (i < R) {
+        const uint64_t *col = depT + (size_t)(i >> 6) * Cpad;   // the same word for the 64 lanes of a wave
+        const int sh = i & 63;
+        for (int32_t c = 0; c < C; ++c) {
+            const int32_t k = cnt0[c];
+            if (((col[c] >> sh) & 1ull) && k > 1) m = min(m, k);
+        }
+        prio[i] = m;
+    }
+    tile[i] = m;
+    __syncthreads();
+    if (i < R && (order || rank)) {
+        int32_t r = 0;
+        for (int32_t j = 0; j < R; ++j) {
+            const int32_t pj = tile[j];
+            r += (pj < m) || (pj == m && j < i);
+        }
+        if (rank) rank[i] = r;
+        if (order) order[r] = i;
+    }
+}
+
 hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank, int32_t *, hipStream_t s)
 {
     const int32_t R = d.R;
     if (R == 0) return hipSuccess;
+    if (R <= 1024 && d.C <= 8192 && d.d_cls_depT && d.d_cls_cnt0) {
+        const int threads = (R + 63) / 64 * 64;
+        hipLaunchKernelGGL(tic_small_kernel, dim3(1), dim3(threads), 0, s, R, d.C, d.Cpad, d.d_cls_depT,
+                           d.d_cls_cnt0, prio, order, rank);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(fill_i32, dim3((R + 255) / 256), dim3(256), 0, s, prio, R, (int32_t)TICTAC_PRIO_INF);
     if (d.n > 0) {
         const int32_t rows_per_block = d.n <= 4096 ? 32 : 128;
