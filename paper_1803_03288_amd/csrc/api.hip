@@ -306,6 +306,48 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             l0 = l1;
         }
         graph.add(&d->d_chunk_end, chunk_end);
+        // the LDS ring: a power of two of positions, at least two chunks (or all nodes), at most 64 KB beyond that
+        int32_t ring = 64;
+        while (ring < M && (ring < 2 * kK1Rpt * per_pass || (size_t)ring * 2 * d->k1_wc * 8 <= 64 * 1024)) ring *= 2;
+        d->k1_ring = ring;
+        if (max_width <= per_pass) {
+            const int32_t row_bytes = d->k1_wc * 8, zero_row = ring * row_bytes;
+            std::vector<Dag::FastRec> frecs(M);
+            std::vector<int32_t> fovf;
+            for (int32_t l = 0; l < n_node_levels; ++l)
+                for (int32_t q = nlvl_ptr[l]; q < nlvl_ptr[l + 1]; ++q) {
+                    const Dag::NodeRec &r = nodes[q];
+                    Dag::FastRec &f = frecs[q];
+                    tmp.clear();
+                    for (int j = 0; j < 6; ++j) if (r.in[j] != INT32_MIN) tmp.push_back(r.in[j]);
+                    if (r.ovf_beg >= 0)
+                        for (int32_t e = 1; e <= ovf_idx[r.ovf_beg]; ++e) tmp.push_back(ovf_idx[r.ovf_beg + e]);
+                    int nn = 0, nr = 0;
+                    bool resident = true;       // every node input is in the ring while level l is computed
+                    for (int32_t x : tmp) {
+                        if (x < 0) { ++nr; continue; }
+                        ++nn;
+                        resident = resident && x >= nlvl_ptr[l + 1] - ring;
+                    }
+                    f.op = r.op;
+                    f.ovf = -1;
+                    for (int j = 0; j < 4; ++j) f.in[j] = zero_row;
+                    f.rcv[0] = f.rcv[1] = -1;
+                    if (nn <= 4 && nr <= 2 && resident) {
+                        int a = 0, b = 0;
+                        for (int32_t x : tmp) {
+                            if (x < 0) f.rcv[b++] = ~x;
+                            else f.in[a++] = (x & (ring - 1)) * row_bytes;
+                        }
+                    } else {
+                        f.ovf = (int32_t)fovf.size();
+                        fovf.push_back((int32_t)tmp.size());
+                        fovf.insert(fovf.end(), tmp.begin(), tmp.end());
+                    }
+                }
+            graph.add(&d->d_frecs, frecs);
+            graph.add(&d->d_fovf, fovf);
+        }
     }
     graph.add(&d->d_src, src);
     const size_t dep_words = (size_t)n * d->W;

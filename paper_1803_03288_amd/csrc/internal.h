@@ -11,6 +11,8 @@
 
 namespace tictac {
 
+constexpr int kK1Rpt = 4;             // positions per thread group and chunk of the node kernel
+
 void set_error(const char *fmt, ...);
 
 // Everything a handle owns.  Device arrays are sized exactly; empty ones are NULL.
@@ -40,6 +42,22 @@ struct Dag {
     // positions and 64 levels each): chunk_end[lv] = first level after the chunk that starts at lv
     int32_t k1_wc = 0, k1_threads = 0;
     int32_t *d_chunk_end = nullptr; // [n_node_levels]
+    // The same nodes decoded for the chunked kernel, which keeps the rows of the last k1_ring
+    // positions (a power of two) in an LDS ring of k1_wc words per row, plus one all-zero row
+    // after it.  A node with at most four node inputs, all of them still in the ring when its
+    // level is computed, and at most two recv inputs, is "fast": in[] are byte offsets of its
+    // input rows in the ring (unused: the zero row), rcv[] its recv indices (-1 none).  Any
+    // other node has only zero rows and -1 here, and all its inputs (in the encoding of
+    // NodeRec::in) at fovf[ovf + 1 ..], fovf[ovf] of them.
+    struct FastRec {                // 32 bytes, one per position
+        int32_t in[4];
+        int32_t rcv[2];
+        int32_t op;                 // op id of the node
+        int32_t ovf;                // -1 for a fast node
+    };
+    int32_t k1_ring = 0;
+    FastRec *d_frecs = nullptr;     // [M] (not built when a level is wider than one pass)
+    int32_t *d_fovf = nullptr;
     int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]

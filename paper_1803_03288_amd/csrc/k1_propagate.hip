@@ -23,6 +23,8 @@ struct PropParams {
     int32_t n_levels, W, M, ring;       // ring: positions held in LDS (power of two)
     const NodeRec *nodes;
     const int32_t *ovf_idx;
+    const Dag::FastRec *frecs;          // the chunked kernel's form of the nodes
+    const int32_t *fovf;
     const int32_t *nlvl_ptr;
     uint64_t *dep;
 };
@@ -166,16 +168,17 @@ propagate_nodes_wide(const PropParams p)
 // thread per node and word).  Nothing on the per-level path touches memory:
 //   * levels are processed in chunks made by the host (at most RPT positions per thread
 //     group, at most 64 levels).  The records of a chunk sit in LDS.  At a chunk boundary a
-//     thread writes the records it loaded one chunk earlier into the other LDS buffer,
-//     stores the words it computed in the chunk just finished, and starts the loads of the
-//     records of the chunk after the next; so loads and stores have a whole chunk to
-//     complete, and the barrier between two levels waits for LDS only;
-//   * the wait for those loads at the next boundary also covers the stores, so the rows of
-//     a chunk are in memory two chunks later.  The ring holds at least two chunks (or every
-//     node), hence any input that has left the ring is in memory.
+//     thread writes the records it requested two boundaries earlier into the other LDS
+//     buffer, stores the words it computed in the chunk just finished, and requests the
+//     records of the third chunk ahead; so loads have two chunks to complete, stores one,
+//     and the barrier between two levels waits for LDS only;
+//   * the wait at a boundary covers everything but the latest request, hence the stores of
+//     the previous boundary: the rows of a chunk are in memory two chunks later.  The ring
+//     holds at least two chunks (or every node), hence any input that has left the ring is
+//     in memory.
 constexpr int WIN_LEVELS = 512;                 // levels per refill of the bounds window
-constexpr int WIN_MARGIN = 200;                 // three chunks ahead (64 levels each) and slack
-constexpr int RPT = 4;                          // positions per thread group and chunk
+constexpr int WIN_MARGIN = 330;                 // one chunk past the window and four chunks ahead (64 levels each), and slack
+constexpr int RPT = kK1Rpt;                     // positions per thread group and chunk
 
 template <int WC>
 __global__ void __launch_bounds__(1024)
@@ -206,131 +209,130 @@ propagate_nodes(const PropParams p, const int32_t *__restrict__ chunk_end)
     __syncthreads();
     if (L == 0) return;
 
-    // chunk c: levels [L0, L1), positions [c0, c1); chunk c+1: levels [L1, L2), positions [c1, c2)
+    // chunk c: levels [L0, L1), positions [c0, c1); chunks c+1, c+2: [L1, L2), [L2, L3)
     int L0 = 0, L1 = cend[0];
     int c0 = lvl[0], c1 = lvl[L1];
     int L2 = L1 < L ? cend[L1] : L1;
     int c2 = lvl[L2];
-    int4 na[RPT], nb[RPT];                              // records of the next chunk, in flight
-    // prologue: records of chunk 0 straight into buffer 0, records of chunk 1 into registers
+    int L3 = L2 < L ? cend[L2] : L2;
+    int c3 = lvl[L3];
+    // Records in flight, two register sets used in turn: at the boundary after chunk c one set
+    // holds the records of chunk c+1 (requested two boundaries earlier) and is refilled with
+    // the request for chunk c+3.  A request is always 2 RPT loads (addresses clamped), so
+    // "at most 2 RPT memory operations outstanding" means: everything before the latest
+    // request has completed.
+    static_assert(RPT == 4, "the s_waitcnt below is written for 2 * RPT = 8 loads per request");
+    int4 a0_0, a0_1, a0_2, a0_3, b0_0, b0_1, b0_2, b0_3, a1_0, a1_1, a1_2, a1_3, b1_0, b1_1, b1_2, b1_3;
+    // (macros rather than functions taking the sets by reference: the sets must stay in registers)
+#define K1_REQ1(sa, sb, from, j)                                                          \
+    {                                                                                     \
+        const int i_ = min((from) + sub + (j) * per_pass, p.M - 1);                       \
+        const int4 *q_ = reinterpret_cast<const int4 *>(p.frecs + i_);                    \
+        sa##_##j = q_[0]; sb##_##j = q_[1];                                               \
+    }
+#define K1_REQUEST(sa, sb, from) K1_REQ1(sa, sb, from, 0) K1_REQ1(sa, sb, from, 1) K1_REQ1(sa, sb, from, 2) K1_REQ1(sa, sb, from, 3)
+#define K1_PUT1(sa, sb, j)                                                                \
+    {                                                                                     \
+        const int i_ = sub + (j) * per_pass;                                              \
+        if (w == 0 && c1 + i_ < c2) { other[(size_t)i_ * 2] = sa##_##j; other[(size_t)i_ * 2 + 1] = sb##_##j; } \
+    }
+    // prologue: records of chunk 0 straight into buffer 0, chunks 1 and 2 requested
     for (int j = 0; j < RPT; ++j) {
         const int i = sub + j * per_pass;
         if (w == 0 && c0 + i < c1) {
-            const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c0 + i);
+            const int4 *q = reinterpret_cast<const int4 *>(p.frecs + c0 + i);
             recbuf[(size_t)i * 2] = q[0];
             recbuf[(size_t)i * 2 + 1] = q[1];
         }
     }
-#pragma unroll
-    for (int j = 0; j < RPT; ++j) {
-        na[j] = make_int4(0, 0, 0, 0); nb[j] = na[j];
-        const int i = sub + j * per_pass;
-        if (c1 + i < c2) {
-            const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c1 + i);
-            na[j] = q[0]; nb[j] = q[1];
-        }
-    }
+    K1_REQUEST(a0, b0, c1)
+    K1_REQUEST(a1, b1, c2)
     __syncthreads();
 
     int cur = 0;
-    while (L0 < L) {
-        const int4 *rec = recbuf + (size_t)cur * 2 * CH;
-        // A level is at most per_pass wide, so a thread group meets at most one of its positions
-        // c0 + sub + j per_pass per level, in ascending j.  The record of the next one is read
-        // from LDS a level ahead; so is the upper bound of the next level.
-        int mypos = c0 + sub;
-        int4 ra = make_int4(0, 0, 0, 0), rb = ra;
-        if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }
-        int end_next = lvl[L0 + 1 - base];
-        for (int lv = L0; lv < L1; ++lv) {
-            const int end = end_next;
-            if (lv + 1 < L1) end_next = lvl[lv + 2 - base];
-            if (mypos < end) {
-                const int safe_from = max(end - p.ring, 0);   // older positions: read from memory
-                const int in[6] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y};
-                const int ovf_beg = rb.w;
-                // all inputs at once: a recv contributes a bit, a position in the ring its word, and
-                // anything else reads the zero row kept after the ring
-                uint64_t bits = 0, v[6];
-                bool slow = ovf_beg >= 0;
-#pragma unroll
-                for (int j = 0; j < 6; ++j) {
-                    const int x = in[j];
-                    const int i = ~x;
-                    const bool is_recv = x < 0 && x != INT32_MIN;
-                    bits |= (is_recv && (i >> 6) == gw) ? 1ull << (i & 63) : 0ull;
-                    const bool in_ring = x >= safe_from;
-                    slow |= x >= 0 && !in_ring;
-                    const uint32_t slot = in_ring ? ((uint32_t)x & rmask) : (uint32_t)p.ring;
-                    v[j] = ring[slot * WC + w];
-                }
-                uint64_t val = bits | v[0] | v[1] | v[2] | v[3] | v[4] | v[5];
-                if (slow && gw < W) {                         // long edges and overflow inputs (rare)
-#pragma unroll
-                    for (int j = 0; j < 6; ++j) {
-                        const int x = in[j];
-                        if (x >= 0 && x < safe_from) val |= p.dep[(size_t)p.nodes[x].op * W + gw];
-                    }
-                    const int ovf_cnt = ovf_beg >= 0 ? p.ovf_idx[ovf_beg] : 0;
-                    for (int e = 1; e <= ovf_cnt; ++e) {
-                        const int x = p.ovf_idx[ovf_beg + e];
-                        if (x < 0) {
-                            const int i = ~x;
-                            if ((i >> 6) == gw) val |= 1ull << (i & 63);
-                        } else if (x >= safe_from) {
-                            val |= ring[((uint32_t)x & rmask) * WC + w];
-                        } else {
-                            val |= p.dep[(size_t)p.nodes[x].op * W + gw];
-                        }
-                    }
-                }
-                if (gw >= W) val = 0;
-                ring[((uint32_t)mypos & rmask) * WC + w] = val;
-                mypos += per_pass;
-                if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }
-            }
-            if (lv + 1 < L1) lds_barrier();
-        }
-        // ---- chunk boundary ----
-        // every thread waits for what it issued at the previous boundary (one chunk ago): the
-        // record loads used next, and the stores of the chunk before this one
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        // records of chunk c+1 into the other buffer
-        int4 *other = recbuf + (size_t)(cur ^ 1) * 2 * CH;
-#pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            const int i = sub + j * per_pass;
-            if (w == 0 && c1 + i < c2) { other[(size_t)i * 2] = na[j]; other[(size_t)i * 2 + 1] = nb[j]; }
-        }
-        // words of chunk c to memory (each thread stores what it computed itself)
-#pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            const int pos = c0 + sub + j * per_pass;
-            if (pos < c1 && gw < W) {
-                const int op = reinterpret_cast<const int32_t *>(rec + (size_t)(pos - c0) * 2 + 1)[2];
-                p.dep[(size_t)op * W + gw] = ring[((uint32_t)pos & rmask) * WC + w];
-            }
-        }
-        // records of chunk c+2
-        const int L3 = L2 < L ? cend[L2 - base] : L2;
-        const int c3 = lvl[L3 - base];
-#pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            const int i = sub + j * per_pass;
-            if (c2 + i < c3) {
-                const int4 *q = reinterpret_cast<const int4 *>(p.nodes + c2 + i);
-                na[j] = q[0]; nb[j] = q[1];
-            }
-        }
-        lds_barrier();
-        cur ^= 1;
-        L0 = L1; L1 = L2; L2 = L3; c0 = c1; c1 = c2; c2 = c3;
-        if (L0 < L && L0 - base >= WIN_LEVELS) {         // slide the windows (uniform)
-            base = L0;
-            fill_window(base);
-            __syncthreads();
-        }
+#define K1_RUN_CHUNK(sa, sb)                                                                        \
+    {                                                                                               \
+        const int4 *rec = recbuf + (size_t)cur * 2 * CH;                                            \
+        /* A level is at most per_pass wide, so a thread group meets at most one of its positions */\
+        /* c0 + sub + j per_pass per level, in ascending j.  The record of the next one is read */  \
+        /* from LDS a level ahead; so is the upper bound of the next level. */                      \
+        int mypos = c0 + sub;                                                                       \
+        int4 ra = make_int4(0, 0, 0, 0), rb = ra;                                                   \
+        if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }\
+        int end_next = lvl[L0 + 1 - base];                                                          \
+        for (int lv = L0; lv < L1; ++lv) {                                                          \
+            const int end = end_next;                                                               \
+            if (lv + 1 < L1) end_next = lvl[lv + 2 - base];                                         \
+            if (mypos < end) {                                                                      \
+                /* a fast node: four rows of the ring (unused inputs read the zero row after it) */ \
+                /* and the bits of up to two recvs */                                               \
+                const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;                   \
+                const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + ra.x);              \
+                const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + ra.y);              \
+                const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + ra.z);              \
+                const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + ra.w);              \
+                uint64_t bits = (rb.x >> 6) == gw ? 1ull << (rb.x & 63) : 0ull;                     \
+                bits |= (rb.y >> 6) == gw ? 1ull << (rb.y & 63) : 0ull;                             \
+                uint64_t val = bits | v0 | v1 | v2 | v3;                                            \
+                const int ovf_beg = rb.w;                                                           \
+                if (ovf_beg >= 0 && gw < W) {                 /* any other node (rare): all inputs from its list */\
+                    const int safe_from = max(end - p.ring, 0);   /* older positions: read from memory */\
+                    const int ovf_cnt = p.fovf[ovf_beg];                                            \
+                    for (int e = 1; e <= ovf_cnt; ++e) {                                            \
+                        const int x = p.fovf[ovf_beg + e];                                          \
+                        if (x < 0) {                                                                \
+                            const int i = ~x;                                                       \
+                            if ((i >> 6) == gw) val |= 1ull << (i & 63);                            \
+                        } else if (x >= safe_from) {                                                \
+                            val |= ring[((uint32_t)x & rmask) * WC + w];                            \
+                        } else {                                                                    \
+                            val |= p.dep[(size_t)p.frecs[x].op * W + gw];                           \
+                        }                                                                           \
+                    }                                                                               \
+                }                                                                                   \
+                if (gw >= W) val = 0;                                                               \
+                ring[((uint32_t)mypos & rmask) * WC + w] = val;                                     \
+                mypos += per_pass;                                                                  \
+                if (mypos < c1) { ra = rec[(size_t)(mypos - c0) * 2]; rb = rec[(size_t)(mypos - c0) * 2 + 1]; }\
+            }                                                                                       \
+            if (lv + 1 < L1) lds_barrier();                                                         \
+        }                                                                                           \
+        /* ---- chunk boundary ---- */                                                              \
+        /* everything issued before the latest request is complete after this: the records in */    \
+        /* (sa, sb), and the stores of the chunk before this one */                                 \
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                                            \
+        /* records of chunk c+1 into the other buffer */                                            \
+        int4 *other = recbuf + (size_t)(cur ^ 1) * 2 * CH;                                          \
+K1_PUT1(sa, sb, 0) K1_PUT1(sa, sb, 1) K1_PUT1(sa, sb, 2) K1_PUT1(sa, sb, 3)                         \
+        /* words of chunk c to memory (each thread stores what it computed itself) */               \
+_Pragma("unroll")                                                                                   \
+        for (int j = 0; j < RPT; ++j) {                                                             \
+            const int pos = c0 + sub + j * per_pass;                                                \
+            if (pos < c1 && gw < W) {                                                               \
+                const int op = reinterpret_cast<const int32_t *>(rec + (size_t)(pos - c0) * 2 + 1)[2];\
+                p.dep[(size_t)op * W + gw] = ring[((uint32_t)pos & rmask) * WC + w];                \
+            }                                                                                       \
+        }                                                                                           \
+        /* request the records of chunk c+3 */                                                      \
+        const int L4 = L3 < L ? cend[L3 - base] : L3;                                               \
+        const int c4 = lvl[L4 - base];                                                              \
+        K1_REQUEST(sa, sb, c3)                                                                      \
+        lds_barrier();                                                                              \
+        cur ^= 1;                                                                                   \
+        L0 = L1; L1 = L2; L2 = L3; L3 = L4; c0 = c1; c1 = c2; c2 = c3; c3 = c4;                     \
+        if (L0 < L && L0 - base >= WIN_LEVELS) {         /* slide the windows (uniform) */          \
+            base = L0;                                                                              \
+            fill_window(base);                                                                      \
+            __syncthreads();                                                                        \
+        }                                                                                           \
     }
+    while (L0 < L) {
+        K1_RUN_CHUNK(a0, b0)
+        if (L0 >= L) break;
+        K1_RUN_CHUNK(a1, b1)
+    }
+#undef K1_RUN_CHUNK
+#undef K1_REQUEST
 }
 
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto
@@ -355,13 +357,13 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     PropParams p;
     p.n_levels = d.n_node_levels; p.W = d.W; p.M = d.M;
     p.nodes = d.d_nodes; p.ovf_idx = d.d_ovf_idx; p.nlvl_ptr = d.d_nlvl_ptr; p.dep = d.d_dep;
+    p.frecs = d.d_frecs; p.fovf = d.d_fovf;
     const int threads = d.k1_threads;
     const int per_pass = threads / WC;
     const int blocks = (d.W + WC - 1) / WC;
     const bool wide = d.max_node_level_width > per_pass;
-    // ring: a power of two of positions; at least two chunks (or all nodes), at most 64 KB beyond that
-    int ring = 64;
-    while (ring < d.M && (ring < 2 * RPT * per_pass || (size_t)ring * 2 * WC * 8 <= 64 * 1024)) ring *= 2;
+    if (!wide && !d.d_frecs) return hipErrorInvalidValue;
+    const int ring = d.k1_ring;
     p.ring = ring;
     size_t lds = (size_t)ring * WC * 8;
     if (wide) lds += (size_t)4 * per_pass * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
