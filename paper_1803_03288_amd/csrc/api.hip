@@ -347,6 +347,7 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
                 }
             graph.add(&d->d_frecs, frecs);
             graph.add(&d->d_fovf, fovf);
+            d->fovf_len = (int32_t)fovf.size();
         }
     }
     graph.add(&d->d_src, src);

@@ -58,6 +58,7 @@ struct Dag {
     int32_t k1_ring = 0;
     FastRec *d_frecs = nullptr;     // [M] (not built when a level is wider than one pass)
     int32_t *d_fovf = nullptr;
+    int32_t fovf_len = 0;
     int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]

@@ -25,6 +25,7 @@ struct PropParams {
     const int32_t *ovf_idx;
     const Dag::FastRec *frecs;          // the chunked kernel's form of the nodes
     const int32_t *fovf;
+    int32_t fovf_lds;                   // > 0: that many entries of fovf (all of them) are copied to LDS
     const int32_t *nlvl_ptr;
     uint64_t *dep;
 };
@@ -197,6 +198,8 @@ propagate_nodes(const PropParams p, const int32_t *__restrict__ chunk_end)
     if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
     int32_t *lvl = reinterpret_cast<int32_t *>(recbuf + (size_t)4 * CH);        // [WIN_LEVELS + WIN_MARGIN]
     int32_t *cend = lvl + WIN_LEVELS + WIN_MARGIN;                               // [WIN_LEVELS + WIN_MARGIN]
+    int32_t *fov = cend + WIN_LEVELS + WIN_MARGIN;                               // [fovf_lds] input lists of the other nodes
+    for (int i = threadIdx.x; i < p.fovf_lds; i += blockDim.x) fov[i] = p.fovf[i];
 
     int base = 0;
     auto fill_window = [&](int b0) {
@@ -277,9 +280,10 @@ propagate_nodes(const PropParams p, const int32_t *__restrict__ chunk_end)
                 const int ovf_beg = rb.w;                                                           \
                 if (ovf_beg >= 0 && gw < W) {                 /* any other node (rare): all inputs from its list */\
                     const int safe_from = max(end - p.ring, 0);   /* older positions: read from memory */\
-                    const int ovf_cnt = p.fovf[ovf_beg];                                            \
+                    const bool in_lds = p.fovf_lds > 0;                                             \
+                    const int ovf_cnt = in_lds ? fov[ovf_beg] : p.fovf[ovf_beg];                    \
                     for (int e = 1; e <= ovf_cnt; ++e) {                                            \
-                        const int x = p.fovf[ovf_beg + e];                                          \
+                        const int x = in_lds ? fov[ovf_beg + e] : p.fovf[ovf_beg + e];              \
                         if (x < 0) {                                                                \
                             const int i = ~x;                                                       \
                             if ((i >> 6) == gw) val |= 1ull << (i & 63);                            \
@@ -358,6 +362,7 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     p.n_levels = d.n_node_levels; p.W = d.W; p.M = d.M;
     p.nodes = d.d_nodes; p.ovf_idx = d.d_ovf_idx; p.nlvl_ptr = d.d_nlvl_ptr; p.dep = d.d_dep;
     p.frecs = d.d_frecs; p.fovf = d.d_fovf;
+    p.fovf_lds = d.fovf_len <= 4096 ? d.fovf_len : 0;
     const int threads = d.k1_threads;
     const int per_pass = threads / WC;
     const int blocks = (d.W + WC - 1) / WC;
@@ -367,7 +372,8 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     p.ring = ring;
     size_t lds = (size_t)ring * WC * 8;
     if (wide) lds += (size_t)4 * per_pass * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
-    else lds += (size_t)2 * WC * 8 + (size_t)4 * RPT * per_pass * 16 + (size_t)2 * (WIN_LEVELS + WIN_MARGIN) * 4;
+    else lds += (size_t)2 * WC * 8 + (size_t)4 * RPT * per_pass * 16 + (size_t)2 * (WIN_LEVELS + WIN_MARGIN) * 4 +
+                (size_t)p.fovf_lds * 4;
     if (lds > 150 * 1024) return hipErrorInvalidValue;
     const void *kern = wide ? reinterpret_cast<const void *>(propagate_nodes_wide<WC>)
                             : reinterpret_cast<const void *>(propagate_nodes<WC>);
