@@ -151,7 +151,6 @@ tac_reg_kernel(const TacRegParams p)
         // ---- b. class totals ----
 #define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, kap_##k = 0, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
         TT_EACH_K(TT_DECL_STATE)
-        double ct_sum = 0.0;
         if (p.col_cls) {
             // the row is read once, coalesced; every column adds itself to the total of its class
             for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
@@ -159,7 +158,7 @@ tac_reg_kernel(const TacRegParams p)
             _Pragma("unroll 4")
             for (int j = lane; j < N; j += 64) atomicAdd(&csum[p.col_cls[j]], ot[j]);
             wave_sync();
-#define TT_READ_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; ct_sum += ct_##k; }
+#define TT_READ_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
             TT_EACH_K(TT_READ_TOTAL)
             wave_sync();
         } else {
@@ -174,7 +173,6 @@ tac_reg_kernel(const TacRegParams p)
                         if (m < mcnt) s += ot[p.cls_cols[mbeg + m]];                      \
                 }                                                                         \
                 ct_##k = s;                                                               \
-                ct_sum += s;                                                              \
             }
             TT_EACH_K(TT_GATHER_TOTAL)
         }
@@ -470,6 +468,9 @@ tac_reg_kernel(const TacRegParams p)
             }
             const double F = fc;
             wave_sync();
+            double ct_sum = 0.0;
+#define TT_TOTAL(k) if constexpr (k < KT) { ct_sum += ct_##k; }
+            TT_EACH_K(TT_TOTAL)
             const double sum_c = wave_sum_f64(ct_sum);
             double sfx = 0.0, mloc = sum_c;               // k = 0: F_0 + S_0 = all class time
             for (int base = ((R - 1) / 64) * 64; base >= 0; base -= 64) {
