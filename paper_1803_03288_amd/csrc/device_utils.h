@@ -10,6 +10,15 @@ namespace tictac {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
+// ordering point for LDS traffic between the lanes of one wave (LDS operations of a wave
+// complete in issue order; this only keeps the compiler from moving them across)
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ __forceinline__ double wave_min_f64(double v)
 {
 #pragma unroll

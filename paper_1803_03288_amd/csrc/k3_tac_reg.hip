@@ -64,15 +64,6 @@ constexpr int kRegWaves = 4;           // waves per workgroup
 constexpr int CNT1 = 1 << 20;          // one unit of the outstanding count in `packed`
 constexpr int IDX_MASK = CNT1 - 1;
 
-// ordering point for LDS traffic between the lanes of one wave (LDS operations of a wave
-// complete in issue order; this only keeps the compiler from moving them across)
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // lowest outstanding recv of class (lane, k); rows: [2W][64][KT] halves, alive: [2W] halves in LDS
 template <int KT>
 __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t *alive, int W, int lane, int k)

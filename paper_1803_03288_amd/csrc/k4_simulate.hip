@@ -125,6 +125,195 @@ simulate_kernel(const SimKernelParams p)
     }
 }
 
+// The same computation with one wavefront per sample, for graphs with at most 8 classes per
+// lane and at most 512 recvs.  Lane l owns the classes l, l + 64, ...; a workgroup is four
+// independent waves.  Per sample: the transfer times and the order are read coalesced; the
+// op_time row is read once, coalesced, every column adding itself to the total of its class
+// in LDS; kappa of a class is the maximum of the positions of its recvs, taken run by run of
+// consecutive recv indices from a sparse table of range maxima over the position array (or read
+// from a table when all samples share one order); then A by kappa, and
+//     makespan = max over k of F_k + (A_k + ... + A_R),   F_0 = 0,
+// which is the recurrence above unrolled.
+struct SimWaveParams {
+    int32_t B, R, C, N, n_waves, wave_bytes, levels;
+    const int32_t *col_cls;     // [N] class of every op_time column
+    const int32_t *run_ptr;     // [C+1] runs [run_lo, run_hi) of consecutive recv indices of the class rows
+    const int32_t *run_lo, *run_hi;
+    const int32_t *order;
+    int32_t order_stride;
+    const int32_t *kappa;       // [C] for a shared order, else NULL
+    const double *op_time, *recv_time;
+    double *makespan, *eff, *U, *L, *S;
+};
+
+constexpr int kSimWaves = 4;
+
+#define SW_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
+
+template <int KT>
+__global__ void __launch_bounds__(64 * kSimWaves)
+simulate_wave_kernel(const SimWaveParams p)
+{
+    extern __shared__ double smem[];
+    const int R = p.R, C = p.C, N = p.N;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    char *mine = reinterpret_cast<char *>(smem) + (size_t)wave * p.wave_bytes;
+    double *t = reinterpret_cast<double *>(mine);           // [R]   Time(recv)
+    double *F = t + R;                                      // [R]   F[k-1] = end of the k-th transfer
+    double *A = F + R;                                      // [R+1] class time by kappa
+    double *csum = F;                                       // [64 KT] class totals while they are summed (spans F and A)
+    uint16_t *pos = reinterpret_cast<uint16_t *>(A + (R + 1));   // [levels][R] range maxima of the 1-based positions
+
+    const int gwave = blockIdx.x * kSimWaves + wave;
+    for (int b = gwave; b < p.B; b += p.n_waves) {
+        const double *rt = p.recv_time + (size_t)b * R;
+        const double *ot = p.op_time + (size_t)b * N;
+        const int32_t *ord = p.order + (size_t)b * p.order_stride;
+        wave_sync();                        // LDS of the previous sample is no longer read
+
+        // ---- transfer times, class totals ----
+        for (int r = lane; r < R; r += 64) { t[r] = rt[r]; pos[r] = 0; }
+        for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
+        wave_sync();
+#pragma unroll 4
+        for (int j = lane; j < N; j += 64) atomicAdd(&csum[p.col_cls[j]], ot[j]);
+        wave_sync();
+#define SW_DECL(k) double ct_##k = 0.0; int kap_##k = 0;
+        SW_EACH_K(SW_DECL)
+#define SW_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
+        SW_EACH_K(SW_TOTAL)
+        wave_sync();
+
+        // ---- positions, F ----
+        double fc = 0.0;
+        for (int base = 0; base < R; base += 64) {
+            const int s = base + lane;
+            const int r = s < R ? ord[s] : -1;
+            const bool ok = (unsigned)r < (unsigned)R;      // an invalid entry is skipped, never dereferenced
+            if (ok) pos[r] = (uint16_t)(s + 1);
+            const double x = ok ? t[r] : 0.0;
+            const double inc = wave_incl_scan_f64(x);
+            if (s < R) F[s] = fc + inc;
+            fc += __shfl(inc, 63);
+        }
+        const double Ftot = fc;
+        for (int j = lane; j <= R; j += 64) A[j] = 0.0;
+        wave_sync();
+
+        // ---- kappa ----
+        if (p.kappa) {
+#define SW_KAPPA_TABLE(k) if constexpr (k < KT) { if (k * 64 + lane < C) kap_##k = p.kappa[k * 64 + lane]; }
+            SW_EACH_K(SW_KAPPA_TABLE)
+        } else {
+            // level j of the table: maximum over [i, min(i + 2^j, R))
+            for (int j = 1; j < p.levels; ++j) {
+                const uint16_t *prev = pos + (size_t)(j - 1) * R;
+                uint16_t *cur = pos + (size_t)j * R;
+                const int h = 1 << (j - 1);
+                for (int i = lane; i < R; i += 64) cur[i] = max(prev[i], prev[min(i + h, R - 1)]);
+                wave_sync();
+            }
+#define SW_KAPPA_RUNS(k)                                                                  \
+            if constexpr (k < KT) {                                                       \
+                const int c = k * 64 + lane;                                              \
+                if (c < C) {                                                              \
+                    const int rend = p.run_ptr[c + 1];                                    \
+                    int m = 0;                                                            \
+                    for (int q = p.run_ptr[c]; q < rend; ++q) {                           \
+                        const int lo = p.run_lo[q], hi = p.run_hi[q];                     \
+                        const int j = 31 - __builtin_clz(hi - lo);                        \
+                        const uint16_t *lv = pos + (size_t)j * R;                         \
+                        m = max(m, max((int)lv[lo], (int)lv[hi - (1 << j)]));             \
+                    }                                                                     \
+                    kap_##k = m;                                                          \
+                }                                                                         \
+            }
+            SW_EACH_K(SW_KAPPA_RUNS)
+        }
+
+        // ---- A by kappa, suffix sums, makespan ----
+        double ct_sum = 0.0;
+#define SW_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); ct_sum += ct_##k; }
+        SW_EACH_K(SW_RELEASE)
+        wave_sync();
+        const double sum_c = wave_sum_f64(ct_sum);
+        double sfx = 0.0, mloc = sum_c;                   // k = 0: F_0 + S_0 = all class time
+        for (int base = ((R - 1) / 64) * 64; base >= 0; base -= 64) {
+            const int k = base + lane + 1;                // 1 <= k <= R handled here
+            const double x = k <= R ? A[k] : 0.0;
+            const double inc = wave_incl_scan_f64(x);
+            const double tot = __shfl(inc, 63);
+            if (k <= R) mloc = fmax(mloc, F[k - 1] + (sfx + (tot - inc + x)));
+            sfx += tot;
+        }
+        const double m = wave_max_f64(mloc);
+        if (lane == 0) {
+            const double U = sum_c + Ftot;
+            const double L = fmax(sum_c, Ftot);
+            p.makespan[b] = m;
+            p.eff[b] = (U == L) ? 1.0 : (U - m) / (U - L);
+            if (p.U) p.U[b] = U;
+            if (p.L) p.L[b] = L;
+            if (p.S) p.S[b] = (U == L || L == 0.0) ? 0.0 : (U - L) / L;
+        }
+    }
+}
+
+template <int KT>
+static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
+{
+    int levels = 1;
+    while ((1 << levels) <= d.R) ++levels;            // floor(log2 R) + 1 levels of the table
+    p.levels = levels;
+    size_t wave_bytes = ((size_t)3 * d.R + 1) * 8 + (size_t)levels * d.R * 2;
+    wave_bytes = (wave_bytes + 15) & ~(size_t)15;
+    const size_t lds = wave_bytes * kSimWaves;
+    if (lds > 64 * 1024) return hipErrorNotSupported;
+    p.wave_bytes = (int32_t)wave_bytes;
+    hipError_t e;
+    if (lds > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(simulate_wave_kernel<KT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, simulate_wave_kernel<KT>, 64 * kSimWaves, lds);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
+    int n_cu = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
+        n_cu = prop.multiProcessorCount;
+    int grid = per_cu * n_cu;
+    const int need = (p.B + kSimWaves - 1) / kSimWaves;
+    if (grid > need) grid = need;
+    p.n_waves = grid * kSimWaves;
+    hipLaunchKernelGGL((simulate_wave_kernel<KT>), dim3(grid), dim3(64 * kSimWaves), lds, s, p);
+    return hipGetLastError();
+}
+
+// hipErrorNotSupported: the graph is outside what the wave kernel handles
+static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_t *kappa, hipStream_t s)
+{
+    const int K = (d.C + 63) / 64;
+    const int KT = K <= 4 ? K : (K <= 6 ? 6 : 8);     // the instantiation that is launched below
+    // (the class totals are summed in the space of F and A: one double per class slot must fit)
+    if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || (size_t)64 * KT > 2 * (size_t)d.R + 1)
+        return hipErrorNotSupported;
+    SimWaveParams p{};
+    p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N;
+    p.col_cls = d.d_col_cls; p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;
+    p.order = a.order; p.order_stride = a.order_stride; p.kappa = kappa;
+    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
+    if (K <= 1) return launch_sim_wave<1>(p, d, s);
+    if (K <= 2) return launch_sim_wave<2>(p, d, s);
+    if (K <= 3) return launch_sim_wave<3>(p, d, s);
+    if (K <= 4) return launch_sim_wave<4>(p, d, s);
+    if (K <= 6) return launch_sim_wave<6>(p, d, s);
+    return launch_sim_wave<8>(p, d, s);
+}
+
 template <int BS>
 static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, hipStream_t s)
 {
@@ -155,6 +344,10 @@ hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
         hipLaunchKernelGGL(position_kernel, dim3((d.R + 255) / 256), dim3(256), 0, s, d.R, a.order, pos);
         hipLaunchKernelGGL(kappa_kernel, dim3((d.C + 255) / 256), dim3(256), 0, s, d.W, d.C, d.d_cls_dep, pos, kappa);
         p.kappa = kappa;
+    }
+    {
+        const hipError_t e = try_simulate_wave(d, a, p.kappa, s);
+        if (e != hipErrorNotSupported) return e;
     }
     const size_t lds = ((size_t)(d.R + 1) * 2 + 16) * 8 + (size_t)d.R * 4;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
