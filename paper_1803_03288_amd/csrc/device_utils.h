@@ -51,6 +51,73 @@ __device__ __forceinline__ double wave_incl_scan_f64(double v)
     return v;
 }
 
+// ---- the same reductions and scans through data-parallel-primitive moves (no LDS traffic) ----
+// A wave64 is four rows of 16 lanes.  row_shr:n moves a value n lanes up inside a row;
+// row_bcast:15 hands lane 15 of every row to the whole next row, row_bcast:31 hands lane 31
+// to rows 2 and 3.  A lane without a source keeps `identity`.  Four shifts (1, 2, 4, 8) scan
+// the rows, the two broadcasts (applied to rows 1 and 3, then to rows 2 and 3) add the totals
+// of the rows before; lane 63 ends with the reduction over the wave.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i32(int identity, int v)
+{
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double identity, double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(__double2loint(identity), __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(__double2hiint(identity), __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double lane63_f64(double v)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
+                            __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+
+#define TT_DPP_SCAN(T, DPP, OP, ID)                                                       \
+    v = OP(v, DPP<0x111, 0xf>(ID, v));                                                    \
+    v = OP(v, DPP<0x112, 0xf>(ID, v));                                                    \
+    v = OP(v, DPP<0x114, 0xf>(ID, v));                                                    \
+    v = OP(v, DPP<0x118, 0xf>(ID, v));                                                    \
+    v = OP(v, DPP<0x142, 0xa>(ID, v));                                                    \
+    v = OP(v, DPP<0x143, 0xc>(ID, v));
+
+__device__ __forceinline__ double tt_add_f64(double a, double b) { return a + b; }
+__device__ __forceinline__ int tt_add_i32(int a, int b) { return a + b; }
+__device__ __forceinline__ int tt_min_i32(int a, int b) { return min(a, b); }
+__device__ __forceinline__ int tt_max_i32(int a, int b) { return max(a, b); }
+
+// inclusive prefix sum over the lanes of a wave
+__device__ __forceinline__ double wave_incl_scan_f64_dpp(double v)
+{
+    TT_DPP_SCAN(double, dpp_f64, tt_add_f64, 0.0)
+    return v;
+}
+__device__ __forceinline__ double wave_sum_f64_dpp(double v)
+{
+    TT_DPP_SCAN(double, dpp_f64, tt_add_f64, 0.0)
+    return lane63_f64(v);
+}
+__device__ __forceinline__ double wave_max_f64_dpp(double v)
+{
+    TT_DPP_SCAN(double, dpp_f64, fmax, -TT_INF)
+    return lane63_f64(v);
+}
+__device__ __forceinline__ double wave_min_f64_dpp(double v)
+{
+    TT_DPP_SCAN(double, dpp_f64, fmin, TT_INF)
+    return lane63_f64(v);
+}
+__device__ __forceinline__ int wave_min_i32_dpp(int v)
+{
+    TT_DPP_SCAN(int, dpp_i32, tt_min_i32, INT32_MAX)
+    return __builtin_amdgcn_readlane(v, 63);
+}
+#undef TT_DPP_SCAN
+
 __device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t x)
 {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);

@@ -227,9 +227,9 @@ tac_reg_kernel(const TacRegParams p)
                 for (int base = 0; base < R; base += 64) {                                \
                     const int r = base + lane;                                            \
                     const double x = r < R ? t[r] : 0.0;                                  \
-                    const double inc = wave_incl_scan_f64(x);                             \
+                    const double inc = wave_incl_scan_f64_dpp(x);                             \
                     if (r < R) A[r + 1] = carry + inc;                                    \
-                    carry += __shfl(inc, 63);                                             \
+                    carry += lane63_f64(inc);                                             \
                 }                                                                         \
                 if (lane == 0) A[0] = 0.0;                                                \
                 wave_sync();                                                              \
@@ -377,13 +377,13 @@ tac_reg_kernel(const TacRegParams p)
                 double lmin = TT_INF;
 #define TT_LMIN(k) if constexpr (k < KT) { if (pk_##k >= 0) lmin = fmin(lmin, M_##k); }
                 TT_EACH_K(TT_LMIN)
-                const double g = wave_min_f64(lmin);
+                const double g = wave_min_f64_dpp(lmin);
                 int cand = INT32_MAX;
                 if (g != TT_INF) {
 #define TT_CAND(k) if constexpr (k < KT) { if (pk_##k >= 0 && M_##k == g) cand = min(cand, first_alive<KT>(rows, aliveh, W, lane, k)); }
                     TT_EACH_K(TT_CAND)
                 }
-                best = wave_min_i32(cand);            // INT32_MAX when no M+ exists: fixed up below
+                best = wave_min_i32_dpp(cand);            // INT32_MAX when no M+ exists: fixed up below
                 if ((unsigned)best >= (unsigned)R) {  // no M+ exists: the lowest outstanding recv
                     for (int h = 2 * W - 1; h >= 0; --h) {
                         const uint32_t x = aliveh[h];
@@ -418,8 +418,8 @@ tac_reg_kernel(const TacRegParams p)
                                 if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);    \
                             }
                             TT_EACH_K(TT_MPLUS)
-                            mp_a = wave_min_f64(v);
-                            if (mp_best < 0.0) mp_best = wave_min_f64(u);
+                            mp_a = wave_min_f64_dpp(v);
+                            if (mp_best < 0.0) mp_best = wave_min_f64_dpp(u);
                             prec = mp_a < mp_best;
                         }
                         if (prec) { best = a; mp_best = mp_a; }
@@ -453,26 +453,26 @@ tac_reg_kernel(const TacRegParams p)
             for (int base = 0; base < R; base += 64) {
                 const int s = base + lane;
                 const double x = s < R ? t[ordl[s]] : 0.0;
-                const double inc = wave_incl_scan_f64(x);
+                const double inc = wave_incl_scan_f64_dpp(x);
                 if (s < R) P[s] = fc + inc;
-                fc += __shfl(inc, 63);
+                fc += lane63_f64(inc);
             }
             const double F = fc;
             wave_sync();
             double ct_sum = 0.0;
 #define TT_TOTAL(k) if constexpr (k < KT) { ct_sum += ct_##k; }
             TT_EACH_K(TT_TOTAL)
-            const double sum_c = wave_sum_f64(ct_sum);
+            const double sum_c = wave_sum_f64_dpp(ct_sum);
             double sfx = 0.0, mloc = sum_c;               // k = 0: F_0 + S_0 = all class time
             for (int base = ((R - 1) / 64) * 64; base >= 0; base -= 64) {
                 const int k = base + lane + 1;            // 1 <= k <= R handled here
                 const double x = k <= R ? A[k] : 0.0;
-                const double inc = wave_incl_scan_f64(x);
-                const double tot = __shfl(inc, 63);
+                const double inc = wave_incl_scan_f64_dpp(x);
+                const double tot = lane63_f64(inc);
                 if (k <= R) mloc = fmax(mloc, P[k - 1] + (sfx + (tot - inc + x)));
                 sfx += tot;
             }
-            const double m = wave_max_f64(mloc);
+            const double m = wave_max_f64_dpp(mloc);
             if (lane == 0) {
                 const double U = sum_c + F;
                 const double L = fmax(sum_c, F);

@@ -192,9 +192,9 @@ simulate_wave_kernel(const SimWaveParams p)
             const bool ok = (unsigned)r < (unsigned)R;      // an invalid entry is skipped, never dereferenced
             if (ok) pos[r] = (uint16_t)(s + 1);
             const double x = ok ? t[r] : 0.0;
-            const double inc = wave_incl_scan_f64(x);
+            const double inc = wave_incl_scan_f64_dpp(x);
             if (s < R) F[s] = fc + inc;
-            fc += __shfl(inc, 63);
+            fc += lane63_f64(inc);
         }
         const double Ftot = fc;
         for (int j = lane; j <= R; j += 64) A[j] = 0.0;
@@ -236,17 +236,17 @@ simulate_wave_kernel(const SimWaveParams p)
 #define SW_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); ct_sum += ct_##k; }
         SW_EACH_K(SW_RELEASE)
         wave_sync();
-        const double sum_c = wave_sum_f64(ct_sum);
+        const double sum_c = wave_sum_f64_dpp(ct_sum);
         double sfx = 0.0, mloc = sum_c;                   // k = 0: F_0 + S_0 = all class time
         for (int base = ((R - 1) / 64) * 64; base >= 0; base -= 64) {
             const int k = base + lane + 1;                // 1 <= k <= R handled here
             const double x = k <= R ? A[k] : 0.0;
-            const double inc = wave_incl_scan_f64(x);
-            const double tot = __shfl(inc, 63);
+            const double inc = wave_incl_scan_f64_dpp(x);
+            const double tot = lane63_f64(inc);
             if (k <= R) mloc = fmax(mloc, F[k - 1] + (sfx + (tot - inc + x)));
             sfx += tot;
         }
-        const double m = wave_max_f64(mloc);
+        const double m = wave_max_f64_dpp(mloc);
         if (lane == 0) {
             const double U = sum_c + Ftot;
             const double L = fmax(sum_c, Ftot);
