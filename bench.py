@@ -43,6 +43,11 @@ def parse() -> argparse.Namespace:
     return ap.parse_args()
 
 
+# HBM bytes per launch of the fused TAC + simulation kernel, FETCH_SIZE + WRITE_SIZE of the two
+# counter runs summarised in profiles/bench_resnet50_hbm_counters.md (scaled by the copy probe).
+# Only valid for the kernel and workload those runs measured; None otherwise.
+TAC_TRAFFIC_BYTES = {("resnet50", 65536): 720.01e6 + 96.08e6}
+
 # peaks of MI355X used for the roofline records
 HBM_PEAK_GBS = 8000.0
 FP64_VECTOR_PEAK_TFLOPS = 78.6
@@ -128,7 +133,8 @@ def main() -> int:
     ops_per_launch = tac_algorithmic_ops(nnz_ops, d.n_recv, d.n_compute) * B
     achieved = ops_per_launch / tac_s / 1e12
     roofline = {"kernel": "tac_reg_kernel (TAC + simulation fused)", "bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
+                "traffic": TAC_TRAFFIC_BYTES.get((args.workload, B)),
                 "ms_per_launch": tac_s * 1e3,
                 "hbm_GBs": (8.0 * (d.n_compute + d.n_recv) + 8.0 * d.n_recv) * B / tac_s / 1e9}
     sim_s = float(np.mean(sim_ms)) * 1e-3
