@@ -271,6 +271,32 @@ def layered_dag(seed: int, levels: int, width: int, fan_in: Tuple[int, int], bac
                recv_bytes=np.rint(sizes).astype(np.float64), seed=seed, **kw)
 
 
+def deep_narrow_dag(seed: int, levels: int, width: int, n_recv: int, name: str = "deep_narrow") -> Dag:
+    """``levels`` x ``width`` compute ops; op (lv, k) depends on op (lv-1, k) and on one op drawn
+    uniformly from all earlier levels (so most edges span many levels); each recv feeds one
+    uniformly chosen compute op.  Deep, narrow, with long edges."""
+    g = _rng(seed, _STREAM_STRUCT)
+    gs = _rng(seed, _STREAM_SIZE)
+    N, R = levels * width, n_recv
+    extra: List[List[int]] = [[] for _ in range(N)]
+    for i in range(R):
+        extra[int(g.integers(0, N))].append(i)
+    row_ptr = np.zeros(R + N + 1, dtype=np.int64)
+    cols: List[int] = []
+    for lv in range(levels):
+        for k in range(width):
+            c = lv * width + k
+            cols.extend(sorted(extra[c]))
+            if lv >= 1:
+                far = int(g.integers(0, lv * width))
+                cols.extend(sorted({R + (lv - 1) * width + k, R + far}))
+            row_ptr[R + c + 1] = len(cols)
+    sizes = gs.uniform(1e3, 4e6, size=R)
+    return Dag(name=name, n_ops=R + N, row_ptr=row_ptr.astype(np.int32),
+               col_idx=np.array(cols, dtype=np.int32), recv_ids=np.arange(R, dtype=np.int32),
+               op_median=np.full(N, 1e-3, dtype=np.float64), recv_bytes=np.rint(sizes).astype(np.float64), seed=seed)
+
+
 def chain_dag(n_recv: int, seed: int = 0, name: str = "chain") -> Dag:
     """``c_1 <- r_1``; ``c_k <- {c_{k-1}, r_k}``: a layer-by-layer model."""
     b = _Builder()

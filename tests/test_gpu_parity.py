@@ -64,6 +64,12 @@ SMALL = {
     "case2": wl.case2_dag,
     "single": lambda: wl.chain_dag(1),
     "mini_stress": lambda: wl.stress_dag(levels=40, width=50, n_recv=300, seed=14, batch=64),
+    # a level wider than one pass of the propagation workgroup (W = 18 words, 1 500 ops per level)
+    "wide_levels": lambda: wl.layered_dag(21, levels=4, width=1500, fan_in=(2, 3), back=1, n_recv=1100, attach=(1, 3)),
+    # deep and narrow with edges that span thousands of positions: inputs that have left the LDS ring
+    "long_edges": lambda: wl.deep_narrow_dag(22, levels=2500, width=4, n_recv=60),
+    # the same with wider rows (W = 3 words, four-word slices)
+    "long_edges_w3": lambda: wl.deep_narrow_dag(23, levels=1300, width=4, n_recv=150),
 }
 PRESETS = ["tiny", "resnet50", "vgg16", "inception3", "stress"]
 
