@@ -154,6 +154,19 @@ def run_tac_sim_parity(tt, d, h, dep, op, rv, tag):
         np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-300, err_msg=f"{tag}: fused {nm}")
     # the presets are quantised: results are exact, not merely close
     assert np.array_equal(got[0], exp[0]) and np.array_equal(fused[4].cpu().numpy(), exp[0])
+    # the same two calls without the per-round outputs: small graphs then run in the
+    # one-wave-per-sample kernels that the benchmark times
+    o2, r2 = tt.tac_priority(h, gop, grv, want_rank=True)[:2]
+    assert np.array_equal(o2.cpu().numpy(), eo), f"{tag}: TAC order (no sel) differs"
+    assert np.array_equal(r2.cpu().numpy(), er)
+    fused2 = tt.tac_simulate(h, gop, grv, want_rank=True)
+    assert np.array_equal(fused2[0].cpu().numpy(), eo), f"{tag}: fused order (no sel) differs"
+    assert np.array_equal(fused2[1].cpu().numpy(), er)
+    for a, b, nm in zip(fused2[4:], exp, "m E U L S".split()):
+        np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-300, err_msg=f"{tag}: fused (no sel) {nm}")
+    assert np.array_equal(fused2[4].cpu().numpy(), exp[0])
+    o3 = tt.tac_priority(h, gop, grv)[0]
+    assert np.array_equal(o3.cpu().numpy(), eo)
 
     if R:
         tic_order = oracle.tic(dep, d.recv_ids)[1]
