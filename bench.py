@@ -35,8 +35,11 @@ def parse() -> argparse.Namespace:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet50", choices=["tiny", "resnet50", "vgg16", "inception3", "stress"])
     ap.add_argument("--batch", type=int, default=0, help="override B of the preset (0 = preset's)")
-    ap.add_argument("--cpu-samples", type=int, default=256, help="samples the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-samples", type=int, default=1024, help="samples the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-deps-bench", action="store_true", help="skip the propagation timing on the stress preset")
+    ap.add_argument("--deps-batch", type=int, default=8,
+                    help="independent instances of the stress graph propagated concurrently on streams of their own "
+                         "(a run beyond the configuration: one graph alone is bound by the latency of its level chain); 0 = skip")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB, the known-size "
                          "reference that hardware byte counters of a profiler run are scaled by")
@@ -142,6 +145,22 @@ def main() -> int:
                 "hbm_GBs": (8.0 * (d.n_compute + d.n_recv) + 4.0 * d.n_recv + 16.0) * B / sim_s / 1e9}
     simulate["frac_of_hbm_peak"] = simulate["hbm_GBs"] / HBM_PEAK_GBS
 
+    # ---- a plain device copy on the same box, the practical ceiling next to the published peak ----
+    cx = torch.zeros(1 << 26, dtype=torch.float64, device="cuda")      # 512 MiB read + 512 MiB written
+    cy = torch.empty_like(cx)
+    copy_ms = []
+    for i in range(6):
+        a, b = ev(), ev()
+        a.record()
+        torch.add(cx, 1.0, out=cy)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            copy_ms.append(a.elapsed_time(b))
+    copy_GBs = 2.0 * cx.numel() * 8 / (float(np.mean(copy_ms)) * 1e-3) / 1e9
+    del cx, cy
+    simulate["frac_of_device_copy"] = simulate["hbm_GBs"] / copy_GBs
+
     # ---- dependency-bitset propagation bandwidth on the stress preset ----
     dep_bitset = None
     if not args.no_deps_bench:
@@ -160,7 +179,30 @@ def main() -> int:
         alg_bytes = ds.n_ops * ds.words * 8 + 4 * (ds.n_ops + 1 + ds.n_edges)
         dep_bitset = {"workload": "stress", "n_ops": ds.n_ops, "words": ds.words, "levels": hs.n_levels,
                       "us_per_launch": k1_s * 1e6, "GB/s": alg_bytes / k1_s / 1e9,
-                      "frac_of_hbm_peak": alg_bytes / k1_s / 1e9 / HBM_PEAK_GBS}
+                      "frac_of_hbm_peak": alg_bytes / k1_s / 1e9 / HBM_PEAK_GBS,
+                      "frac_of_device_copy": alg_bytes / k1_s / 1e9 / copy_GBs,
+                      "device_copy_GB/s": copy_GBs}
+        if args.deps_batch > 1:
+            # beyond the configuration: G instances of the same graph, each on its own stream
+            G = args.deps_batch
+            hb = [hs] + [tt.build_deps(ds.n_ops, ds.row_ptr, ds.col_idx, ds.recv_ids) for _ in range(G - 1)]
+            streams = [torch.cuda.Stream() for _ in range(G)]
+            torch.cuda.synchronize()
+            bt = []
+            for i in range(5):
+                t0 = time.perf_counter()
+                for hh, st in zip(hb, streams):
+                    with torch.cuda.stream(st):
+                        hh.recompute_deps()
+                torch.cuda.synchronize()
+                if i >= 2:
+                    bt.append(time.perf_counter() - t0)
+            bs = float(np.mean(bt))
+            dep_bitset["batched"] = {"instances": G, "us_total": bs * 1e6, "GB/s": G * alg_bytes / bs / 1e9,
+                                     "frac_of_hbm_peak": G * alg_bytes / bs / 1e9 / HBM_PEAK_GBS,
+                                     "note": "G independent graphs on G streams, wall clock; beyond the configuration"}
+            for hh in hb[1:]:
+                hh.close()
         hs.close()
 
     if args.copy_probe:
