@@ -41,6 +41,16 @@ constexpr int LVL_CHUNK = 512;
 // Workgroup barrier that waits for this wave's LDS traffic only.  The per-level barrier must
 // not wait for the global stores of the level (a trip to memory per level); rows that have
 // left the LDS ring are read from memory only after a barrier that did drain the stores.
+// Slice of the row words that a workgroup owns.  Consecutive workgroups are placed on
+// different XCDs (eight of them, each with an L2 of its own); when the number of slices is a
+// multiple of eight, the slices are dealt so that every XCD gets a run of adjacent slices
+// and the narrow stores of one row meet in one L2 before they are written back.
+__device__ __forceinline__ int slice_of_block()
+{
+    const int b = blockIdx.x, n = gridDim.x;
+    return (n & 7) == 0 ? (b & 7) * (n >> 3) + (b >> 3) : b;
+}
+
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void drain_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -51,7 +61,7 @@ propagate_nodes_wide(const PropParams p)
     extern __shared__ uint64_t ring[];                  // [ring][WC], then records, then level bounds
     const int W = p.W;
     const int w = threadIdx.x % WC;                     // word of the slice
-    const int gw = blockIdx.x * WC + w;                 // word of the row
+    const int gw = slice_of_block() * WC + w;           // word of the row
     const int sub = threadIdx.x / WC;                   // node within a pass over a level
     const int per_pass = blockDim.x / WC;
     const uint32_t rmask = (uint32_t)p.ring - 1u;
@@ -188,7 +198,7 @@ propagate_nodes(const PropParams p, const int32_t *__restrict__ chunk_end)
     extern __shared__ uint64_t ring[];                  // [ring][WC], records [2][CH], level windows
     const int W = p.W, L = p.n_levels;
     const int w = threadIdx.x % WC;
-    const int gw = blockIdx.x * WC + w;
+    const int gw = slice_of_block() * WC + w;
     const int sub = threadIdx.x / WC;
     const int per_pass = blockDim.x / WC;
     const int CH = RPT * per_pass;                      // most positions of a chunk
