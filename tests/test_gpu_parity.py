@@ -209,6 +209,19 @@ def test_ties_and_zero_times(tt, name):
     run_tac_sim_parity(tt, d, h, dep, op, rv0, name + "/zero-transfers")
 
 
+@pytest.mark.parametrize("n_recv", [63, 64, 65, 128, 129])
+def test_word_boundaries_and_ragged_batches(tt, n_recv):
+    """Recv counts at and around multiples of the 64-bit word, batches that do not fill a
+    workgroup of four waves (1 and 7 samples)."""
+    name = f"r{n_recv}"
+    d, h, dep = get(tt, name, lambda: wl.layered_dag(30 + n_recv, levels=7, width=9, fan_in=(1, 3), back=2,
+                                                      n_recv=n_recv, attach=(1, 3)))
+    assert np.array_equal(h.deps().cpu().numpy().view(np.uint64), dep)
+    for B in (1, 7):
+        op, rv = wl.timing_samples(d, 0, B)
+        run_tac_sim_parity(tt, d, h, dep, op, rv, f"{name}/B{B}")
+
+
 def test_random_orders_per_sample(tt):
     d, h, dep = get(tt, "layered70", SMALL["layered70"])
     rng = np.random.default_rng(8)
