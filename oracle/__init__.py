@@ -144,3 +144,16 @@ def simulate(n_ops: int, row_ptr, col_idx, recv_ids, order, op_time, recv_time, 
                                  _p(key), *(_p(o) for o in out))
     _check(rc, "oracle_simulate")
     return tuple(out)
+
+
+def straggler(makespan, w: int) -> np.ndarray:
+    """Sec. 6, Straggler Effect: per group of ``w`` consecutive samples, the longest wait of any
+    worker over the iteration time, ``(max - min) / max`` of the group's makespans.
+    Returns ``[B // w]``."""
+    makespan = _f64(makespan)
+    B = makespan.size
+    out = np.zeros(B // w if w >= 1 else 0)
+    rc = _load().oracle_straggler(ctypes.c_int(B), ctypes.c_int(w), _p(makespan), _p(out))
+    _check(rc, "oracle_straggler")
+    return out
+

@@ -429,3 +429,28 @@ int oracle_simulate(int n, const int32_t *row_ptr, const int32_t *col_idx, int R
     free(ri); free(sptr); free(sidx); free(fill); free(waiting); free(time); free(h.key); free(h.op);
     return rc;
 }
+
+/* ---------------------------------------------------------------------------
+ * Straggler effect (Sec. 6, "Straggler Effect"): workers that run one synchronous
+ * iteration together all wait for the slowest; the effect is the longest wait of any
+ * worker as a fraction of the iteration time.  Here the workers of group g are the w
+ * consecutive samples g*w .. g*w + w - 1 with makespans m_i:
+ *     iteration time T = max m_i,  longest wait = T - min m_i,  effect = (T - min m_i) / T,
+ * 0 when T == 0.  Groups: B / w (whole groups only).
+ * ------------------------------------------------------------------------- */
+int oracle_straggler(int B, int w, const double *makespan, double *out)
+{
+    if (B < 0 || w < 1) return -2;
+    if (B > 0 && (!makespan || !out)) return -1;
+    for (int g = 0; g < B / w; ++g) {
+        double mx = makespan[(size_t)g * w], mn = mx;
+        for (int i = 1; i < w; ++i) {
+            const double m = makespan[(size_t)g * w + i];
+            if (m > mx) mx = m;
+            if (m < mn) mn = m;
+        }
+        out[g] = mx > 0.0 ? (mx - mn) / mx : 0.0;
+    }
+    return 0;
+}
+

@@ -388,3 +388,48 @@ def test_partial_rounds_prefix():
     part = oracle.tac(dep, d.recv_ids, op, rv, max_rounds=5)[0]
     np.testing.assert_array_equal(part[:, :5], full[:, :5])
     assert (part[:, 5:] == -1).all()
+
+
+# --------------------------------------------------------------------------
+# Straggler effect (Sec. 6): longest wait over iteration time, per group of workers
+# --------------------------------------------------------------------------
+
+def test_straggler_effect_closed_forms():
+    # hand-computed: workers that finish at 8, 10 and 5 s wait 2, 0 and 5 s of a 10 s iteration
+    assert np.array_equal(oracle.straggler([8.0, 10.0, 5.0], 3), [0.5])
+    # identical workers never wait; a single worker has nobody to wait for
+    assert np.array_equal(oracle.straggler([3.0, 3.0, 3.0, 3.0], 2), [0.0, 0.0])
+    assert np.array_equal(oracle.straggler([1.0, 7.0, 2.0], 1), [0.0, 0.0, 0.0])
+    # a worker with nothing to do waits for the whole iteration; an all-zero group gives 0
+    assert np.array_equal(oracle.straggler([0.0, 4.0, 0.0, 0.0], 2), [1.0, 0.0])
+    # whole groups only: the trailing sample is not used
+    assert np.array_equal(oracle.straggler([2.0, 4.0, 100.0], 2), [0.5])
+    assert oracle.straggler([], 4).size == 0
+    rng = np.random.default_rng(5)
+    m = rng.integers(1, 1000, size=96).astype(np.float64)
+    for w in (2, 3, 8, 32):
+        s = oracle.straggler(m, w)
+        g = m[:96 // w * w].reshape(-1, w)
+        assert np.array_equal(s, (g.max(axis=1) - g.min(axis=1)) / g.max(axis=1))
+        assert np.array_equal(oracle.straggler(m * 8, w), s)                 # scale-free
+        assert np.array_equal(oracle.straggler(g[:, ::-1].ravel(), w), s)    # order of the workers
+        assert (s >= 0).all() and (s < 1).all()
+
+
+def test_straggler_effect_of_the_toy_graph_orders():
+    """Two workers on the toy graph of Sec. 2.2, one with the good transfer order and one with
+    the bad one: the makespans the fixture gives by hand (8 s and 10 s) mean the first worker
+    waits 2 s of a 10 s iteration."""
+    g = read_golden("fig1_toy.txt")
+    d = wl.toy_dag()
+    op = np.tile(np.array(g["op_time"], dtype=np.float64), (2, 1))
+    rv = np.tile(np.array(g["recv_time"], dtype=np.float64), (2, 1))
+    orders = np.array([[0, 1], [1, 0]], dtype=np.int32)
+    m = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, orders, op, rv)[0]
+    assert m.tolist() == [g["makespan_order_0_1"][0], g["makespan_order_1_0"][0]]
+    assert oracle.straggler(m, 2).tolist() == [0.2]
+    # both workers on the same order: no straggler, whatever the order
+    for o in orders:
+        m1 = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, np.tile(o, (2, 1)), op, rv)[0]
+        assert oracle.straggler(m1, 2).tolist() == [0.0]
+
