@@ -153,6 +153,18 @@ int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time,
                         double *makespan, double *eff, double *U, double *L, double *S,
                         tictac_stream stream);
 
+/*
+ * Sec. 6, "Straggler Effect": workers that run one synchronous iteration together wait
+ * for the slowest one; the effect is the longest wait of any worker as a fraction of the
+ * iteration time.  The workers of group g are the w consecutive samples g*w .. g*w+w-1:
+ *     straggler[g] = (max m_i - min m_i) / max m_i   over the group, 0 when the maximum is 0.
+ *   makespan  [B]      device (as written by tictac_simulate / tictac_tac_simulate)
+ *   straggler [B / w]  device; only whole groups are formed, trailing samples are not used
+ * w >= 1 (TICTAC_ERR_UNSUPPORTED otherwise); B = 0 is valid.
+ */
+int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double *straggler,
+                            tictac_stream stream);
+
 /* Message of the last error on the calling thread; valid until its next call. */
 const char *tictac_last_error(void);
 

@@ -30,6 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
+    "tictac_straggler_effect",
     "tictac_last_error", "tictac_version",
 )
 
@@ -168,6 +169,15 @@ def simulate(dag: Dag, order: torch.Tensor, op_time: torch.Tensor, recv_time: to
     _check(lib().tictac_simulate(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride), _dev(op_time),
                                  _dev(recv_time), *(_dev(o) for o in out), _stream()))
     return tuple(out)
+
+
+def straggler_effect(makespan: torch.Tensor, w: int) -> torch.Tensor:
+    """``tictac_straggler_effect``: float64 CUDA tensor ``[B // w]``."""
+    assert makespan.is_cuda and makespan.dtype == torch.float64 and makespan.is_contiguous() and makespan.dim() == 1
+    B = makespan.shape[0]
+    out = torch.empty(B // w if w >= 1 else 0, dtype=torch.float64, device="cuda")
+    _check(lib().tictac_straggler_effect(ctypes.c_int32(B), ctypes.c_int32(w), _dev(makespan), _dev(out), _stream()))
+    return out
 
 
 def tac_simulate(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_rank: bool = False,

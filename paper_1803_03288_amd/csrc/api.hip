@@ -567,6 +567,16 @@ int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int3
     return TICTAC_OK;
 }
 
+int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double *straggler, tictac_stream stream)
+{
+    if (B < 0) { set_error("B = %d is negative", B); return TICTAC_ERR_UNSUPPORTED; }
+    if (w < 1) { set_error("w = %d, expected at least 1", w); return TICTAC_ERR_UNSUPPORTED; }
+    if (B / w == 0) return TICTAC_OK;
+    if (!makespan || !straggler) { set_error("makespan or straggler is NULL"); return TICTAC_ERR_NULL; }
+    HIP_TRY(launch_straggler(B, w, makespan, straggler, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
 const char *tictac_last_error(void) { return g_err; }
 
 const char *tictac_version(void) { return "0.1"; }

@@ -122,5 +122,6 @@ struct SimArgs {
     double *makespan, *eff, *U, *L, *S;
 };
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
+hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s);
 
 }  // namespace tictac

@@ -339,6 +339,47 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
     return hipGetLastError();
 }
 
+// Straggler effect of groups of w consecutive samples (Sec. 6): (max - min) / max of their
+// makespans.  A group is spread over the lanes of one wave (w > 4) or handled by one thread.
+__global__ void __launch_bounds__(256)
+straggler_kernel(int32_t n_groups, int32_t w, const double *__restrict__ makespan, double *__restrict__ out)
+{
+    if (w <= 4) {
+        const int g = blockIdx.x * blockDim.x + threadIdx.x;
+        if (g >= n_groups) return;
+        double mx = makespan[(size_t)g * w], mn = mx;
+        for (int i = 1; i < w; ++i) {
+            const double m = makespan[(size_t)g * w + i];
+            mx = fmax(mx, m);
+            mn = fmin(mn, m);
+        }
+        out[g] = mx > 0.0 ? (mx - mn) / mx : 0.0;
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);     // wave-uniform
+    if (g >= n_groups) return;
+    double mx = -TT_INF, mn = TT_INF;
+    for (int i = lane; i < w; i += 64) {
+        const double m = makespan[(size_t)g * w + i];
+        mx = fmax(mx, m);
+        mn = fmin(mn, m);
+    }
+    mx = wave_max_f64_dpp(mx);
+    mn = wave_min_f64_dpp(mn);
+    if (lane == 0) out[g] = mx > 0.0 ? (mx - mn) / mx : 0.0;
+}
+
+hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s)
+{
+    const int32_t n_groups = B / w;
+    if (n_groups == 0) return hipSuccess;
+    const int per_block = w <= 4 ? 256 : 4;
+    hipLaunchKernelGGL(straggler_kernel, dim3((n_groups + per_block - 1) / per_block), dim3(256), 0, s,
+                       n_groups, w, makespan, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;

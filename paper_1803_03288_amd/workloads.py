@@ -42,7 +42,7 @@ QUANTUM = 2.0 ** -30          # seconds
 LINK_BITS_PER_S = 1.0e10      # 10 Gb/s link of every preset
 CHUNK = 256                   # samples per independently seeded chunk
 
-_STREAM_STRUCT, _STREAM_SIZE, _STREAM_OP, _STREAM_RECV = 0, 1, 2, 3
+_STREAM_STRUCT, _STREAM_SIZE, _STREAM_OP, _STREAM_RECV, _STREAM_ORDER = 0, 1, 2, 3, 4
 
 
 def _rng(seed: int, stream: int, chunk: int = 0) -> np.random.Generator:
@@ -204,6 +204,24 @@ def timing_samples(dag: Dag, b0: int = 0, b1: Optional[int] = None) -> Tuple[np.
         op[lo - b0:hi - b0] = quantise(blk[s])
         rv[lo - b0:hi - b0] = quantise(blk_r[s])
     return op, rv
+
+
+def random_orders(dag: Dag, b0: int = 0, b1: Optional[int] = None) -> np.ndarray:
+    """Rows ``b0..b1-1`` of ``[B][R]`` int32: one uniformly random transfer order per sample, the
+    stand-in for a system that imposes no order (every iteration and worker sees another one)."""
+    if b1 is None:
+        b1 = dag.batch
+    assert 0 <= b0 <= b1
+    R = dag.n_recv
+    out = np.empty((b1 - b0, R), dtype=np.int32)
+    for c in range(b0 // CHUNK, (b1 + CHUNK - 1) // CHUNK):
+        lo, hi = max(b0, c * CHUNK), min(b1, (c + 1) * CHUNK)
+        if hi <= lo:
+            continue
+        keys = _rng(dag.seed, _STREAM_ORDER, c).random((CHUNK, R))
+        blk = np.argsort(keys, axis=1, kind="stable").astype(np.int32)
+        out[lo - b0:hi - b0] = blk[lo - c * CHUNK:hi - c * CHUNK]
+    return out
 
 
 def sample_rows(dag: Dag, rows: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:

@@ -234,6 +234,39 @@ def test_random_orders_per_sample(tt):
         assert np.array_equal(a, b)
 
 
+def test_random_order_baseline_and_straggler_effect(tt):
+    """The no-scheduling baseline (one random transfer order per sample) against TIC and TAC on the
+    same samples, and the straggler effect of groups of w workers: simulation and group
+    reduction equal to the oracle, element by element."""
+    d, h, dep = get(tt, "resnet50")
+    B = 96
+    op, rv = wl.timing_samples(d, 0, B)
+    orders = wl.random_orders(d, 0, B)
+    assert np.array_equal(np.sort(orders, axis=1), np.tile(np.arange(d.n_recv, dtype=np.int32), (B, 1)))
+    gop, grv = cuda(op), cuda(rv)
+    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, orders, op, rv)
+    got = tt.simulate(h, cuda(orders), gop, grv)
+    for a, b in zip(got, exp):
+        assert np.array_equal(a.cpu().numpy(), b)
+    m_tac = tt.tac_simulate(h, gop, grv)[4]
+    m_tic = tt.simulate(h, tt.tic_priority(h)[1], gop, grv)[0]
+    for m in (got[0], m_tac, m_tic):
+        mh = m.cpu().numpy()
+        for w in (1, 2, 3, 4, 5, 8, 16, 96, 97):
+            s = tt.straggler_effect(m, w).cpu().numpy()
+            assert np.array_equal(s, oracle.straggler(mh, w)), w
+    # a random order is never better than the lower bound and, here, worse than TAC on average
+    assert (got[0].cpu().numpy() >= exp[3]).all()
+    assert got[0].mean() > m_tac.mean()
+    # degenerate inputs
+    assert tt.straggler_effect(torch.zeros(0, dtype=torch.float64, device="cuda"), 4).numel() == 0
+    z = tt.straggler_effect(torch.zeros(8, dtype=torch.float64, device="cuda"), 4).cpu().numpy()
+    assert np.array_equal(z, [0.0, 0.0])
+    big = torch.from_numpy(np.random.default_rng(1).integers(1, 10**6, size=5000).astype(np.float64)).cuda()
+    for w in (7, 64, 65, 1000, 5000):
+        assert np.array_equal(tt.straggler_effect(big, w).cpu().numpy(), oracle.straggler(big.cpu().numpy(), w))
+
+
 def test_power_of_two_scaling_and_determinism(tt):
     d, h, dep = get(tt, "resnet50")
     op, rv = wl.timing_samples(d, 0, 64)
