@@ -37,6 +37,8 @@ def parse() -> argparse.Namespace:
     ap.add_argument("--batch", type=int, default=0, help="override B of the preset (0 = preset's)")
     ap.add_argument("--cpu-samples", type=int, default=1024, help="samples the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-deps-bench", action="store_true", help="skip the propagation timing on the stress preset")
+    ap.add_argument("--no-compare", action="store_true",
+                    help="skip the comparison of random, TIC and TAC orders (efficiency, straggler effect)")
     ap.add_argument("--deps-batch", type=int, default=8,
                     help="independent instances of the stress graph propagated concurrently on streams of their own "
                          "(a run beyond the configuration: one graph alone is bound by the latency of its level chain); 0 = skip")
@@ -145,6 +147,25 @@ def main() -> int:
                 "hbm_GBs": (8.0 * (d.n_compute + d.n_recv) + 4.0 * d.n_recv + 16.0) * B / sim_s / 1e9}
     simulate["frac_of_hbm_peak"] = simulate["hbm_GBs"] / HBM_PEAK_GBS
 
+    # ---- no scheduling (a random order per sample) against TIC and TAC on the same samples ----
+    comparison = None
+    if not args.no_compare and d.n_recv > 0:
+        t0 = time.time()
+        rnd = torch.from_numpy(wl.random_orders(d, 0, B)).cuda()
+        tic_order = tt.tic_priority(h)[1]
+        legs = {"random": tt.simulate(h, rnd, gop, grv), "tic": tt.simulate(h, tic_order, gop, grv), "tac": out}
+        comparison = {}
+        for name_, r_ in legs.items():
+            m_, e_ = r_[0], r_[1]
+            rec = {"mean_makespan_s": float(m_.mean()), "mean_efficiency": float(e_.mean()),
+                   "min_efficiency": float(e_.min())}
+            for w_ in (2, 4, 8, 16):
+                s_ = tt.straggler_effect(m_, w_)
+                rec[f"straggler_w{w_}"] = {"mean": float(s_.mean()), "max": float(s_.max())}
+            comparison[name_] = rec
+        torch.cuda.synchronize()
+        print(f"[bench] order comparison in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
     # ---- a plain device copy on the same box, the practical ceiling next to the published peak ----
     cx = torch.zeros(1 << 26, dtype=torch.float64, device="cuda")      # 512 MiB read + 512 MiB written
     cy = torch.empty_like(cx)
@@ -235,7 +256,8 @@ def main() -> int:
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{d.name} preset (seed {d.seed}): N={d.n_compute} compute ops, R={d.n_recv} recvs, "
                                f"B={B} timing samples; step = build_deps + TIC + fused TAC/simulate"},
-        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "cpu_baseline": cpu,
+        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison,
+        "cpu_baseline": cpu,
         "mean_scheduling_efficiency": mean_eff,
     }
     print(json.dumps(line))
