@@ -60,7 +60,11 @@ struct TacRegParams {
     int32_t n_waves;            // total waves of the grid
 };
 
-constexpr int kRegWaves = 4;           // waves per workgroup
+// Waves per workgroup.  The class rows in LDS are shared by the workgroup, so with many classes
+// per lane (large rows, many registers: three waves per SIMD at most) one large workgroup
+// per compute unit leaves the most LDS to the per-wave arrays.
+constexpr int kRegWavesMax = 12;
+constexpr int reg_waves(int KT) { return KT <= 4 ? 4 : kRegWavesMax; }
 constexpr int CNT1 = 1 << 20;          // one unit of the outstanding count in `packed`
 constexpr int IDX_MASK = CNT1 - 1;
 
@@ -81,7 +85,7 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
 #define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
 template <int KT>
-__global__ void __launch_bounds__(64 * kRegWaves, (KT <= 3 ? 6 : (KT <= 4 ? 5 : 2)))
+__global__ void __launch_bounds__(64 * reg_waves(KT), (KT <= 3 ? 6 : (KT <= 4 ? 5 : 1)))
 tac_reg_kernel(const TacRegParams p)
 {
     extern __shared__ double smem[];
@@ -122,7 +126,7 @@ tac_reg_kernel(const TacRegParams p)
     const uint32_t *rows_lane = rows + lane * KT;      // this lane's KT words of half-row 0
     double *csum = P;                                  // [64 KT] class totals while they are summed (spans P and A)
 
-    const int gwave = blockIdx.x * kRegWaves + wave;
+    const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
         const double *rt = p.recv_time + (size_t)b * R;
         const double *ot = p.op_time + (size_t)b * N;
@@ -492,8 +496,11 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
     // LDS: shared rows + per wave t [R], P [R+1], A [R+1], ordl [R] i32, outstanding set [2W] u32
     const size_t rows_doubles = ((size_t)2 * d.W * 64 * KT + 1) / 2;
     const size_t per_wave = (size_t)d.R + 2 * (d.R + 1) + ((size_t)d.R + 2 * d.W + 1) / 2 + 1;
-    const size_t lds = (rows_doubles + per_wave * kRegWaves) * 8;
-    if (lds > 80 * 1024) return hipErrorNotSupported;
+    // as many waves as LDS allows, at most reg_waves(KT)
+    int waves = reg_waves(KT);
+    while (waves > 4 && (rows_doubles + per_wave * waves) * 8 > 150 * 1024) --waves;
+    const size_t lds = (rows_doubles + per_wave * waves) * 8;
+    if (lds > (waves > 4 ? 150 : 80) * 1024) return hipErrorNotSupported;
     p.wave_doubles = (int32_t)per_wave;
     // the class totals are summed in the space of P and A when that holds one double per class slot
     p.col_cls = (size_t)64 * KT <= 2 * ((size_t)d.R + 1) ? d.d_col_cls : nullptr;
@@ -504,7 +511,7 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT>, 64 * kRegWaves, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT>, 64 * waves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
     int n_cu = 256;
@@ -512,10 +519,10 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
     if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
         n_cu = prop.multiProcessorCount;
     int grid = per_cu * n_cu;                       // one resident set of workgroups, no tail
-    const int need = (p.B + kRegWaves - 1) / kRegWaves;
+    const int need = (p.B + waves - 1) / waves;
     if (grid > need) grid = need;
-    p.n_waves = grid * kRegWaves;
-    hipLaunchKernelGGL((tac_reg_kernel<KT>), dim3(grid), dim3(64 * kRegWaves), lds, s, p);
+    p.n_waves = grid * waves;
+    hipLaunchKernelGGL((tac_reg_kernel<KT>), dim3(grid), dim3(64 * waves), lds, s, p);
     return hipGetLastError();
 }
 
