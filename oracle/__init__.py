@@ -146,6 +146,31 @@ def simulate(n_ops: int, row_ptr, col_idx, recv_ids, order, op_time, recv_time, 
     return tuple(out)
 
 
+def simulate_channels(n_ops: int, row_ptr, col_idx, recv_ids, n_channels: int, channel_of_recv, order, op_time,
+                      recv_time):
+    """Sec. 4.1 / 5.1: the iteration of ``simulate`` with ``n_channels`` channels side by side; recv
+    ``i`` uses channel ``channel_of_recv[i]`` and every channel serves its recvs in the order in
+    which they appear in ``order``.  Returns ``(makespan, E, U, L, S)``, each ``[B]``."""
+    row_ptr, col_idx, recv_ids = _i32(row_ptr), _i32(col_idx), _i32(recv_ids)
+    op_time, recv_time, order, chan = _f64(op_time), _f64(recv_time), _i32(order), _i32(channel_of_recv)
+    R = recv_ids.size
+    B = recv_time.shape[0]
+    assert op_time.shape == (B, n_ops - R) and recv_time.shape == (B, R) and chan.shape == (R,)
+    if order.ndim == 1:
+        assert order.shape == (R,)
+        stride = 0
+    else:
+        assert order.shape == (B, R)
+        stride = R
+    out = [np.zeros(B) for _ in range(5)]
+    rc = _load().oracle_simulate_channels(ctypes.c_int(n_ops), _p(row_ptr), _p(col_idx), ctypes.c_int(R),
+                                          _p(recv_ids), ctypes.c_int(n_channels), _p(chan), ctypes.c_int(B),
+                                          _p(order), ctypes.c_int(stride), _p(op_time), _p(recv_time),
+                                          *(_p(o) for o in out))
+    _check(rc, "oracle_simulate_channels")
+    return tuple(out)
+
+
 def straggler(makespan, w: int) -> np.ndarray:
     """Sec. 6, Straggler Effect: per group of ``w`` consecutive samples, the longest wait of any
     worker over the iteration time, ``(max - min) / max`` of the group's makespans.

@@ -430,6 +430,125 @@ int oracle_simulate(int n, const int32_t *row_ptr, const int32_t *col_idx, int R
     return rc;
 }
 
+/* ------------------------------------------------------------------------
+ * The same iteration with several channels (Sec. 4.1: a device has one channel per
+ * parameter server it talks to; Sec. 5.1: each channel carries one transfer at a time, in
+ * priority order).  Recv i uses channel channel_of_recv[i]; every channel serves its own
+ * recvs back-to-back from t = 0, in the order in which they appear in `order`, and the
+ * channels run side by side.  The compute device is as in oracle_simulate.
+ *   L = max(sum of compute times, largest per-channel sum of recv times)   (Eq. 2: one
+ *   term per resource); everything else as in oracle_simulate.
+ * ---------------------------------------------------------------------- */
+int oracle_simulate_channels(int n, const int32_t *row_ptr, const int32_t *col_idx, int R,
+                             const int32_t *recv_ids, int n_channels, const int32_t *channel_of_recv,
+                             int B, const int32_t *order, int order_stride, const double *op_time,
+                             const double *recv_time, double *makespan, double *eff,
+                             double *U_out, double *L_out, double *S_out)
+{
+    if (n_channels < 1) return ORACLE_ERR_ARG;
+    for (int i = 0; i < R; ++i)
+        if (channel_of_recv[i] < 0 || channel_of_recv[i] >= n_channels) return ORACLE_ERR_ARG;
+    const int N = n - R, C = n_channels;
+    const size_t n1 = (size_t)(n > 0 ? n : 1), r1 = (size_t)(R > 0 ? R : 1);
+    int32_t *ri = recv_index_of_op(n, R, recv_ids);
+    int32_t *sptr = (int32_t *)calloc(n1 + 1, sizeof(int32_t));
+    int32_t *sidx = (int32_t *)malloc((size_t)(row_ptr[n] > 0 ? row_ptr[n] : 1) * sizeof(int32_t));
+    int32_t *fill = (int32_t *)malloc(n1 * sizeof(int32_t));
+    int32_t *waiting = (int32_t *)malloc(n1 * sizeof(int32_t));
+    double *time = (double *)malloc(n1 * sizeof(double));
+    heap_t h = { (int32_t *)malloc(n1 * sizeof(int32_t)), (int32_t *)malloc(n1 * sizeof(int32_t)), 0 };
+    /* per channel: its queue of recv indices (a slice of `queue`), the next one to complete,
+       the completion time of the transfer in progress, the sum of its transfer times */
+    int32_t *queue = (int32_t *)malloc(r1 * sizeof(int32_t));
+    int32_t *qbeg = (int32_t *)malloc(((size_t)C + 1) * sizeof(int32_t));
+    int32_t *qnext = (int32_t *)malloc((size_t)C * sizeof(int32_t));
+    double *qend = (double *)malloc((size_t)C * sizeof(double));
+    double *qsum = (double *)malloc((size_t)C * sizeof(double));
+    if (!ri || !sptr || !sidx || !fill || !waiting || !time || !h.key || !h.op || !queue || !qbeg || !qnext ||
+        !qend || !qsum)
+        return ORACLE_ERR_MEM;
+    for (int v = 0; v < n; ++v)
+        for (int e = row_ptr[v]; e < row_ptr[v + 1]; ++e) sptr[col_idx[e] + 1]++;
+    for (int v = 0; v < n; ++v) sptr[v + 1] += sptr[v];
+    for (int v = 0; v < n; ++v) fill[v] = sptr[v];
+    for (int v = 0; v < n; ++v)
+        for (int e = row_ptr[v]; e < row_ptr[v + 1]; ++e) sidx[fill[col_idx[e]]++] = v;
+
+    int rc = ORACLE_OK;
+    for (int b = 0; b < B && rc == ORACLE_OK; ++b) {
+        const double *ot = op_time + (size_t)b * N, *rt = recv_time + (size_t)b * R;
+        const int32_t *ord = order + (size_t)b * order_stride;
+        int j = 0;
+        double sum_c = 0.0, sum_r = 0.0;
+        for (int v = 0; v < n; ++v) {
+            if (ri[v] >= 0) { time[v] = rt[ri[v]]; sum_r += time[v]; }
+            else { time[v] = ot[j++]; sum_c += time[v]; }
+            waiting[v] = row_ptr[v + 1] - row_ptr[v];
+        }
+        /* the queues: channel c takes its recvs in the order of `ord` */
+        int pos = 0;
+        for (int c = 0; c < C; ++c) {
+            qbeg[c] = pos;
+            qsum[c] = 0.0;
+            for (int k = 0; k < R; ++k)
+                if (channel_of_recv[ord[k]] == c) { queue[pos++] = ord[k]; qsum[c] += rt[ord[k]]; }
+            qnext[c] = qbeg[c];
+            qend[c] = (pos > qbeg[c]) ? rt[queue[qbeg[c]]] : 0.0;
+        }
+        qbeg[C] = pos;
+        h.len = 0;
+        for (int v = 0; v < n; ++v)
+            if (ri[v] < 0 && waiting[v] == 0) heap_push(&h, v, v);
+
+        double now = 0.0, m = 0.0;
+        int running = -1;
+        double run_end = 0.0;
+        int finished = 0;
+        while (finished < n) {
+            int acted = 0;
+            for (int c = 0; c < C; ++c)
+                while (qnext[c] < qbeg[c + 1] && qend[c] <= now) {
+                    int v = recv_ids[queue[qnext[c]]];
+                    if (qend[c] > m) m = qend[c];
+                    for (int e = sptr[v]; e < sptr[v + 1]; ++e)
+                        if (--waiting[sidx[e]] == 0) heap_push(&h, sidx[e], sidx[e]);
+                    ++finished; ++qnext[c]; acted = 1;
+                    if (qnext[c] < qbeg[c + 1]) qend[c] = qend[c] + rt[queue[qnext[c]]];
+                }
+            if (running >= 0 && run_end <= now) {
+                int v = running;
+                if (run_end > m) m = run_end;
+                for (int e = sptr[v]; e < sptr[v + 1]; ++e)
+                    if (--waiting[sidx[e]] == 0) heap_push(&h, sidx[e], sidx[e]);
+                running = -1; ++finished; acted = 1;
+            }
+            if (running < 0 && h.len > 0) {
+                running = heap_pop(&h);
+                run_end = now + time[running];
+                acted = 1;
+            }
+            if (acted) continue;
+            double nxt = HUGE_VAL;
+            for (int c = 0; c < C; ++c)
+                if (qnext[c] < qbeg[c + 1] && qend[c] < nxt) nxt = qend[c];
+            if (running >= 0 && run_end < nxt) nxt = run_end;
+            if (nxt == HUGE_VAL) { rc = ORACLE_ERR_CYCLE; break; }
+            now = nxt;
+        }
+        double U = sum_c + sum_r;
+        double L = sum_c;
+        for (int c = 0; c < C; ++c) if (qsum[c] > L) L = qsum[c];
+        makespan[b] = m;
+        eff[b] = (U == L) ? 1.0 : (U - m) / (U - L);
+        if (U_out) U_out[b] = U;
+        if (L_out) L_out[b] = L;
+        if (S_out) S_out[b] = (U == L || L == 0.0) ? 0.0 : (U - L) / L;
+    }
+    free(ri); free(sptr); free(sidx); free(fill); free(waiting); free(time); free(h.key); free(h.op);
+    free(queue); free(qbeg); free(qnext); free(qend); free(qsum);
+    return rc;
+}
+
 /* ---------------------------------------------------------------------------
  * Straggler effect (Sec. 6, "Straggler Effect"): workers that run one synchronous
  * iteration together all wait for the slowest; the effect is the longest wait of any

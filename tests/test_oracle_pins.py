@@ -433,3 +433,83 @@ def test_straggler_effect_of_the_toy_graph_orders():
         m1 = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, np.tile(o, (2, 1)), op, rv)[0]
         assert oracle.straggler(m1, 2).tolist() == [0.0]
 
+
+# --------------------------------------------------------------------------
+# Several channels (Sec. 4.1, 5.1)
+# --------------------------------------------------------------------------
+
+def release_date_makespan(dep_b, chan, n_channels, order, op, rv):
+    """The makespan from first principles, for one sample: the channels never wait (recvs are
+    roots), so recv r arrives at the sum of the transfer times queued before and including it on its
+    channel; a compute op is released when the last recv it depends on has arrived; a device that
+    never idles while an op is ready finishes at  max over release dates rho of
+    (rho + total time of the ops released at rho or later); the last arrival also bounds it."""
+    R = order.size
+    arrival = np.zeros(R)
+    for c in range(n_channels):
+        q = [r for r in order if chan[r] == c]
+        arrival[q] = np.cumsum(rv[q])
+    rho = (dep_b * arrival[None, :]).max(axis=1) if R else np.zeros(dep_b.shape[0])
+    m = arrival.max() if R else 0.0
+    for x in np.unique(rho):
+        m = max(m, x + op[rho >= x].sum())
+    return m
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_channels_equal_release_date_form_and_reduce_to_one_channel(seed):
+    rng = np.random.default_rng(100 + seed)
+    R = int(rng.integers(2, 14))
+    d = wl.layered_dag(200 + seed, levels=int(rng.integers(2, 6)), width=int(rng.integers(2, 6)), fan_in=(1, 3),
+                       back=2, n_recv=R, attach=(1, 3))
+    dep = oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    dep_b = dep_bool(dep, R)[d.compute_ids()]
+    B = 12
+    op = rng.integers(0, 40, size=(B, d.n_compute)).astype(np.float64) * 0.125
+    rv = rng.integers(1, 40, size=(B, R)).astype(np.float64) * 0.125
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    one = oracle.simulate(*args, orders, op, rv)
+    got1 = oracle.simulate_channels(*args, 1, np.zeros(R, np.int32), orders, op, rv)
+    for a, b in zip(one, got1):
+        assert np.array_equal(a, b)
+    prev = one[0]
+    for C in (2, 3, R):
+        chan = (np.arange(R) % C).astype(np.int32) if C == R else rng.integers(0, C, size=R).astype(np.int32)
+        m, e, U, L, S = oracle.simulate_channels(*args, C, chan, orders, op, rv)
+        for b in range(B):
+            assert m[b] == release_date_makespan(dep_b, chan, C, orders[b], op[b], rv[b])
+            per_chan = max(rv[b][chan == c].sum() for c in range(C))
+            assert U[b] == op[b].sum() + rv[b].sum() and L[b] == max(op[b].sum(), per_chan)
+            assert L[b] <= m[b] <= U[b]
+        # a shared order gives the same as the same order repeated per sample
+        ms = oracle.simulate_channels(*args, C, chan, orders[0], op, rv)[0]
+        mr = oracle.simulate_channels(*args, C, chan, np.tile(orders[0], (B, 1)), op, rv)[0]
+        assert np.array_equal(ms, mr)
+        if C == R:
+            # a channel per recv: every transfer starts at 0, the order plays no role, and no
+            # split of the recvs over fewer channels can be faster
+            m2 = oracle.simulate_channels(*args, C, chan, orders[:, ::-1].copy(), op, rv)[0]
+            assert np.array_equal(m, m2)
+            assert (m <= prev).all() and (m <= one[0]).all()
+        prev = np.minimum(prev, m) if C != R else prev
+
+
+def test_channels_toy_graph_by_hand():
+    g = read_golden("toy_two_channels.txt")
+    d = wl.toy_dag()
+    op = np.array([g["op_time"]], dtype=np.float64)
+    rv = np.array([g["recv_time"]], dtype=np.float64)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    for order in ([0, 1], [1, 0]):
+        m, e, U, L, S = oracle.simulate_channels(*args, 2, [0, 1], np.array(order, np.int32), op, rv)
+        assert (m[0], U[0], L[0]) == (g["makespan_two_channels"][0], g["U"][0], g["L_two_channels"][0])
+        assert e[0] == g["E_two_channels"][0] and S[0] == g["S_two_channels"][0]
+        m, e, U, L, S = oracle.simulate_channels(*args, 1, [0, 0], np.array(order, np.int32), op, rv)
+        key = f"order_{order[0]}_{order[1]}"
+        assert m[0] == g["makespan_one_channel_" + key][0] and e[0] == g["E_one_channel_" + key][0]
+        assert L[0] == g["L_one_channel"][0] and S[0] == g["S_one_channel"][0]
+    # both recvs on channel 1 of two: channel 0 stays empty and nothing changes against one channel
+    m = oracle.simulate_channels(*args, 2, [1, 1], np.array([0, 1], np.int32), op, rv)[0]
+    assert m[0] == g["makespan_one_channel_order_0_1"][0]
+
