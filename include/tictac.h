@@ -154,6 +154,23 @@ int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time,
                         tictac_stream stream);
 
 /*
+ * tictac_simulate with several channels (Sec. 4.1: a device has one channel per parameter
+ * server it talks to; Sec. 5.1: every channel carries one transfer at a time, in priority
+ * order).  Recv i uses channel channel_of_recv[i]; every channel serves its own recvs back to
+ * back from t = 0, in the order in which they appear in `order`, and the channels run side
+ * by side.  L counts every channel as a resource: L = max(sum of compute times, largest
+ * per-channel sum of transfer times).  Everything else as in tictac_simulate.
+ *   n_channels       1 .. 64
+ *   channel_of_recv  HOST, [n_recv], values in 0 .. n_channels-1 (TICTAC_ERR_BAD_ORDER otherwise)
+ * Graphs with more than 512 recvs or more than 512 classes of compute ops with identical
+ * dependency sets: TICTAC_ERR_UNSUPPORTED.
+ */
+int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channels, const int32_t *channel_of_recv,
+                             const int32_t *order, int32_t order_stride, const double *op_time,
+                             const double *recv_time, double *makespan, double *eff, double *U, double *L,
+                             double *S, tictac_stream stream);
+
+/*
  * Sec. 6, "Straggler Effect": workers that run one synchronous iteration together wait
  * for the slowest one; the effect is the longest wait of any worker as a fraction of the
  * iteration time.  The workers of group g are the w consecutive samples g*w .. g*w+w-1:

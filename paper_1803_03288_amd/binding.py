@@ -30,7 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
-    "tictac_straggler_effect",
+    "tictac_simulate_channels", "tictac_straggler_effect",
     "tictac_last_error", "tictac_version",
 )
 
@@ -168,6 +168,28 @@ def simulate(dag: Dag, order: torch.Tensor, op_time: torch.Tensor, recv_time: to
     out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
     _check(lib().tictac_simulate(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride), _dev(op_time),
                                  _dev(recv_time), *(_dev(o) for o in out), _stream()))
+    return tuple(out)
+
+
+def simulate_channels(dag: Dag, n_channels: int, channel_of_recv, order: torch.Tensor, op_time: torch.Tensor,
+                      recv_time: torch.Tensor):
+    """``tictac_simulate_channels``: ``(makespan, eff, U, L, S)``, float64 CUDA tensors ``[B]``.
+    ``channel_of_recv`` is a host int32 array ``[R]``; ``order`` is int32 ``[R]`` or ``[B][R]``."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    chan = np.ascontiguousarray(channel_of_recv, dtype=np.int32)
+    assert chan.shape == (R,)
+    assert order.is_cuda and order.dtype == torch.int32 and order.is_contiguous()
+    if order.dim() == 1:
+        assert order.shape[0] == R
+        stride = 0
+    else:
+        assert tuple(order.shape) == (B, R)
+        stride = R
+    out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
+    _check(lib().tictac_simulate_channels(dag._h, ctypes.c_int32(B), ctypes.c_int32(n_channels),
+                                          chan.ctypes.data_as(ctypes.c_void_p), _dev(order), ctypes.c_int32(stride),
+                                          _dev(op_time), _dev(recv_time), *(_dev(o) for o in out), _stream()))
     return tuple(out)
 
 

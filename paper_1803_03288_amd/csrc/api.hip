@@ -89,10 +89,32 @@ hipError_t ensure_workspace(Dag *d, size_t bytes)
     return hipSuccess;
 }
 
+// Device copy of a channel table [R].  A table equal to the one already there is not sent
+// again; a new one is copied synchronously after the work queued on the stream (which may
+// still read the old table) has finished.
+static hipError_t ensure_chan_table(Dag *d, const int32_t *chan, hipStream_t s)
+{
+    const size_t bytes = (size_t)d->R * sizeof(int32_t);
+    if (d->d_chan && d->h_chan.size() == (size_t)d->R && memcmp(d->h_chan.data(), chan, bytes) == 0)
+        return hipSuccess;
+    hipError_t e;
+    if (!d->d_chan) {
+        e = hipMalloc((void **)&d->d_chan, bytes);
+        if (e != hipSuccess) return e;
+    }
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return e;
+    d->h_chan.clear();
+    e = hipMemcpy(d->d_chan, chan, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return e;
+    d->h_chan.assign(chan, chan + d->R);
+    return hipSuccess;
+}
+
 static void free_dag(Dag *d)
 {
     if (!d) return;
-    void *ptrs[] = {d->d_graph_block, d->d_class_block, d->d_work};
+    void *ptrs[] = {d->d_graph_block, d->d_class_block, d->d_work, d->d_chan};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete d;
@@ -564,6 +586,53 @@ int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int3
     if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
     SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
     HIP_TRY(launch_simulate(*d, a, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channels, const int32_t *channel_of_recv,
+                             const int32_t *order, int32_t order_stride, const double *op_time,
+                             const double *recv_time, double *makespan, double *eff, double *U, double *L,
+                             double *S, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (n_channels < 1 || n_channels > 64) {
+        set_error("n_channels = %d, expected 1 .. 64", n_channels);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    if (order_stride != 0 && order_stride != d->R) {
+        set_error("order_stride = %d, expected 0 or n_recv = %d", order_stride, d->R);
+        return TICTAC_ERR_BAD_ORDER;
+    }
+    if (d->R > 0 && !channel_of_recv) { set_error("channel_of_recv is NULL"); return TICTAC_ERR_NULL; }
+    for (int32_t i = 0; i < d->R; ++i)
+        if (channel_of_recv[i] < 0 || channel_of_recv[i] >= n_channels) {
+            set_error("channel_of_recv[%d] = %d is outside 0 .. %d", i, channel_of_recv[i], n_channels - 1);
+            return TICTAC_ERR_BAD_ORDER;
+        }
+    if (B == 0) return TICTAC_OK;
+    if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
+    SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
+    hipStream_t s = (hipStream_t)stream;
+    if (d->R == 0) {                      // no transfers: the channels play no role
+        HIP_TRY(launch_simulate(*d, a, s));
+        return TICTAC_OK;
+    }
+    if (d->R > 512 || d->C > 512) {
+        set_error("%d recvs and %d classes: the several-channel simulation handles at most 512 of each", d->R, d->C);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    // the channel table goes to the device through a staging block of the handle
+    HIP_TRY(ensure_chan_table(d, channel_of_recv, s));
+    const hipError_t e = launch_simulate_channels(*d, a, n_channels, d->d_chan, s);
+    if (e == hipErrorNotSupported) {
+        set_error("graph outside what the several-channel simulation handles");
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    HIP_TRY(e);
     return TICTAC_OK;
 }
 

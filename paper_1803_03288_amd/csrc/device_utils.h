@@ -71,6 +71,12 @@ __device__ __forceinline__ double dpp_f64(double identity, double v)
     return __hiloint2double(hi, lo);
 }
 
+__device__ __forceinline__ double readlane_f64(double v, int l)      // l wave-uniform
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                            __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+
 __device__ __forceinline__ double lane63_f64(double v)
 {
     return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),

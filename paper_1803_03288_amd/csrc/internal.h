@@ -85,6 +85,8 @@ struct Dag {
     // the two allocations that hold every array above (graph tables + dep; class tables)
     void *d_graph_block = nullptr, *d_class_block = nullptr;
     void *d_work = nullptr;
+    int32_t *d_chan = nullptr;      // [R] channel table of the last several-channel simulation
+    std::vector<int32_t> h_chan;    // its host copy
     size_t work_bytes = 0;
 };
 
@@ -122,6 +124,7 @@ struct SimArgs {
     double *makespan, *eff, *U, *L, *S;
 };
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
+hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s);
 hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s);
 
 }  // namespace tictac

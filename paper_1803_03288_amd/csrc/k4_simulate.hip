@@ -339,6 +339,203 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
     return hipGetLastError();
 }
 
+// Several channels (Sec. 4.1: one per parameter server; Sec. 5.1: one transfer at a time per
+// channel).  Recv i uses channel chan[i]; every channel serves its recvs back to back from
+// t = 0 in the order in which they appear in the given order.  The channels never wait (recvs
+// are roots), so recv r arrives at the sum of the transfer times queued up to and including it
+// on its channel; a class is released when the last recv of its row has arrived (rho); and a
+// device that never idles while an op is ready finishes at
+//     max( latest arrival,  max over classes c of  rho_c + sum of the times of the classes with rho >= rho_c ).
+// One wave per sample: arrivals by one wave scan per channel, rho by range maxima over the
+// arrival array (runs of the class rows), the last step by comparing every class with every
+// class (lane l owns classes l, l + 64, ...; the pairs (rho, time) are broadcast from LDS).
+struct SimChanParams {
+    int32_t B, R, C, N, n_waves, wave_bytes, levels, n_channels;
+    const int32_t *col_cls, *run_ptr, *run_lo, *run_hi;
+    const int32_t *chan;        // [R] channel of every recv, 0 <= chan < n_channels <= 64
+    const int32_t *order;
+    int32_t order_stride;
+    const double *op_time, *recv_time;
+    double *makespan, *eff, *U, *L, *S;
+};
+
+template <int KT>
+__global__ void __launch_bounds__(256)
+simulate_channels_kernel(const SimChanParams p)
+{
+    extern __shared__ double smem[];
+    const int R = p.R, C = p.C, N = p.N;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double *mine = reinterpret_cast<double *>(reinterpret_cast<char *>(smem) + (size_t)wave * p.wave_bytes);
+    double *t = mine;                       // [R]          Time(recv)
+    double *arr = t + R;                    // [levels][R]  level 0: arrival of recv r; level j: maxima over [i, i + 2^j)
+    // [64 KT][2] (rho, class time), 16-byte aligned; first the class totals while they are summed
+    double *pairs = arr + (size_t)p.levels * R + (((size_t)(1 + p.levels) * R) & 1);
+    double *csum = pairs;
+
+    const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
+    for (int b = gwave; b < p.B; b += p.n_waves) {
+        const double *rt = p.recv_time + (size_t)b * R;
+        const double *ot = p.op_time + (size_t)b * N;
+        const int32_t *ord = p.order + (size_t)b * p.order_stride;
+        wave_sync();
+
+        // ---- transfer times, class totals ----
+        for (int r = lane; r < R; r += 64) { t[r] = rt[r]; arr[r] = 0.0; }
+        for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
+        wave_sync();
+        for (int j0 = lane; j0 < N; j0 += 64 * 8) {
+            double x[8];
+            int cls[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + u * 64;
+                x[u] = j < N ? ot[j] : 0.0;
+                cls[u] = j < N ? p.col_cls[j] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j0 + u * 64 < N) atomicAdd(&csum[cls[u]], x[u]);
+        }
+        wave_sync();
+#define SC_DECL(k) double ct_##k = 0.0, rho_##k = 0.0;
+        SW_EACH_K(SC_DECL)
+#define SC_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
+        SW_EACH_K(SC_TOTAL)
+        wave_sync();
+
+        // ---- arrivals: per channel, prefix sums over the positions of the order ----
+        double carry = 0.0;                 // lane c: time queued on channel c so far
+        double sum_r = 0.0;
+        for (int base = 0; base < R; base += 64) {
+            const int s = base + lane;
+            const int r = s < R ? ord[s] : -1;
+            const bool ok = (unsigned)r < (unsigned)R;      // an invalid entry is skipped, never dereferenced
+            const int cl = ok ? p.chan[r] : -1;
+            const double x = ok ? t[r] : 0.0;
+            double a = 0.0;
+            for (int c = 0; c < p.n_channels; ++c) {
+                const double inc = wave_incl_scan_f64_dpp(cl == c ? x : 0.0);
+                const double before = readlane_f64(carry, c);
+                if (cl == c) a = before + inc;
+                if (lane == c) carry += lane63_f64(inc);
+            }
+            if (ok) arr[r] = a;
+            sum_r += x;
+        }
+        sum_r = wave_sum_f64_dpp(sum_r);
+        const double last_arrival = wave_max_f64_dpp(lane < p.n_channels ? carry : 0.0);   // = largest channel sum
+        wave_sync();
+
+        // ---- rho of every class: maximum arrival over the runs of its row ----
+        for (int j = 1; j < p.levels; ++j) {
+            const double *prev = arr + (size_t)(j - 1) * R;
+            double *cur = arr + (size_t)j * R;
+            const int h = 1 << (j - 1);
+            for (int i = lane; i < R; i += 64) cur[i] = fmax(prev[i], prev[min(i + h, R - 1)]);
+            wave_sync();
+        }
+#define SC_RHO(k)                                                                         \
+        if constexpr (k < KT) {                                                           \
+            const int c = k * 64 + lane;                                                  \
+            if (c < C) {                                                                  \
+                const int rend = p.run_ptr[c + 1];                                        \
+                double m = 0.0;                                                           \
+                for (int q = p.run_ptr[c]; q < rend; ++q) {                               \
+                    const int lo = p.run_lo[q], hi = p.run_hi[q];                         \
+                    const int j = 31 - __builtin_clz(hi - lo);                            \
+                    const double *lv = arr + (size_t)j * R;                               \
+                    m = fmax(m, fmax(lv[lo], lv[hi - (1 << j)]));                         \
+                }                                                                         \
+                rho_##k = m;                                                              \
+            }                                                                             \
+            pairs[2 * (k * 64 + lane)] = rho_##k;                                         \
+            pairs[2 * (k * 64 + lane) + 1] = ct_##k;                                      \
+        }
+        SW_EACH_K(SC_RHO)
+        wave_sync();
+
+        // ---- every class against every class ----
+#define SC_ACC_DECL(k) double w_##k = 0.0;
+        SW_EACH_K(SC_ACC_DECL)
+        for (int c = 0; c < C; ++c) {
+            const double2 pr = *reinterpret_cast<const double2 *>(pairs + 2 * c);   // the same for every lane
+#define SC_ACC(k) if constexpr (k < KT) { w_##k += pr.x >= rho_##k ? pr.y : 0.0; }
+            SW_EACH_K(SC_ACC)
+        }
+        double mloc = last_arrival, ct_sum = 0.0;
+#define SC_MAX(k) if constexpr (k < KT) { if (k * 64 + lane < C) mloc = fmax(mloc, rho_##k + w_##k); ct_sum += ct_##k; }
+        SW_EACH_K(SC_MAX)
+        const double m = wave_max_f64_dpp(mloc);
+        const double sum_c = wave_sum_f64_dpp(ct_sum);
+        if (lane == 0) {
+            const double U = sum_c + sum_r;
+            const double L = fmax(sum_c, last_arrival);
+            p.makespan[b] = m;
+            p.eff[b] = (U == L) ? 1.0 : (U - m) / (U - L);
+            if (p.U) p.U[b] = U;
+            if (p.L) p.L[b] = L;
+            if (p.S) p.S[b] = (U == L || L == 0.0) ? 0.0 : (U - L) / L;
+        }
+    }
+}
+
+template <int KT>
+static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
+{
+    int levels = 1;
+    while ((1 << levels) <= d.R) ++levels;
+    p.levels = levels;
+    const size_t wave_bytes = (((size_t)d.R * (1 + levels) + 1 + (size_t)128 * KT) * 8 + 15) & ~(size_t)15;
+    int waves = 4;
+    while (waves > 1 && wave_bytes * waves > 40 * 1024) waves >>= 1;
+    const size_t lds = wave_bytes * waves;
+    if (lds > 64 * 1024) return hipErrorNotSupported;
+    p.wave_bytes = (int32_t)wave_bytes;
+    hipError_t e;
+    if (lds > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(simulate_channels_kernel<KT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, simulate_channels_kernel<KT>, 64 * waves, lds);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
+    int n_cu = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
+        n_cu = prop.multiProcessorCount;
+    int grid = per_cu * n_cu;
+    const int need = (p.B + waves - 1) / waves;
+    if (grid > need) grid = need;
+    p.n_waves = grid * waves;
+    hipLaunchKernelGGL((simulate_channels_kernel<KT>), dim3(grid), dim3(64 * waves), lds, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s)
+{
+    if (a.B == 0) return hipSuccess;
+    const int K = (d.C + 63) / 64;
+    const int KT = K <= 4 ? (K < 1 ? 1 : K) : (K <= 6 ? 6 : 8);
+    if (d.R == 0 || d.R > 512 || K > 8 || n_channels > 64 || (d.C > 0 && !d.d_col_cls)) return hipErrorNotSupported;
+    SimChanParams p{};
+    p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N; p.n_channels = n_channels;
+    p.col_cls = d.d_col_cls; p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;
+    p.chan = chan; p.order = a.order; p.order_stride = a.order_stride;
+    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
+    switch (KT) {
+    case 1: return launch_sim_chan<1>(p, d, s);
+    case 2: return launch_sim_chan<2>(p, d, s);
+    case 3: return launch_sim_chan<3>(p, d, s);
+    case 4: return launch_sim_chan<4>(p, d, s);
+    case 6: return launch_sim_chan<6>(p, d, s);
+    default: return launch_sim_chan<8>(p, d, s);
+    }
+}
+
 // Straggler effect of groups of w consecutive samples (Sec. 6): (max - min) / max of their
 // makespans.  A group is spread over the lanes of one wave (w > 4) or handled by one thread.
 __global__ void __launch_bounds__(256)

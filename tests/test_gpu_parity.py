@@ -267,6 +267,76 @@ def test_random_order_baseline_and_straggler_effect(tt):
         assert np.array_equal(tt.straggler_effect(big, w).cpu().numpy(), oracle.straggler(big.cpu().numpy(), w))
 
 
+@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "single", "r64", "r129", "resnet50",
+                                  "inception3"])
+def test_several_channels(tt, name):
+    """tictac_simulate_channels against the oracle: 1, 2, 3, 4 and 64 channels (and a channel per
+    recv where there are at most 64), random and round-robin assignments, per-sample and
+    shared orders; one channel equals tictac_simulate."""
+    makers = dict(SMALL)
+    makers["r64"] = lambda: wl.layered_dag(94, levels=7, width=9, fan_in=(1, 3), back=2, n_recv=64, attach=(1, 3))
+    makers["r129"] = lambda: wl.layered_dag(159, levels=7, width=9, fan_in=(1, 3), back=2, n_recv=129, attach=(1, 3))
+    d, h, dep = get(tt, name, makers.get(name))
+    R = d.n_recv
+    B = {"resnet50": 24, "inception3": 4}.get(name, 37)
+    op, rv = wl.timing_samples(d, 0, B)
+    rng = np.random.default_rng(17)
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    gop, grv, gord = cuda(op), cuda(rv), cuda(orders)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    one = [x.cpu().numpy() for x in tt.simulate(h, gord, gop, grv)]
+    got = [x.cpu().numpy() for x in tt.simulate_channels(h, 1, np.zeros(R, np.int32), gord, gop, grv)]
+    for a, b in zip(one, got):
+        assert np.array_equal(a, b)
+    cases = [(2, rng.integers(0, 2, size=R)), (3, np.arange(R) % 3), (4, rng.integers(0, 4, size=R)),
+             (64, rng.integers(0, 64, size=R)), (5, np.full(R, 4))]
+    if R <= 64:
+        cases.append((max(R, 1), np.arange(R)))
+    for C, chan in cases:
+        chan = chan.astype(np.int32)
+        exp = oracle.simulate_channels(*args, C, chan, orders, op, rv)
+        got = tt.simulate_channels(h, C, chan, gord, gop, grv)
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: {C} channels, {nm}"
+        exp = oracle.simulate_channels(*args, C, chan, orders[0], op, rv)
+        got = tt.simulate_channels(h, C, chan, gord[0].contiguous(), gop, grv)
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: {C} channels, shared order, {nm}"
+    # zero-length transfers and zero-time ops (equal arrivals, equal release dates)
+    op0, rv0 = op.copy(), rv.copy()
+    op0[rng.random(op0.shape) < 0.3] = 0.0
+    rv0[rng.random(rv0.shape) < 0.3] = 0.0
+    chan = rng.integers(0, 3, size=R).astype(np.int32)
+    exp = oracle.simulate_channels(*args, 3, chan, orders, op0, rv0)
+    got = tt.simulate_channels(h, 3, chan, gord, cuda(op0), cuda(rv0))
+    for a, b in zip(got, exp):
+        assert np.array_equal(a.cpu().numpy(), b)
+
+
+def test_several_channels_limits(tt):
+    from paper_1803_03288_amd.binding import TicTacError
+    d, h, dep = get(tt, "toy", wl.toy_dag)
+    op, rv = wl.timing_samples(d, 0, 4)
+    o = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    for C, chan, code in ((0, [0, 0], -9), (65, [0, 0], -9), (2, [0, 2], -6), (2, [-1, 0], -6)):
+        with pytest.raises(TicTacError) as e:
+            tt.simulate_channels(h, C, np.array(chan, np.int32), o, cuda(op), cuda(rv))
+        assert e.value.code == code
+    ds, hs, _ = get(tt, "stress")
+    with pytest.raises(TicTacError) as e:
+        tt.simulate_channels(hs, 2, np.zeros(ds.n_recv, np.int32), torch.zeros(ds.n_recv, dtype=torch.int32, device="cuda"),
+                             torch.zeros((1, ds.n_compute), dtype=torch.float64, device="cuda"),
+                             torch.zeros((1, ds.n_recv), dtype=torch.float64, device="cuda"))
+    assert e.value.code == -9
+    # no recvs: the channels play no role
+    dn = wl.no_recv_dag(17)
+    hn = tt.build_deps(dn.n_ops, dn.row_ptr, dn.col_idx, dn.recv_ids)
+    opn = np.arange(1, 3 * 17 + 1, dtype=np.float64).reshape(3, 17) * wl.QUANTUM
+    got = tt.simulate_channels(hn, 3, np.zeros(0, np.int32), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                               cuda(opn), cuda(np.zeros((3, 0))))
+    assert np.array_equal(got[0].cpu().numpy(), opn.sum(axis=1))
+
+
 def test_power_of_two_scaling_and_determinism(tt):
     d, h, dep = get(tt, "resnet50")
     op, rv = wl.timing_samples(d, 0, 64)
