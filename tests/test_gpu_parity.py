@@ -222,6 +222,30 @@ def test_word_boundaries_and_ragged_batches(tt, n_recv):
         run_tac_sim_parity(tt, d, h, dep, op, rv, f"{name}/B{B}")
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_graphs(tt, seed):
+    """Seeded random layered graphs of varied shape (1 to 200 recvs, shallow and deep, sparse and
+    dense attachment), each with ordinary samples and with samples drawn from three values
+    (ties everywhere, zero-time ops)."""
+    rng = np.random.default_rng(1000 + seed)
+    R = int(rng.choice([1, 2, 3, 5, 17, 40, 64, 65, 100, 130, 200]))
+    levels, width = int(rng.integers(1, 12)), int(rng.integers(1, 10))
+    hi_attach = int(rng.integers(1, 6))
+    d = wl.layered_dag(500 + seed, levels=levels, width=width, fan_in=(1, int(rng.integers(1, 4))),
+                       back=int(rng.integers(1, 4)), n_recv=R, attach=(1, hi_attach))
+    print(f"[random] seed {seed}: R={R} levels={levels} width={width} attach<= {hi_attach}", flush=True)
+    h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    dep = oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    assert np.array_equal(h.deps().cpu().numpy().view(np.uint64), dep)
+    B = 24
+    op, rv = wl.timing_samples(d, 0, B)
+    run_tac_sim_parity(tt, d, h, dep, op, rv, f"random{seed}")
+    op3 = rng.integers(0, 3, size=(B, d.n_compute)).astype(np.float64) * 0.5
+    rv3 = rng.integers(1, 3, size=(B, R)).astype(np.float64) * 0.5
+    run_tac_sim_parity(tt, d, h, dep, op3, rv3, f"random{seed}/ties")
+    h.close()
+
+
 def test_random_orders_per_sample(tt):
     d, h, dep = get(tt, "layered70", SMALL["layered70"])
     rng = np.random.default_rng(8)
