@@ -26,8 +26,9 @@
 //     each column adding itself to its class's total in LDS;
 //   * the order is collected in a register (one lane per step) and written to LDS once per
 //     64 steps, or when a path needs it;
-//   * the last step at which a class's count is decremented is its release position kappa; after the
-//     loop the class times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
+//   * a class is released when the recv it pointed at (its last one) is selected, so its release
+//     position kappa is that recv's position in the finished order; after the loop the class
+//     times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
 //     the end of the k-th transfer, S_k the time of the classes with kappa >= k (the closed
 //     form of the work-conserving device described in k4_simulate.hip);
 //   * a sample with a transfer time of zero is not handled here: it is flagged for the
@@ -144,7 +145,7 @@ tac_reg_kernel(const TacRegParams p)
         if (skip) continue;
 
         // ---- b. class totals ----
-#define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, kap_##k = 0, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
+#define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, sole_##k = -1, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
         TT_EACH_K(TT_DECL_STATE)
         if (p.col_cls) {
             // the row is read once, coalesced; every column adds itself to the total of its class
@@ -260,7 +261,10 @@ tac_reg_kernel(const TacRegParams p)
         // positive time it becomes a pointer.
 #define TT_TO_P(k, hit1)                                                                  \
         {                                                                                 \
-            if (hit1) atomicAdd(&P[pk_##k & IDX_MASK], ct_##k);                           \
+            if (hit1) {                                                                   \
+                sole_##k = pk_##k & IDX_MASK;       /* the class is released when this recv is */ \
+                atomicAdd(&P[sole_##k], ct_##k);                                          \
+            }                                                                             \
             uint64_t nm = __ballot((hit1) && ct_##k > 0.0);                               \
             while (nm) {                                                                  \
                 const int l = __builtin_ctzll(nm);                                        \
@@ -287,7 +291,6 @@ tac_reg_kernel(const TacRegParams p)
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
                 pk_##k += __mul24(mk_##k, delta);                                         \
-                kap_##k = (kap_##k & ~mk_##k) | (step1 & mk_##k);  /* last decrement = release */ \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
 #define TT_EVENT(k)                                                                       \
@@ -303,7 +306,6 @@ tac_reg_kernel(const TacRegParams p)
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
                 const int delta = CNT1 + best;                                            \
-                const int step1 = step + 1;                                               \
                 uint32_t hmax = 0;                                                        \
                 TT_EACH_K(TT_UPDATE)                                                      \
                 if (__ballot(hmax >= (uint32_t)-CNT1) != 0ull) { TT_EACH_K(TT_EVENT) }    \
@@ -448,10 +450,19 @@ tac_reg_kernel(const TacRegParams p)
         if (p.simulate) {
             // A[k] = time of the classes released after k transfers; F_k = end of the k-th transfer;
             // makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
+            // A class is released by its last recv, the one it pointed at once its count had fallen
+            // to one: kappa = 1-based position of that recv in the order, 0 for a class without recvs.
+            int32_t *posl = reinterpret_cast<int32_t *>(P);        // [R] recv -> step (P is free now)
+            for (int s = lane; s < R; s += 64) posl[ordl[s]] = s;
             for (int j = lane; j <= R; j += 64) A[j] = 0.0;
             wave_sync();
-#define TT_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); }
+#define TT_RELEASE(k)                                                                     \
+            if constexpr (k < KT) {                                                       \
+                const int kap = sole_##k >= 0 ? posl[sole_##k] + 1 : 0;                   \
+                if (k * 64 + lane < C) atomicAdd(&A[kap], ct_##k);                        \
+            }
             TT_EACH_K(TT_RELEASE)
+            wave_sync();                                           // posl is read before P is written below
             // F_k into P[k - 1] (P is free now): prefix sums of the transfer times in TAC order
             double fc = 0.0;
             for (int base = 0; base < R; base += 64) {
