@@ -259,14 +259,8 @@ tac_reg_kernel(const TacRegParams p)
 
         // A class that fell to one outstanding recv: its time goes to P of that recv, and with a
         // positive time it becomes a pointer.
-#define TT_TO_P(k, hit1)                                                                  \
-        {                                                                                 \
-            if (hit1) {                                                                   \
-                sole_##k = pk_##k & IDX_MASK;       /* the class is released when this recv is */ \
-                atomicAdd(&P[sole_##k], ct_##k);                                          \
-            }                                                                             \
-            uint64_t nm = __ballot((hit1) && ct_##k > 0.0);                               \
-            while (nm) {                                                                  \
+#define TT_POINTER(k)                                                                     \
+            {                                                                             \
                 const int l = __builtin_ctzll(nm);                                        \
                 nm &= nm - 1;                                                             \
                 const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
@@ -274,8 +268,22 @@ tac_reg_kernel(const TacRegParams p)
                 qs += sole;                                                               \
                 qq += sole * sole;                                                        \
                 qlast = sole;                                                             \
+            }
+#define TT_TO_P(k, hit1)                                                                  \
+        {                                                                                 \
+            if (hit1) {                                                                   \
+                sole_##k = pk_##k & IDX_MASK;       /* the class is released when this recv is */ \
+                atomicAdd(&P[sole_##k], ct_##k);                                          \
+            }                                                                             \
+            uint64_t nm = __ballot(hit1) & ctpos_##k;     /* positive class time: a pointer */ \
+            if (nm) {                                     /* one, as a rule */            \
+                TT_POINTER(k)                                                             \
+                while (nm) TT_POINTER(k)                                                  \
             }                                                                             \
         }
+        // lanes whose class k has a positive time (wave-uniform masks, fixed for the sample)
+#define TT_CTPOS(k) const uint64_t ctpos_##k = (k < KT) ? __ballot(ct_##k > 0.0) : 0ull;
+        TT_EACH_K(TT_CTPOS)
 #define TT_INIT_P(k)                                                                      \
         if constexpr (k < KT) {                                                           \
             const bool one = pk_##k < 0 && pk_##k >= -CNT1;                               \
@@ -322,7 +330,7 @@ tac_reg_kernel(const TacRegParams p)
         // unknown number of them)
 #define TT_RECOUNT(k)                                                                     \
             if constexpr (k < KT) {                                                       \
-                uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1 && ct_##k > 0.0); \
+                uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1) & ctpos_##k;    \
                 while (nm) {                                                              \
                     const int l = __builtin_ctzll(nm);                                    \
                     nm &= nm - 1;                                                         \
