@@ -183,8 +183,8 @@ tac_reg_kernel(const TacRegParams p)
         for (int r = lane; r < R; r += 64) P[r] = 0.0;
         wave_sync();
         // A class with exactly one outstanding recv left and a positive time "points" at that
-        // recv; Q is the set of recvs pointed at (they are the recvs with P > 0, P of a recv
-        // being reset when it is selected).  Tracked wave-uniformly: the number of pointers, the
+        // recv; Q is the set of recvs pointed at (the outstanding recvs with P > 0).  Tracked
+        // wave-uniformly: the number of pointers, the
         // sum and the sum of squares of their targets, and the target of the latest one.
         int qm = 0, qs = 0, qq = 0, qlast = 0;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
@@ -292,7 +292,7 @@ tac_reg_kernel(const TacRegParams p)
         TT_EACH_K(TT_INIT_P)
 
         // ---- d. selection loop ----
-        // What a round does once `best` is chosen: record it, reset its P, and the straight-line
+        // What a round does once `best` is chosen: record it, and the straight-line
         // incremental update of every class; then, where a class fell to one outstanding recv,
         // that class's time goes to P of that recv.
 #define TT_UPDATE(k)                                                                      \
@@ -310,7 +310,6 @@ tac_reg_kernel(const TacRegParams p)
             {                                                                             \
                 ord_reg = lane == (step & 63) ? best : ord_reg;                           \
                 if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;                  \
-                P[best] = 0.0;                      /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
                 const int delta = CNT1 + best;                                            \
@@ -408,9 +407,21 @@ tac_reg_kernel(const TacRegParams p)
                 // ascending scan over Q with the comparator
                 double mp_best = -1.0;
                 best = -1;
+                // Q from the pointers: bit j of lane l stands for recv 64 j + l
+                uint32_t qbits_l = 0;
+#define TT_QBITS(k)                                                                       \
+                if constexpr (k < KT) {                                                   \
+                    uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1) & ctpos_##k; \
+                    while (nm) {                                                          \
+                        const int l = __builtin_ctzll(nm);                                \
+                        nm &= nm - 1;                                                     \
+                        const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK; \
+                        qbits_l |= (uint32_t)(lane == (sole & 63)) << (sole >> 6);        \
+                    }                                                                     \
+                }
+                TT_EACH_K(TT_QBITS)
                 for (int j = 0; j < W; ++j) {
-                    const int rj = j * 64 + lane;
-                    uint64_t x = __ballot(rj < R && P[rj] > 0.0);
+                    uint64_t x = __ballot((qbits_l >> j) & 1u);
                     while (x) {
                         const int a = j * 64 + __builtin_ctzll(x);
                         x &= x - 1;
