@@ -182,3 +182,14 @@ def straggler(makespan, w: int) -> np.ndarray:
     _check(rc, "oracle_straggler")
     return out
 
+
+def time_oracle_min(runs) -> np.ndarray:
+    """Sec. 5, Time Oracle: the smallest of the measured runs of every op.  ``runs [K][n]`` -> ``[n]``."""
+    runs = _f64(runs)
+    assert runs.ndim == 2 and runs.shape[0] >= 1
+    K, n = runs.shape
+    out = np.zeros(n)
+    rc = _load().oracle_time_oracle_min(ctypes.c_int(K), ctypes.c_longlong(n), _p(runs), _p(out))
+    _check(rc, "oracle_time_oracle_min")
+    return out
+

@@ -573,3 +573,20 @@ int oracle_straggler(int B, int w, const double *makespan, double *out)
     return 0;
 }
 
+/* ---------------------------------------------------------------------------
+ * Time oracle estimator (Sec. 5, "Time Oracle"): every op is measured in several runs and
+ * the smallest measurement is taken as its time.  runs [n_runs][n] -> time [n].
+ * ------------------------------------------------------------------------- */
+int oracle_time_oracle_min(int n_runs, long long n, const double *runs, double *time)
+{
+    if (n_runs < 1 || n < 0) return -2;
+    if (n > 0 && (!runs || !time)) return -1;
+    for (long long i = 0; i < n; ++i) {
+        double m = runs[i];
+        for (int k = 1; k < n_runs; ++k)
+            if (runs[(size_t)k * (size_t)n + (size_t)i] < m) m = runs[(size_t)k * (size_t)n + (size_t)i];
+        time[i] = m;
+    }
+    return 0;
+}
+

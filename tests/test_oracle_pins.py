@@ -513,3 +513,24 @@ def test_channels_toy_graph_by_hand():
     m = oracle.simulate_channels(*args, 2, [1, 1], np.array([0, 1], np.int32), op, rv)[0]
     assert m[0] == g["makespan_one_channel_order_0_1"][0]
 
+
+# --------------------------------------------------------------------------
+# Time oracle estimator (Sec. 5): minimum over the measured runs
+# --------------------------------------------------------------------------
+
+def test_time_oracle_is_the_minimum_of_the_runs():
+    # five runs of three ops, by hand
+    runs = np.array([[3.0, 9.0, 1.5], [2.5, 9.5, 1.5], [4.0, 8.0, 2.0], [2.75, 8.25, 1.75], [3.5, 9.0, 1.25]])
+    assert oracle.time_oracle_min(runs).tolist() == [2.5, 8.0, 1.25]
+    assert np.array_equal(oracle.time_oracle_min(runs[:1]), runs[0])                 # one run: itself
+    assert np.array_equal(oracle.time_oracle_min(runs[::-1].copy()), [2.5, 8.0, 1.25])  # run order plays no role
+    rng = np.random.default_rng(2)
+    big = rng.integers(1, 10**6, size=(5, 1000)).astype(np.float64)
+    t = oracle.time_oracle_min(big)
+    assert np.array_equal(t, np.sort(big, axis=0)[0])
+    assert (t[None, :] <= big).all() and (t[None, :] == big).any(axis=0).all()
+    # a run that is slower everywhere changes nothing; one that is faster everywhere replaces all
+    assert np.array_equal(oracle.time_oracle_min(np.vstack([big, big.max(axis=0) + 1])), t)
+    assert np.array_equal(oracle.time_oracle_min(np.vstack([big, t - 1])), t - 1)
+    assert oracle.time_oracle_min(np.zeros((5, 0))).size == 0
+
