@@ -182,6 +182,17 @@ int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channel
 int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double *straggler,
                             tictac_stream stream);
 
+/*
+ * Sec. 5, "Time Oracle": every op is measured in several runs and the smallest measurement
+ * is taken as its time.
+ *   runs [n_runs][n]  device, row-major (one row per measured run; n may be a whole batch
+ *                     of timing rows, B * N or B * n_recv values)
+ *   time [n]          device
+ * n_runs >= 1 and n >= 0 (TICTAC_ERR_UNSUPPORTED otherwise); NaN measurements are ignored
+ * where another run has a number.
+ */
+int tictac_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, tictac_stream stream);
+
 /* Message of the last error on the calling thread; valid until its next call. */
 const char *tictac_last_error(void);
 

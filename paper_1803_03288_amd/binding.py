@@ -30,7 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
-    "tictac_simulate_channels", "tictac_straggler_effect",
+    "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min",
     "tictac_last_error", "tictac_version",
 )
 
@@ -191,6 +191,15 @@ def simulate_channels(dag: Dag, n_channels: int, channel_of_recv, order: torch.T
                                           chan.ctypes.data_as(ctypes.c_void_p), _dev(order), ctypes.c_int32(stride),
                                           _dev(op_time), _dev(recv_time), *(_dev(o) for o in out), _stream()))
     return tuple(out)
+
+
+def time_oracle_min(runs: torch.Tensor) -> torch.Tensor:
+    """``tictac_time_oracle_min``: ``runs`` float64 CUDA ``[K][...]`` -> the minimum over the K runs."""
+    assert runs.is_cuda and runs.dtype == torch.float64 and runs.is_contiguous() and runs.dim() >= 2
+    K = runs.shape[0]
+    out = torch.empty(runs.shape[1:], dtype=torch.float64, device="cuda")
+    _check(lib().tictac_time_oracle_min(ctypes.c_int32(K), ctypes.c_int64(out.numel()), _dev(runs), _dev(out), _stream()))
+    return out
 
 
 def straggler_effect(makespan: torch.Tensor, w: int) -> torch.Tensor:

@@ -646,6 +646,16 @@ int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double
     return TICTAC_OK;
 }
 
+int tictac_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, tictac_stream stream)
+{
+    if (n_runs < 1) { set_error("n_runs = %d, expected at least 1", n_runs); return TICTAC_ERR_UNSUPPORTED; }
+    if (n < 0) { set_error("n is negative"); return TICTAC_ERR_UNSUPPORTED; }
+    if (n == 0) return TICTAC_OK;
+    if (!runs || !time) { set_error("runs or time is NULL"); return TICTAC_ERR_NULL; }
+    HIP_TRY(launch_time_oracle_min(n_runs, n, runs, time, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
 const char *tictac_last_error(void) { return g_err; }
 
 const char *tictac_version(void) { return "0.1"; }

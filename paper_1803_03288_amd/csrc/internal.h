@@ -125,6 +125,7 @@ struct SimArgs {
 };
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
 hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s);
+hipError_t launch_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, hipStream_t s);
 hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s);
 
 }  // namespace tictac

@@ -577,6 +577,45 @@ hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double
     return hipGetLastError();
 }
 
+// Time oracle estimator (Sec. 5): time[i] = minimum over the measured runs of runs[k][i].
+// A streaming kernel: every element is read once per run; two doubles per lane and load.
+__global__ void __launch_bounds__(256)
+time_oracle_min_kernel(int32_t n_runs, int64_t n, bool pairs_ok, const double *__restrict__ runs,
+                       double *__restrict__ time)
+{
+    const int64_t n2 = n >> 1;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (pairs_ok) {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) {
+            double2 m = reinterpret_cast<const double2 *>(runs)[i];
+            for (int k = 1; k < n_runs; ++k) {
+                const double2 x = reinterpret_cast<const double2 *>(runs + (size_t)k * n)[i];
+                m.x = fmin(m.x, x.x);
+                m.y = fmin(m.y, x.y);
+            }
+            reinterpret_cast<double2 *>(time)[i] = m;
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+            double m = runs[i];
+            for (int k = 1; k < n_runs; ++k) m = fmin(m, runs[(size_t)k * n + i]);
+            time[i] = m;
+        }
+    }
+}
+
+hipError_t launch_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    // pairs when every row starts on a 16-byte boundary
+    const bool pairs_ok = (n & 1) == 0 && ((reinterpret_cast<uintptr_t>(runs) | reinterpret_cast<uintptr_t>(time)) & 15) == 0;
+    const int64_t work = pairs_ok ? n / 2 : n;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;          // 32 workgroups per compute unit, grid-stride beyond
+    hipLaunchKernelGGL(time_oracle_min_kernel, dim3((unsigned)blocks), dim3(256), 0, s, n_runs, n, pairs_ok, runs, time);
+    return hipGetLastError();
+}
+
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;

@@ -78,6 +78,11 @@ def test_null_handle_is_rejected(L):
     assert L.tictac_simulate(None, ctypes.c_int32(1), None, ctypes.c_int32(0), None, None, None, None, None, None,
                              None, None) == -1
     assert L.tictac_dag_free(None) == 0
+    # time oracle: no run, negative length, NULL buffers
+    assert L.tictac_time_oracle_min(ctypes.c_int32(0), ctypes.c_int64(4), None, None, None) == -9
+    assert L.tictac_time_oracle_min(ctypes.c_int32(5), ctypes.c_int64(-1), None, None, None) == -9
+    assert L.tictac_time_oracle_min(ctypes.c_int32(5), ctypes.c_int64(4), None, None, None) == -1
+    assert L.tictac_time_oracle_min(ctypes.c_int32(5), ctypes.c_int64(0), None, None, None) == 0
     # straggler effect: group size below 1, negative batch, NULL buffers with at least one group
     assert L.tictac_straggler_effect(ctypes.c_int32(8), ctypes.c_int32(0), None, None, None) == -9
     assert L.tictac_straggler_effect(ctypes.c_int32(-1), ctypes.c_int32(2), None, None, None) == -9

@@ -361,6 +361,21 @@ def test_several_channels_limits(tt):
     assert np.array_equal(got[0].cpu().numpy(), opn.sum(axis=1))
 
 
+def test_time_oracle_min(tt):
+    """Minimum over measured runs, element by element against the oracle: even and odd lengths
+    (two-element and one-element loads), one run, many runs, a batch of timing rows."""
+    rng = np.random.default_rng(4)
+    for K, n in ((5, 1000), (5, 1001), (1, 77), (2, 1), (9, 300001), (5, 0)):
+        runs = rng.integers(1, 10**6, size=(K, n)).astype(np.float64) * wl.QUANTUM
+        got = tt.time_oracle_min(cuda(runs)).cpu().numpy()
+        assert np.array_equal(got, oracle.time_oracle_min(runs)), (K, n)
+    d = wl.preset("resnet50")
+    ops = np.stack([wl.timing_samples(d, 256 * k, 256 * k + 64)[0] for k in range(5)])      # [5][64][N]
+    got = tt.time_oracle_min(cuda(ops)).cpu().numpy()
+    assert got.shape == ops.shape[1:]
+    assert np.array_equal(got.ravel(), oracle.time_oracle_min(ops.reshape(5, -1)))
+
+
 def test_power_of_two_scaling_and_determinism(tt):
     d, h, dep = get(tt, "resnet50")
     op, rv = wl.timing_samples(d, 0, 64)
