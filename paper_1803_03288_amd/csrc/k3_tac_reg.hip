@@ -269,13 +269,13 @@ tac_reg_kernel(const TacRegParams p)
                 qq += sole * sole;                                                        \
                 qlast = sole;                                                             \
             }
-#define TT_TO_P(k, hit1)                                                                  \
+#define TT_TO_P(k, hit1, hm)     /* hm: the ballot of hit1 */                            \
         {                                                                                 \
             if (hit1) {                                                                   \
                 sole_##k = pk_##k & IDX_MASK;       /* the class is released when this recv is */ \
                 atomicAdd(&P[sole_##k], ct_##k);                                          \
             }                                                                             \
-            uint64_t nm = __ballot(hit1) & ctpos_##k;     /* positive class time: a pointer */ \
+            uint64_t nm = (hm) & ctpos_##k;               /* positive class time: a pointer */ \
             if (nm) {                                     /* one, as a rule */            \
                 TT_POINTER(k)                                                             \
                 while (nm) TT_POINTER(k)                                                  \
@@ -287,7 +287,8 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_INIT_P(k)                                                                      \
         if constexpr (k < KT) {                                                           \
             const bool one = pk_##k < 0 && pk_##k >= -CNT1;                               \
-            TT_TO_P(k, one)                                                               \
+            const uint64_t hm1 = __builtin_amdgcn_ballot_w64(one);                        \
+            TT_TO_P(k, one, hm1)                                                          \
         }
         TT_EACH_K(TT_INIT_P)
 
@@ -298,13 +299,15 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
                 mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
-                pk_##k += __mul24(mk_##k, delta);                                         \
+                __builtin_assume(mk_##k >= -1 && mk_##k <= 0);                            \
+                pk_##k += mk_##k * delta;           /* both fit 24 bits: one multiply-add */                                         \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
 #define TT_EVENT(k)                                                                       \
             if constexpr (k < KT) {                                                       \
                 const bool hit1 = (uint32_t)(pk_##k & mk_##k) >= (uint32_t)-CNT1;         \
-                if (__ballot(hit1) != 0ull) TT_TO_P(k, hit1)                              \
+                const uint64_t hm_ = __builtin_amdgcn_ballot_w64(hit1);                   \
+                if (hm_ != 0ull) TT_TO_P(k, hit1, hm_)                                    \
             }
 #define TT_APPLY()                                                                        \
             {                                                                             \
@@ -312,6 +315,7 @@ tac_reg_kernel(const TacRegParams p)
                 if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;                  \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
+                __builtin_assume((unsigned)best < (unsigned)CNT1);                        \
                 const int delta = CNT1 + best;                                            \
                 uint32_t hmax = 0;                                                        \
                 TT_EACH_K(TT_UPDATE)                                                      \
