@@ -24,8 +24,6 @@
 //     from the order built so far; rounds that do not need it do not touch it;
 //   * the class totals of a sample are formed by one coalesced pass over its op_time row,
 //     each column adding itself to its class's total in LDS;
-//   * the order is collected in a register (one lane per step) and written to LDS once per
-//     64 steps, or when a path needs it;
 //   * a class is released when the recv it pointed at (its last one) is selected, so its release
 //     position kappa is that recv's position in the finished order; after the loop the class
 //     times are added up by kappa and the makespan is max_k (F_k + S_k), F_k
@@ -188,7 +186,7 @@ tac_reg_kernel(const TacRegParams p)
         // sum and the sum of squares of their targets, and the target of the latest one.
         int qm = 0, qs = 0, qq = 0, qlast = 0;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
-        int ord_reg = 0;                    // lane i: the recv selected at step (step & ~63) + i
+        int32_t *ord_next = ordl;           // where the next selected recv is recorded
 
         // outstanding recvs as 32-bit halves in LDS, rebuilt from the order so far on the rare
         // path that needs them by index
@@ -311,8 +309,7 @@ tac_reg_kernel(const TacRegParams p)
             }
 #define TT_APPLY()                                                                        \
             {                                                                             \
-                ord_reg = lane == (step & 63) ? best : ord_reg;                           \
-                if ((step & 63) == 63) ordl[step - 63 + lane] = ord_reg;                  \
+                *ord_next++ = best;                     /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
                 __builtin_assume((unsigned)best < (unsigned)CNT1);                        \
@@ -383,9 +380,7 @@ tac_reg_kernel(const TacRegParams p)
                 continue;
             }
             int best;
-            // the steps of the current block of 64 so far, for the paths that read ordl
-            if (lane < (step & 63)) ordl[(step & ~63) + lane] = ord_reg;
-            wave_sync();
+            wave_sync();                    // the order so far is in ordl for the paths that read it
             m_sync = __builtin_amdgcn_readfirstlane(m_sync);
             if (qm == 0) {
                 // every outstanding recv has P = 0: lowest index among those of minimal M+
@@ -461,7 +456,6 @@ tac_reg_kernel(const TacRegParams p)
             TT_EACH_K(TT_RECOUNT)
             TT_UNIFORM_Q()
         }
-        if ((R & 63) && lane < (R & 63)) ordl[(R & ~63) + lane] = ord_reg;
         wave_sync();
 
         // ---- e. outputs ----
