@@ -312,8 +312,7 @@ tac_reg_kernel(const TacRegParams p)
                 *ord_next++ = best;                     /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
                 const int sh = best & 31;                                                 \
-                __builtin_assume((unsigned)best < (unsigned)CNT1);                        \
-                const int delta = CNT1 + best;                                            \
+                const int delta = CNT1 + (best & IDX_MASK);    /* the mask tells the compiler it fits 24 bits */ \
                 uint32_t hmax = 0;                                                        \
                 TT_EACH_K(TT_UPDATE)                                                      \
                 if (__ballot(hmax >= (uint32_t)-CNT1) != 0ull) { TT_EACH_K(TT_EVENT) }    \
