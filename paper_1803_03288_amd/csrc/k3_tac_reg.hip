@@ -84,7 +84,7 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
 #define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
 template <int KT>
-__global__ void __launch_bounds__(64 * reg_waves(KT), (KT <= 3 ? 6 : (KT <= 4 ? 5 : 1)))
+__global__ void __launch_bounds__(64 * reg_waves(KT), (KT <= 3 ? 8 : (KT <= 4 ? 5 : 1)))
 tac_reg_kernel(const TacRegParams p)
 {
     extern __shared__ double smem[];
@@ -95,10 +95,9 @@ tac_reg_kernel(const TacRegParams p)
     uint32_t *rows = reinterpret_cast<uint32_t *>(smem);            // [2W][64][KT]
     const int rows_doubles = (2 * W * 64 * KT + 1) / 2;
     double *mine = smem + rows_doubles + (size_t)wave * p.wave_doubles;
-    double *t = mine;                       // [R]    Time(recv)
-    double *P = t + R;                      // [R+1]  P; before the loop: prefix sums T
-    double *A = P + (R + 1);                // [R+1]  class time by release position
-    int32_t *ordl = reinterpret_cast<int32_t *>(A + (R + 1));       // [R] order built so far
+    double *t = mine;                       // [R+1]  Time(recv); after the loop: class time by release position
+    double *P = t + (R + 1);                // [R+1]  P; after the loop: positions, then the ends of the transfers
+    int32_t *ordl = reinterpret_cast<int32_t *>(P + (R + 1));       // [R] order built so far
     uint32_t *aliveh = reinterpret_cast<uint32_t *>(ordl + R);      // [2W] outstanding recvs
 
     for (int idx = threadIdx.x; idx < 2 * W * 64 * KT; idx += blockDim.x) {
@@ -123,7 +122,7 @@ tac_reg_kernel(const TacRegParams p)
     TT_EACH_K(TT_INIT_CONST)
 
     const uint32_t *rows_lane = rows + lane * KT;      // this lane's KT words of half-row 0
-    double *csum = P;                                  // [64 KT] class totals while they are summed (spans P and A)
+    double *csum = P;                                  // [64 KT] class totals while they are summed (spans P, ordl, aliveh)
 
     const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
@@ -204,9 +203,8 @@ tac_reg_kernel(const TacRegParams p)
         };
 
         // M of the classes is only needed when Q is empty or the comparator ties, so its
-        // updates are deferred: formed from prefix sums T of the transfer times (the sum over
-        // the runs [lo, hi) of consecutive recv indices of a row of T[hi] - T[lo]; T sits in A,
-        // which is free until the loop ends) and then brought up to `upto` by the
+        // updates are deferred: formed as the sum of the transfer times over the runs [lo, hi)
+        // of consecutive recv indices of the class row, and then brought up to `upto` by the
         // subtractions of the rounds since m_sync, in their order.  ordl holds those rounds.
 #define TT_M_FORM(k)                                                                      \
         if constexpr (k < KT) {                                                           \
@@ -214,7 +212,10 @@ tac_reg_kernel(const TacRegParams p)
             double Mk = 0.0;                                                              \
             if (c < C) {                                                                  \
                 const int rend = p.run_ptr[c + 1];                                        \
-                for (int q = p.run_ptr[c]; q < rend; ++q) Mk += A[p.run_hi[q]] - A[p.run_lo[q]]; \
+                for (int q = p.run_ptr[c]; q < rend; ++q) {                               \
+                    const int hi_ = p.run_hi[q];                                          \
+                    for (int r_ = p.run_lo[q]; r_ < hi_; ++r_) Mk += t[r_];               \
+                }                                                                         \
             }                                                                             \
             M_##k = Mk;                                                                   \
         }
@@ -226,16 +227,6 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_ENSURE_M(upto)                                                                 \
         {                                                                                 \
             if (m_sync < 0) {                                                             \
-                double carry = 0.0;                                                       \
-                for (int base = 0; base < R; base += 64) {                                \
-                    const int r = base + lane;                                            \
-                    const double x = r < R ? t[r] : 0.0;                                  \
-                    const double inc = wave_incl_scan_f64_dpp(x);                             \
-                    if (r < R) A[r + 1] = carry + inc;                                    \
-                    carry += lane63_f64(inc);                                             \
-                }                                                                         \
-                if (lane == 0) A[0] = 0.0;                                                \
-                wave_sync();                                                              \
                 TT_EACH_K(TT_M_FORM)                                                      \
                 m_sync = 0;                                                               \
             }                                                                             \
@@ -464,22 +455,15 @@ tac_reg_kernel(const TacRegParams p)
             if (p.rank) p.rank[(size_t)b * R + r] = s;
         }
         if (p.simulate) {
-            // A[k] = time of the classes released after k transfers; F_k = end of the k-th transfer;
-            // makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
             // A class is released by its last recv, the one it pointed at once its count had fallen
             // to one: kappa = 1-based position of that recv in the order, 0 for a class without recvs.
             int32_t *posl = reinterpret_cast<int32_t *>(P);        // [R] recv -> step (P is free now)
             for (int s = lane; s < R; s += 64) posl[ordl[s]] = s;
-            for (int j = lane; j <= R; j += 64) A[j] = 0.0;
             wave_sync();
-#define TT_RELEASE(k)                                                                     \
-            if constexpr (k < KT) {                                                       \
-                const int kap = sole_##k >= 0 ? posl[sole_##k] + 1 : 0;                   \
-                if (k * 64 + lane < C) atomicAdd(&A[kap], ct_##k);                        \
-            }
-            TT_EACH_K(TT_RELEASE)
-            wave_sync();                                           // posl is read before P is written below
-            // F_k into P[k - 1] (P is free now): prefix sums of the transfer times in TAC order
+#define TT_KAPPA(k) const int kap_##k = (k < KT && sole_##k >= 0) ? posl[sole_##k] + 1 : 0;
+            TT_EACH_K(TT_KAPPA)
+            wave_sync();
+            // F_k into P[k - 1]: prefix sums of the transfer times in TAC order
             double fc = 0.0;
             for (int base = 0; base < R; base += 64) {
                 const int s = base + lane;
@@ -489,6 +473,14 @@ tac_reg_kernel(const TacRegParams p)
                 fc += lane63_f64(inc);
             }
             const double F = fc;
+            wave_sync();
+            // A[k] = time of the classes released after k transfers (in the space of t, which is
+            // not read any more); makespan = max over k of F_k + (A[k] + ... + A[R]), with F_0 = 0.
+            double *A = t;
+            for (int j = lane; j <= R; j += 64) A[j] = 0.0;
+            wave_sync();
+#define TT_RELEASE(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[kap_##k], ct_##k); }
+            TT_EACH_K(TT_RELEASE)
             wave_sync();
             double ct_sum = 0.0;
 #define TT_TOTAL(k) if constexpr (k < KT) { ct_sum += ct_##k; }
@@ -520,17 +512,18 @@ tac_reg_kernel(const TacRegParams p)
 template <int KT>
 static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
 {
-    // LDS: shared rows + per wave t [R], P [R+1], A [R+1], ordl [R] i32, outstanding set [2W] u32
+    // LDS: shared rows + per wave t [R+1], P [R+1], ordl [R] i32, outstanding set [2W] u32
     const size_t rows_doubles = ((size_t)2 * d.W * 64 * KT + 1) / 2;
-    const size_t per_wave = (size_t)d.R + 2 * (d.R + 1) + ((size_t)d.R + 2 * d.W + 1) / 2 + 1;
+    const size_t per_wave = 2 * ((size_t)d.R + 1) + ((size_t)d.R + 2 * d.W + 1) / 2 + 1;
     // as many waves as LDS allows, at most reg_waves(KT)
     int waves = reg_waves(KT);
     while (waves > 4 && (rows_doubles + per_wave * waves) * 8 > 150 * 1024) --waves;
     const size_t lds = (rows_doubles + per_wave * waves) * 8;
     if (lds > (waves > 4 ? 150 : 80) * 1024) return hipErrorNotSupported;
     p.wave_doubles = (int32_t)per_wave;
-    // the class totals are summed in the space of P and A when that holds one double per class slot
-    p.col_cls = (size_t)64 * KT <= 2 * ((size_t)d.R + 1) ? d.d_col_cls : nullptr;
+    // the class totals are summed in the space of P, ordl and the outstanding set when that holds
+    // one double per class slot
+    p.col_cls = (size_t)64 * KT <= (size_t)d.R + 1 + ((size_t)d.R + 2 * d.W) / 2 ? d.d_col_cls : nullptr;
     int per_cu = 0;
     hipError_t e;
     if (lds > 48 * 1024) {
