@@ -182,8 +182,8 @@ tac_reg_kernel(const TacRegParams p)
         // A class with exactly one outstanding recv left and a positive time "points" at that
         // recv; Q is the set of recvs pointed at (the outstanding recvs with P > 0).  Tracked
         // wave-uniformly: the number of pointers, the
-        // sum and the sum of squares of their targets, and the target of the latest one.
-        int qm = 0, qs = 0, qq = 0, qlast = 0;
+        // sum of their targets, and the target of the latest one.
+        int qm = 0, qs = 0, qlast = 0;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
         int32_t *ord_next = ordl;           // where the next selected recv is recorded
 
@@ -251,11 +251,10 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_POINTER(k)                                                                     \
             {                                                                             \
                 const int l = __builtin_ctzll(nm);                                        \
-                nm &= nm - 1;                                                             \
-                const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;         \
+                nm ^= 1ull << l;                                                          \
+                const int sole = __builtin_amdgcn_readlane(sole_##k, l);                  \
                 qm += 1;                                                                  \
                 qs += sole;                                                               \
-                qq += sole * sole;                                                        \
                 qlast = sole;                                                             \
             }
 #define TT_TO_P(k, hit1, hm)     /* hm: the ballot of hit1 */                            \
@@ -313,7 +312,6 @@ tac_reg_kernel(const TacRegParams p)
             {                                                                             \
                 qm = __builtin_amdgcn_readfirstlane(qm);                                  \
                 qs = __builtin_amdgcn_readfirstlane(qs);                                  \
-                qq = __builtin_amdgcn_readfirstlane(qq);                                  \
                 qlast = __builtin_amdgcn_readfirstlane(qlast);                            \
             }
         // pointers counted afresh from the class registers (after a round that removed an
@@ -323,11 +321,10 @@ tac_reg_kernel(const TacRegParams p)
                 uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1) & ctpos_##k;    \
                 while (nm) {                                                              \
                     const int l = __builtin_ctzll(nm);                                    \
-                    nm &= nm - 1;                                                         \
-                    const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK;     \
+                    nm ^= 1ull << l;                                                      \
+                    const int sole = __builtin_amdgcn_readlane(sole_##k, l);              \
                     qm += 1;                                                              \
                     qs += sole;                                                           \
-                    qq += sole * sole;                                                    \
                     qlast = sole;                                                         \
                 }                                                                         \
             }
@@ -339,7 +336,7 @@ tac_reg_kernel(const TacRegParams p)
             // classes is not touched in it.
             while (qm == 1) {
                 const int best = qs;
-                qm = 0; qs = 0; qq = 0;
+                qm = 0; qs = 0;
                 TT_APPLY()
                 TT_UNIFORM_Q()
             }
@@ -355,19 +352,27 @@ tac_reg_kernel(const TacRegParams p)
                 if (__builtin_amdgcn_readfirstlane((int)(xa != ya))) {
                     const int best = __builtin_amdgcn_readfirstlane((int)(xa < ya)) ? b_ : a_;
                     const int other = a_ + b_ - best;
-                    qm = 1; qs = other; qq = other * other; qlast = other;
+                    qm = 1; qs = other; qlast = other;
                     TT_APPLY()
                     TT_UNIFORM_Q()
                     continue;
                 }
             }
-            if (qm >= 2 && qs == qm * qlast && qq == qm * qlast * qlast) {
-                // several pointers at one recv (both moments agree): |Q| = 1 as well
-                const int best = qlast;
-                qm = 0; qs = 0; qq = 0;
-                TT_APPLY()
-                TT_UNIFORM_Q()
-                continue;
+            if (qm >= 2 && qs == qm * qlast) {
+                // the sum allows that all pointers aim at one recv; look at them to be sure
+                uint64_t other_target = 0;
+#define TT_SAME(k)                                                                        \
+                if constexpr (k < KT)                                                     \
+                    other_target |= __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1 && sole_##k != qlast) & ctpos_##k;
+                TT_EACH_K(TT_SAME)
+                if (other_target == 0) {
+                    // several pointers at one recv: |Q| = 1 as well
+                    const int best = qlast;
+                    qm = 0; qs = 0;
+                    TT_APPLY()
+                    TT_UNIFORM_Q()
+                    continue;
+                }
             }
             int best;
             wave_sync();                    // the order so far is in ordl for the paths that read it
@@ -403,8 +408,8 @@ tac_reg_kernel(const TacRegParams p)
                     uint64_t nm = __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1) & ctpos_##k; \
                     while (nm) {                                                          \
                         const int l = __builtin_ctzll(nm);                                \
-                        nm &= nm - 1;                                                     \
-                        const int sole = __builtin_amdgcn_readlane(pk_##k, l) & IDX_MASK; \
+                        nm ^= 1ull << l;                                                  \
+                        const int sole = __builtin_amdgcn_readlane(sole_##k, l);          \
                         qbits_l |= (uint32_t)(lane == (sole & 63)) << (sole >> 6);        \
                     }                                                                     \
                 }
@@ -442,7 +447,7 @@ tac_reg_kernel(const TacRegParams p)
             }
             best = __builtin_amdgcn_readfirstlane(best);
             TT_APPLY()
-            qm = 0; qs = 0; qq = 0;
+            qm = 0; qs = 0;
             TT_EACH_K(TT_RECOUNT)
             TT_UNIFORM_Q()
         }
