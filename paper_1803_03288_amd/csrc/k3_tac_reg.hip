@@ -286,9 +286,9 @@ tac_reg_kernel(const TacRegParams p)
         // that class's time goes to P of that recv.
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
-                mk_##k = __builtin_amdgcn_sbfe(rb[k], sh, 1);            /* 0 or -1 */    \
+                mk_##k = __builtin_amdgcn_sbfe(rb[k], best, 1);   /* 0 or -1; the bit offset is best mod 32 */ \
                 __builtin_assume(mk_##k >= -1 && mk_##k <= 0);                            \
-                pk_##k += mk_##k * delta;           /* both fit 24 bits: one multiply-add */                                         \
+                pk_##k += mk_##k * delta;           /* both fit 24 bits: one multiply-add */ \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
             }
 #define TT_EVENT(k)                                                                       \
@@ -301,7 +301,6 @@ tac_reg_kernel(const TacRegParams p)
             {                                                                             \
                 *ord_next++ = best;                     /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
-                const int sh = best & 31;                                                 \
                 const int delta = CNT1 + (best & IDX_MASK);    /* the mask tells the compiler it fits 24 bits */ \
                 uint32_t hmax = 0;                                                        \
                 TT_EACH_K(TT_UPDATE)                                                      \
