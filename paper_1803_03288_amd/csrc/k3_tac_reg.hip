@@ -84,7 +84,7 @@ __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t 
 #define TT_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
 template <int KT>
-__global__ void __launch_bounds__(64 * reg_waves(KT), (KT <= 3 ? 8 : (KT <= 4 ? 5 : 1)))
+__global__ void __launch_bounds__(64 * reg_waves(KT), (KT <= 3 ? 6 : (KT <= 4 ? 5 : 1)))
 tac_reg_kernel(const TacRegParams p)
 {
     extern __shared__ double smem[];
