@@ -1,27 +1,28 @@
 // TAC (Sec. 4.3, Algorithm 3) with the iteration under its order (Sec. 3.2), one wavefront
-// per timing sample, for graphs with few classes (at most 8 per lane).  A workgroup is four
+// per timing sample, for graphs with few classes (at most 8 per lane).  A workgroup is a few
 // independent waves that share one read-only LDS copy of the class rows; lane l of a wave
-// owns the classes l, l + 64, ... and keeps their outstanding counts, M and class times in
+// owns the classes l, l + 64, ... and keeps their outstanding counts and class times in
 // VGPRs for the whole selection loop.  Per round nothing is read from global memory.
 //
 // The algorithm is the one described at the top of k3_tac.hip (incremental Algorithm 1;
 // selection by the scan over Q = {outstanding recvs with P > 0}, or by the minimum of M over
 // classes with two or more outstanding recvs when Q is empty).  How it is carried out here:
-//   * a round is instruction-bound, so it is kept short: the row bits of the selected recv
-//     come from one LDS read per lane, the per-class update is branch-free, and whatever is
-//     wave-uniform stays in scalar registers;
+//   * a round is bound by instruction issue (the scalar unit first), so it is kept short: the
+//     row bits of the selected recv come from one LDS read per lane, the per-class update is
+//     branch-free, and whatever is wave-uniform stays in scalar registers;
 //   * one register per class holds (count - 2) << 20 | sum of the indices of its outstanding
 //     recvs.  It goes negative when the count falls below 2 (the only moments at which
 //     anything else has to happen), and once the count is 1 the index sum *is* the last
-//     outstanding recv of the class, to whose P the class time is then added;
-//   * Q is tracked by its size and the sum of its members (one member: the sum is the
-//     member, the common case on layered models); the bitsets of outstanding recvs and of
-//     Q are spread over the lanes (bits j and 16 + j of lane l stand for recv 64 j + l) and
-//     are only gathered by ballots on the paths that need them;
+//     outstanding recv of the class, to whose P the class time is then added: the class
+//     "points" at that recv;
+//   * Q, the set of recvs pointed at by a class with a positive time, is tracked by the number
+//     of pointers, the sum of their targets and the latest target (one pointer: the sum is
+//     the member of Q, the common case on layered models; two pointers at two recvs: one
+//     comparison).  Only the general path enumerates Q, from the class registers;
 //   * M of a class is needed only when Q is empty or the comparator ties.  It is formed at the
-//     first such round from prefix sums T of the transfer times (the sum over the runs
-//     [lo, hi) of consecutive recv indices of its row of T[hi] - T[lo]) and brought up to date
-//     from the order built so far; rounds that do not need it do not touch it;
+//     first such round as the sum of the transfer times over the runs of consecutive recv
+//     indices of its row and brought up to date from the order built so far; rounds that do
+//     not need it do not touch it;
 //   * the class totals of a sample are formed by one coalesced pass over its op_time row,
 //     each column adding itself to its class's total in LDS;
 //   * a class is released when the recv it pointed at (its last one) is selected, so its release
