@@ -12,6 +12,9 @@
  *   4. makespan, its bounds, Scheduling Efficiency and
  *      Speedup of an iteration under a transfer order,
  *      for a batch of timing samples                       (Sec. 3.2, Eq. 1-4)
+ *   5. the same with several channels side by side         (Sec. 4.1, 5.1)
+ *   6. the straggler effect of groups of workers           (Sec. 6)
+ *   7. the time oracle estimate from measured runs         (Sec. 5)
  *
  * Conventions
  *   - "host" pointers are ordinary memory, "device" pointers are HIP device
@@ -47,7 +50,7 @@ typedef enum tictac_status {
     TICTAC_ERR_CYCLE = -3,         /* the graph is not acyclic */
     TICTAC_ERR_RECV_NOT_ROOT = -4, /* a recv op has predecessors (Sec. 2.2: recvs are roots) */
     TICTAC_ERR_DUP_RECV = -5,      /* recv_ids holds an op twice */
-    TICTAC_ERR_BAD_ORDER = -6,     /* order_stride is neither 0 nor n_recv */
+    TICTAC_ERR_BAD_ORDER = -6,     /* order_stride is neither 0 nor n_recv, or a channel index is out of range */
     TICTAC_ERR_HIP = -7,           /* a HIP runtime call failed */
     TICTAC_ERR_NO_MEM = -8,        /* host or device allocation failed */
     TICTAC_ERR_UNSUPPORTED = -9    /* size beyond what the kernels are built for */
