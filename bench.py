@@ -70,7 +70,7 @@ def tac_algorithmic_ops(nnz_ops: int, R: int, N: int) -> float:
 def main() -> int:
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (timing samples are independent and would shard "
+        print("bench.py: the library runs on one GPU only (timing samples are independent and would shard "
               "by sample with no collective); run with --gpus 1", file=sys.stderr)
         return 2
 
