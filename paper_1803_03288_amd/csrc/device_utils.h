@@ -124,6 +124,43 @@ __device__ __forceinline__ int wave_min_i32_dpp(int v)
 }
 #undef TT_DPP_SCAN
 
+// totals[cls_of[j]] += row[j] for j in [0, N), totals in LDS, by one wave.  A lane takes four
+// consecutive columns at a time and first adds up runs of equal class in registers: columns of
+// one class tend to sit next to each other, and every LDS add of several lanes to one address
+// is served one lane after the other.
+__device__ __forceinline__ void class_totals(double *totals, const double *__restrict__ row,
+                                             const int32_t *__restrict__ cls_of, int N, int lane)
+{
+    for (int j0 = lane * 4; j0 < N; j0 += 64 * 4 * 2) {          // two groups of four in flight per lane
+        double x[2][4];
+        int c[2][4];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = j0 + g * 256 + i;
+                x[g][i] = j < N ? row[j] : 0.0;
+                c[g][i] = j < N ? cls_of[j] : -1;
+            }
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            double acc = x[g][0];
+            int cur = c[g][0];
+#pragma unroll
+            for (int i = 1; i < 4; ++i) {
+                if (c[g][i] == cur) {
+                    acc += x[g][i];
+                } else {
+                    if (cur >= 0) atomicAdd(&totals[cur], acc);
+                    cur = c[g][i];
+                    acc = x[g][i];
+                }
+            }
+            if (cur >= 0) atomicAdd(&totals[cur], acc);
+        }
+    }
+}
+
 __device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t x)
 {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);

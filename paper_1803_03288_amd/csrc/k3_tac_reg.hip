@@ -146,11 +146,10 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_DECL_STATE(k) int pk_##k = -2 * CNT1, sole_##k = -1, mk_##k = 0; double M_##k = 0.0, ct_##k = 0.0;
         TT_EACH_K(TT_DECL_STATE)
         if (p.col_cls) {
-            // the row is read once, coalesced; every column adds itself to the total of its class
+            // the row is read once; every column (run of columns) adds itself to the total of its class
             for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
             wave_sync();
-            _Pragma("unroll 4")
-            for (int j = lane; j < N; j += 64) atomicAdd(&csum[p.col_cls[j]], ot[j]);
+            class_totals(csum, ot, p.col_cls, N, lane);
             wave_sync();
 #define TT_READ_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
             TT_EACH_K(TT_READ_TOTAL)

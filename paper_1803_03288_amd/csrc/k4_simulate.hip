@@ -175,20 +175,7 @@ simulate_wave_kernel(const SimWaveParams p)
         for (int r = lane; r < R; r += 64) { t[r] = rt[r]; pos[r] = 0; }
         for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
         wave_sync();
-        // eight loads of the row in flight per lane before the first is consumed
-        for (int j0 = lane; j0 < N; j0 += 64 * 8) {
-            double x[8];
-            int cls[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + u * 64;
-                x[u] = j < N ? ot[j] : 0.0;
-                cls[u] = j < N ? p.col_cls[j] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (j0 + u * 64 < N) atomicAdd(&csum[cls[u]], x[u]);
-        }
+        class_totals(csum, ot, p.col_cls, N, lane);
         wave_sync();
 #define SW_DECL(k) double ct_##k = 0.0; int kap_##k = 0;
         SW_EACH_K(SW_DECL)
@@ -384,19 +371,7 @@ simulate_channels_kernel(const SimChanParams p)
         for (int r = lane; r < R; r += 64) { t[r] = rt[r]; arr[r] = 0.0; }
         for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
         wave_sync();
-        for (int j0 = lane; j0 < N; j0 += 64 * 8) {
-            double x[8];
-            int cls[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + u * 64;
-                x[u] = j < N ? ot[j] : 0.0;
-                cls[u] = j < N ? p.col_cls[j] : 0;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (j0 + u * 64 < N) atomicAdd(&csum[cls[u]], x[u]);
-        }
+        class_totals(csum, ot, p.col_cls, N, lane);
         wave_sync();
 #define SC_DECL(k) double ct_##k = 0.0, rho_##k = 0.0;
         SW_EACH_K(SC_DECL)
