@@ -193,3 +193,31 @@ def time_oracle_min(runs) -> np.ndarray:
     _check(rc, "oracle_time_oracle_min")
     return out
 
+
+
+def order_search(n_ops: int, row_ptr, col_idx, recv_ids, order, moves, op_time, recv_time):
+    """Sec. 3.1 / 4.3: every sample climbs from its start order through the proposed exchanges
+    ``moves [n_moves][2]`` (positions of the order), keeping an exchange only when the makespan
+    of ``simulate`` gets strictly smaller.  ``order`` is ``[R]`` (shared) or ``[B][R]``.
+    Returns ``(best_order [B][R], best_makespan [B], start_makespan [B], n_accepted [B])``."""
+    row_ptr, col_idx, recv_ids = _i32(row_ptr), _i32(col_idx), _i32(recv_ids)
+    op_time, recv_time, order = _f64(op_time), _f64(recv_time), _i32(order)
+    moves = _i32(moves).reshape(-1, 2)
+    R = recv_ids.size
+    B = recv_time.shape[0]
+    assert op_time.shape == (B, n_ops - R) and recv_time.shape == (B, R)
+    if order.ndim == 1:
+        assert order.shape == (R,)
+        stride = 0
+    else:
+        assert order.shape == (B, R)
+        stride = R
+    best = np.zeros((B, R), dtype=np.int32)
+    m_best, m_start = np.zeros(B), np.zeros(B)
+    n_acc = np.zeros(B, dtype=np.int32)
+    rc = _load().oracle_order_search(ctypes.c_int(n_ops), _p(row_ptr), _p(col_idx), ctypes.c_int(R), _p(recv_ids),
+                                     ctypes.c_int(B), _p(order), ctypes.c_int(stride), ctypes.c_int(moves.shape[0]),
+                                     _p(moves), _p(op_time), _p(recv_time), _p(best), _p(m_best), _p(m_start),
+                                     _p(n_acc))
+    _check(rc, "oracle_order_search")
+    return best, m_best, m_start, n_acc

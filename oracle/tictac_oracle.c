@@ -18,6 +18,14 @@
  *                              (makespan bounds U and L, Scheduling Efficiency E,
  *                              Speedup S), Sec. 5.1 (one transfer at a time per
  *                              channel, transfers released in priority order)
+ *   oracle_simulate_channels   the same with one channel per parameter server
+ *                              (Sec. 4.1, 5.1)
+ *   oracle_straggler           Sec. 6 "Straggler Effect"
+ *   oracle_time_oracle_min     Sec. 5 "Time Oracle"
+ *   oracle_order_search        Sec. 3.1 (the best order is NP-hard to find) and
+ *                              Sec. 4.3 (the comparator is an approximation): a
+ *                              climb through proposed exchanges, measured by
+ *                              oracle_simulate
  *
  * Readings where the paper is silent or inconsistent (each is restated at the
  * function that uses it):
@@ -590,3 +598,52 @@ int oracle_time_oracle_min(int n_runs, long long n, const double *runs, double *
     return 0;
 }
 
+
+/* ---------------------------------------------------------------------------
+ * Order search with the iteration of oracle_simulate as its measure (Sec. 3.1: the best
+ * order is a job-shop problem and NP-hard, so TIC and TAC are heuristics; Sec. 4.3: the
+ * comparator extends the two-recv rule by an induction that need not hold in general).  To
+ * see how far a heuristic order is from a better one, every sample climbs from its start
+ * order through a list of proposed exchanges that the caller draws:
+ *     cur = start order, m_cur = makespan(cur)
+ *     for each move (a, b), in the order given:
+ *         positions a and b of cur are exchanged; m = makespan of that order
+ *         if m < m_cur the exchange is kept (m_cur = m), else it is undone
+ * A move with a == b or a position outside 0 .. R-1 changes nothing.  The moves are the same
+ * for every sample.
+ *   order  [R] shared (order_stride = 0) or [B][R] (order_stride = R): the start orders
+ *   moves  [n_moves][2]
+ *   best_order [B][R], best_makespan [B]: the order a sample ends with and its makespan
+ *   start_makespan [B], n_accepted [B]: may be NULL
+ * ------------------------------------------------------------------------- */
+int oracle_order_search(int n, const int32_t *row_ptr, const int32_t *col_idx, int R, const int32_t *recv_ids,
+                        int B, const int32_t *order, int order_stride, int n_moves, const int32_t *moves,
+                        const double *op_time, const double *recv_time, int32_t *best_order,
+                        double *best_makespan, double *start_makespan, int32_t *n_accepted)
+{
+    if (B < 0 || n_moves < 0) return ORACLE_ERR_ARG;
+    const int N = n - R;
+    int rc = ORACLE_OK;
+    for (int b = 0; b < B && rc == ORACLE_OK; ++b) {
+        const double *ot = op_time + (size_t)b * N, *rt = recv_time + (size_t)b * R;
+        int32_t *cur = best_order + (size_t)b * R;
+        for (int k = 0; k < R; ++k) cur[k] = order[(size_t)b * order_stride + k];
+        double m_cur, e;
+        rc = oracle_simulate(n, row_ptr, col_idx, R, recv_ids, 1, cur, 0, ot, rt, NULL, &m_cur, &e, NULL, NULL, NULL);
+        if (rc != ORACLE_OK) break;
+        if (start_makespan) start_makespan[b] = m_cur;
+        int acc = 0;
+        for (int i = 0; i < n_moves && rc == ORACLE_OK; ++i) {
+            const int pa = moves[2 * i], pb = moves[2 * i + 1];
+            if (pa < 0 || pa >= R || pb < 0 || pb >= R || pa == pb) continue;
+            int32_t x = cur[pa]; cur[pa] = cur[pb]; cur[pb] = x;
+            double m;
+            rc = oracle_simulate(n, row_ptr, col_idx, R, recv_ids, 1, cur, 0, ot, rt, NULL, &m, &e, NULL, NULL, NULL);
+            if (rc == ORACLE_OK && m < m_cur) { m_cur = m; ++acc; }
+            else { x = cur[pa]; cur[pa] = cur[pb]; cur[pb] = x; }
+        }
+        best_makespan[b] = m_cur;
+        if (n_accepted) n_accepted[b] = acc;
+    }
+    return rc;
+}
