@@ -15,6 +15,8 @@
  *   5. the same with several channels side by side         (Sec. 4.1, 5.1)
  *   6. the straggler effect of groups of workers           (Sec. 6)
  *   7. the time oracle estimate from measured runs         (Sec. 5)
+ *   8. a search for better orders by proposed exchanges,
+ *      measured by 4                                       (Sec. 3.1, 4.3)
  *
  * Conventions
  *   - "host" pointers are ordinary memory, "device" pointers are HIP device
@@ -195,6 +197,30 @@ int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double
  * where another run has a number.
  */
 int tictac_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, tictac_stream stream);
+
+/*
+ * Order search with the iteration of tictac_simulate as its measure.  Sec. 3.1: finding the best
+ * order is a job-shop problem and NP-hard, TIC and TAC are heuristics; Sec. 4.3: the comparator
+ * extends the two-recv rule by an induction that need not hold in general.  Every sample climbs
+ * from its start order through the proposed exchanges, which are the same for all samples:
+ *     cur = start order, m_cur = makespan(cur)
+ *     for every move (a, b), in the order given: exchange positions a and b of cur and take the
+ *     makespan m of that order; keep the exchange when m < m_cur (then m_cur = m), else undo it.
+ * A move with a == b or with a position outside 0 .. n_recv-1 is skipped.
+ *   order  device, start orders: order_stride = 0: one order [n_recv] for every sample;
+ *          order_stride = n_recv: [B][n_recv].  Must be permutations (not checked on the device).
+ *   moves  device, int32 [n_moves][2]; n_moves >= 0
+ *   best_order     [B][n_recv] device: the order every sample ends with
+ *   best_makespan  [B] device: its makespan, equal to what tictac_simulate gives for it
+ *   start_makespan [B] device, may be NULL: makespan of the start order
+ *   n_accepted     [B] device, may be NULL: number of exchanges that were kept
+ * Graphs without a recv, with more than 512 recvs or with more than 512 classes of compute ops
+ * with identical dependency sets: TICTAC_ERR_UNSUPPORTED.  B = 0 is valid.
+ */
+int tictac_order_search(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                        int32_t n_moves, const int32_t *moves, const double *op_time, const double *recv_time,
+                        int32_t *best_order, double *best_makespan, double *start_makespan, int32_t *n_accepted,
+                        tictac_stream stream);
 
 /* Message of the last error on the calling thread; valid until its next call. */
 const char *tictac_last_error(void);

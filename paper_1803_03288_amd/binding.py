@@ -30,7 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
-    "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min",
+    "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min", "tictac_order_search",
     "tictac_last_error", "tictac_version",
 )
 
@@ -200,6 +200,30 @@ def time_oracle_min(runs: torch.Tensor) -> torch.Tensor:
     out = torch.empty(runs.shape[1:], dtype=torch.float64, device="cuda")
     _check(lib().tictac_time_oracle_min(ctypes.c_int32(K), ctypes.c_int64(out.numel()), _dev(runs), _dev(out), _stream()))
     return out
+
+
+def order_search(dag: Dag, order: torch.Tensor, moves: torch.Tensor, op_time: torch.Tensor, recv_time: torch.Tensor):
+    """``tictac_order_search``: ``order`` int32 CUDA ``[R]`` or ``[B][R]`` (start orders), ``moves`` int32
+    CUDA ``[n_moves][2]``.  Returns ``(best_order [B][R], best_makespan, start_makespan, n_accepted)``."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    assert order.is_cuda and order.dtype == torch.int32 and order.is_contiguous()
+    assert moves.is_cuda and moves.dtype == torch.int32 and moves.is_contiguous()
+    assert moves.dim() == 2 and moves.shape[1] == 2
+    if order.dim() == 1:
+        assert order.shape == (R,)
+        stride = 0
+    else:
+        assert order.shape == (B, R)
+        stride = R
+    best = torch.empty((B, R), dtype=torch.int32, device="cuda")
+    m_best = torch.empty(B, dtype=torch.float64, device="cuda")
+    m_start = torch.empty(B, dtype=torch.float64, device="cuda")
+    n_acc = torch.empty(B, dtype=torch.int32, device="cuda")
+    _check(lib().tictac_order_search(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride),
+                                     ctypes.c_int32(moves.shape[0]), _dev(moves), _dev(op_time), _dev(recv_time),
+                                     _dev(best), _dev(m_best), _dev(m_start), _dev(n_acc), _stream()))
+    return best, m_best, m_start, n_acc
 
 
 def straggler_effect(makespan: torch.Tensor, w: int) -> torch.Tensor:

@@ -656,6 +656,40 @@ int tictac_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double
     return TICTAC_OK;
 }
 
+int tictac_order_search(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                        int32_t n_moves, const int32_t *moves, const double *op_time, const double *recv_time,
+                        int32_t *best_order, double *best_makespan, double *start_makespan, int32_t *n_accepted,
+                        tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (n_moves < 0) { set_error("n_moves = %d is negative", n_moves); return TICTAC_ERR_UNSUPPORTED; }
+    if (order_stride != 0 && order_stride != d->R) {
+        set_error("order_stride = %d, expected 0 or n_recv = %d", order_stride, d->R);
+        return TICTAC_ERR_BAD_ORDER;
+    }
+    if (d->R == 0) { set_error("the graph has no recv: there is nothing to order"); return TICTAC_ERR_UNSUPPORTED; }
+    if (d->R > 512 || d->C > 512) {
+        set_error("%d recvs and %d classes: the order search handles at most 512 of each", d->R, d->C);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    if (B == 0) return TICTAC_OK;
+    if (!order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    if (n_moves > 0 && !moves) { set_error("moves is NULL"); return TICTAC_ERR_NULL; }
+    if (!best_order || !best_makespan) { set_error("best_order or best_makespan is NULL"); return TICTAC_ERR_NULL; }
+    SearchArgs a{B, order, order_stride, n_moves, moves, op_time, recv_time, best_order, best_makespan,
+                 start_makespan, n_accepted};
+    const hipError_t e = launch_order_search(*d, a, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) {
+        set_error("graph outside what the order search handles");
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    HIP_TRY(e);
+    return TICTAC_OK;
+}
+
 const char *tictac_last_error(void) { return g_err; }
 
 const char *tictac_version(void) { return "0.1"; }

@@ -122,6 +122,11 @@ __device__ __forceinline__ int wave_min_i32_dpp(int v)
     TT_DPP_SCAN(int, dpp_i32, tt_min_i32, INT32_MAX)
     return __builtin_amdgcn_readlane(v, 63);
 }
+__device__ __forceinline__ int wave_max_i32_dpp(int v)
+{
+    TT_DPP_SCAN(int, dpp_i32, tt_max_i32, INT32_MIN)
+    return __builtin_amdgcn_readlane(v, 63);
+}
 #undef TT_DPP_SCAN
 
 // totals[cls_of[j]] += row[j] for j in [0, N), totals in LDS, by one wave.  A lane takes four

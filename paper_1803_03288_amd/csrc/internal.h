@@ -128,4 +128,19 @@ hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels
 hipError_t launch_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, hipStream_t s);
 hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s);
 
+// order search (Sec. 3.1, 4.3): a climb through proposed exchanges of two positions
+struct SearchArgs {
+    int32_t B;
+    const int32_t *order;
+    int32_t order_stride;       // 0 (one start order) or R
+    int32_t n_moves;
+    const int32_t *moves;       // [n_moves][2]
+    const double *op_time, *recv_time;
+    int32_t *best_order;
+    double *best_makespan, *start_makespan;
+    int32_t *n_accepted;
+};
+// hipErrorNotSupported: the graph is outside what the kernel handles
+hipError_t launch_order_search(Dag &d, const SearchArgs &a, hipStream_t s);
+
 }  // namespace tictac

@@ -88,4 +88,7 @@ def test_null_handle_is_rejected(L):
     assert L.tictac_straggler_effect(ctypes.c_int32(-1), ctypes.c_int32(2), None, None, None) == -9
     assert L.tictac_straggler_effect(ctypes.c_int32(8), ctypes.c_int32(2), None, None, None) == -1
     assert L.tictac_straggler_effect(ctypes.c_int32(3), ctypes.c_int32(4), None, None, None) == 0     # no whole group
+    # order search: no handle
+    assert L.tictac_order_search(None, ctypes.c_int32(1), None, ctypes.c_int32(0), ctypes.c_int32(0), None, None, None,
+                                 None, None, None, None, None) == -1
     assert binding.version().count(".") == 1

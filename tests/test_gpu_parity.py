@@ -361,6 +361,80 @@ def test_several_channels_limits(tt):
     assert np.array_equal(got[0].cpu().numpy(), opn.sum(axis=1))
 
 
+EXTRA = {
+    "r64": lambda: wl.layered_dag(94, levels=7, width=9, fan_in=(1, 3), back=2, n_recv=64, attach=(1, 3)),
+    "r129": lambda: wl.layered_dag(159, levels=7, width=9, fan_in=(1, 3), back=2, n_recv=129, attach=(1, 3)),
+}
+
+
+@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "case2", "single", "chain", "r64",
+                                  "r129", "resnet50", "vgg16", "inception3"])
+def test_order_search(tt, name):
+    """tictac_order_search against the oracle: the orders the samples end with, both makespans
+    and the number of kept exchanges, from random start orders per sample and from the TIC
+    order for all samples; moves include exchanges of a position with itself and positions
+    outside the order.  The makespan it reports is the one tictac_simulate gives for that order."""
+    makers = dict(SMALL)
+    makers.update(EXTRA)
+    d, h, dep = get(tt, name, makers.get(name))
+    R = d.n_recv
+    B, n_moves = {"resnet50": (10, 48), "vgg16": (40, 48), "inception3": (3, 24)}.get(name, (37, 150))
+    print(f"[order_search] {name}: R={R} B={B} moves={n_moves}", flush=True)
+    op, rv = wl.timing_samples(d, 0, B)
+    rng = np.random.default_rng(29)
+    start = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    moves = rng.integers(0, R, size=(n_moves, 2)).astype(np.int32)
+    moves[3] = (-1, 0)
+    moves[7] = (0, R)
+    moves[11] = (R - 1, R - 1)
+    gop, grv = cuda(op), cuda(rv)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    tic_order = oracle.tic(dep, d.recv_ids)[1].astype(np.int32)
+    for st in (start, tic_order):
+        exp = oracle.order_search(*args, st, moves, op, rv)
+        got = tt.order_search(h, cuda(st), cuda(moves), gop, grv)
+        for a, b, nm in zip(got, exp, ("best_order", "best_makespan", "start_makespan", "n_accepted")):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: {nm}"
+        again = tt.simulate(h, got[0], gop, grv)[0]
+        assert torch.equal(again, got[1])
+    # no moves: the start orders come back with their makespans
+    got = tt.order_search(h, cuda(start), torch.zeros((0, 2), dtype=torch.int32, device="cuda"), gop, grv)
+    assert np.array_equal(got[0].cpu().numpy(), start) and torch.equal(got[1], got[2])
+    assert int(got[3].abs().sum()) == 0
+    # zero-length transfers and zero-time ops (many equal makespans: nothing is kept on a tie)
+    op0, rv0 = op.copy(), rv.copy()
+    op0[rng.random(op0.shape) < 0.3] = 0.0
+    rv0[rng.random(rv0.shape) < 0.3] = 0.0
+    exp = oracle.order_search(*args, start, moves, op0, rv0)
+    got = tt.order_search(h, cuda(start), cuda(moves), cuda(op0), cuda(rv0))
+    for a, b in zip(got, exp):
+        assert np.array_equal(a.cpu().numpy(), b)
+
+
+def test_order_search_limits(tt):
+    from paper_1803_03288_amd.binding import TicTacError
+    ds, hs, _ = get(tt, "stress")
+    mv = torch.zeros((1, 2), dtype=torch.int32, device="cuda")
+    with pytest.raises(TicTacError) as e:
+        tt.order_search(hs, torch.zeros(ds.n_recv, dtype=torch.int32, device="cuda"), mv,
+                        torch.zeros((1, ds.n_compute), dtype=torch.float64, device="cuda"),
+                        torch.zeros((1, ds.n_recv), dtype=torch.float64, device="cuda"))
+    assert e.value.code == -9
+    dn = wl.no_recv_dag(17)
+    hn = tt.build_deps(dn.n_ops, dn.row_ptr, dn.col_idx, dn.recv_ids)
+    with pytest.raises(TicTacError) as e:
+        tt.order_search(hn, torch.zeros(0, dtype=torch.int32, device="cuda"), mv,
+                        torch.zeros((2, 17), dtype=torch.float64, device="cuda"),
+                        torch.zeros((2, 0), dtype=torch.float64, device="cuda"))
+    assert e.value.code == -9
+    # an empty batch is valid
+    d, h, _ = get(tt, "toy", wl.toy_dag)
+    got = tt.order_search(h, torch.tensor([0, 1], dtype=torch.int32, device="cuda"), mv,
+                          torch.zeros((0, d.n_compute), dtype=torch.float64, device="cuda"),
+                          torch.zeros((0, 2), dtype=torch.float64, device="cuda"))
+    assert got[0].shape == (0, 2)
+
+
 def test_time_oracle_min(tt):
     """Minimum over measured runs, element by element against the oracle: even and odd lengths
     (two-element and one-element loads), one run, many runs, a batch of timing rows."""
