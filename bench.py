@@ -186,6 +186,33 @@ def main() -> int:
                     "frac_of_hbm_peak": c_bytes / c_s / 1e9 / HBM_PEAK_GBS,
                     "mean_makespan_s": float(rc_[0].mean()), "mean_efficiency": float(rc_[1].mean())}
 
+    # ---- order search: every sample climbs from its random order through 1024 proposed exchanges ----
+    search = None
+    if not args.no_compare and 0 < d.n_recv <= 512 and h.n_classes <= 512:
+        n_moves = 1024
+        mv = torch.from_numpy(np.random.default_rng(d.seed + 77).integers(0, d.n_recv, size=(n_moves, 2))
+                              .astype(np.int32)).cuda()
+        rnd = torch.from_numpy(wl.random_orders(d, 0, B)).cuda()
+        sms = []
+        for i in range(4):
+            a, b = ev(), ev()
+            a.record()
+            sr_ = tt.order_search(h, rnd, mv, gop, grv)
+            b.record()
+            torch.cuda.synchronize()
+            if i >= 1:
+                sms.append(a.elapsed_time(b))
+        s_s = float(np.mean(sms)) * 1e-3
+        from_tac = tt.order_search(h, tt.tac_priority(h, gop, grv)[0], mv, gop, grv)
+        search = {"n_moves": n_moves, "start": "random order per sample", "ms_per_launch": s_s * 1e3,
+                  "sample_moves_per_s": n_moves * B / s_s,
+                  "mean_makespan_start_s": float(sr_[2].mean()), "mean_makespan_end_s": float(sr_[1].mean()),
+                  "mean_exchanges_kept": float(sr_[3].double().mean()),
+                  "from_tac": {"mean_makespan_start_s": float(from_tac[2].mean()),
+                               "mean_makespan_end_s": float(from_tac[1].mean()),
+                               "samples_improved": int((from_tac[3] > 0).sum())}}
+        del rnd, sr_, from_tac
+
     # ---- time oracle estimator: minimum over five measured runs of the whole op_time array ----
     time_oracle = None
     if not args.no_compare:
@@ -296,7 +323,7 @@ def main() -> int:
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{d.name} preset (seed {d.seed}): N={d.n_compute} compute ops, R={d.n_recv} recvs, "
                                f"B={B} timing samples; step = build_deps + TIC + fused TAC/simulate"},
-        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels, "time_oracle_min": time_oracle,
+        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels, "time_oracle_min": time_oracle, "order_search": search,
         "cpu_baseline": cpu,
         "mean_scheduling_efficiency": mean_eff,
     }

@@ -20,6 +20,15 @@
 // wave does over the row (one recv per lane and word); every other class keeps its kappa.  A and
 // the two scans are then formed afresh from the registers, so every makespan is the one a full
 // evaluation of that order gives.
+//
+// Most moves are turned down without that evaluation.  Let k* be a position where the current
+// makespan is attained, m_cur = F_k* + S_k* (S_k = class time with kappa >= k).  The makespan after
+// the move is at least F'_k* + S'_k*.  Exchanging positions lo < hi leaves F_k and S_k as they are
+// for k <= lo and for k > hi + 1, so a move with k* outside lo + 1 .. hi + 1 cannot help (decided
+// for 64 moves at a time, one per lane).  Otherwise F_k* changes by Time(y) - Time(x) when k* <= hi, S_k* gains the
+// classes with x whose kappa was below k* and loses at most the classes that need their maximum
+// taken again; when that sum is not negative the move cannot help either (one wave sum, no LDS
+// write).  Only the remaining moves are evaluated.
 #include "device_utils.h"
 #include "internal.h"
 
@@ -136,19 +145,39 @@ order_search_kernel(const SearchParams p)
 
         double m_cur = 0.0;
         int n_acc = 0;
-        for (int it = -1; it < p.n_moves; ++it) {
-            int lo = 0, hi = 0, x = 0, y = 0;
-            if (it >= 0) {
-                const int pa = p.moves[2 * it], pb = p.moves[2 * it + 1];
-                if ((unsigned)pa >= (unsigned)R || (unsigned)pb >= (unsigned)R || pa == pb) continue;
-                lo = min(pa, pb);
-                hi = max(pa, pb);
+        int kstar = 0;                      // a position where the current makespan is attained
+        // 64 moves at a time, one per lane: the moves that k* rules out are dropped by one ballot
+        int base = -64;                     // first move of the chunk in mv_lo / mv_hi
+        int mv_lo = 0, mv_hi = -1;          // lane i: the positions of move base + i; mv_hi < 0: not an exchange
+        unsigned long long todo = 0;        // moves of the chunk that are still to be looked at
+        bool first = true;                  // the start order is evaluated before any move
+        for (;;) {
+            int lo = 0, hi = 0, x = 0, y = 0, cur = 0;
+            if (!first) {
+                while (todo == 0) {
+                    base += 64;
+                    if (base >= p.n_moves) break;
+                    const int i = base + lane;
+                    const int pa = i < p.n_moves ? p.moves[2 * i] : -1;
+                    const int pb = i < p.n_moves ? p.moves[2 * i + 1] : -1;
+                    const bool ok = (unsigned)pa < (unsigned)R && (unsigned)pb < (unsigned)R && pa != pb;
+                    mv_lo = min(pa, pb);
+                    mv_hi = ok ? max(pa, pb) : -1;
+                    todo = __ballot(mv_hi >= 0 && kstar > mv_lo && kstar <= mv_hi + 1);
+                }
+                if (todo == 0) break;       // no move left
+                cur = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                lo = __builtin_amdgcn_readlane(mv_lo, cur);
+                hi = __builtin_amdgcn_readlane(mv_hi, cur);
                 x = __builtin_amdgcn_readfirstlane((int)ordl[lo]);      // moves from lo to hi
                 y = __builtin_amdgcn_readfirstlane((int)ordl[hi]);      // moves from hi to lo
                 const double tx = t[x], ty = t[y];
                 // which classes hold x, which hold y
                 const int wx = x >> 6, wy = y >> 6;
                 const uint64_t bx = (uint64_t)1 << (x & 63), by = (uint64_t)1 << (y & 63);
+                double dsum = 0.0;          // change of S at k*: classes gained, classes that may be lost
+                bool moved = false;
 #define OS_MEMBER(k)                                                                      \
                 bool redo_##k = false;                                                    \
                 if constexpr (k < T) {                                                    \
@@ -159,9 +188,15 @@ order_search_kernel(const SearchParams p)
                         const bool has_y = (rows[(size_t)c * W + wy] & by) != 0;          \
                         if (has_x) kn_##k = max(kap_##k, hi + 1);                         \
                         redo_##k = has_y && !has_x && kap_##k == hi + 1;                  \
+                        if (has_x && kap_##k < kstar) { dsum += ct_##k; moved = true; }   \
+                        if (redo_##k) { dsum -= ct_##k; moved = true; }                   \
                     }                                                                     \
                 }
                 OS_EACH(OS_MEMBER)
+                double d = kstar <= hi ? ty - tx : 0.0;
+                if (__ballot(moved)) d += wave_sum_f64_dpp(dsum);
+                // (the comparison is the same in every lane; taking it from the first one tells the compiler so)
+                if (__builtin_amdgcn_readfirstlane((int)(d >= 0.0))) continue;     // F'_k* + S'_k* >= m_cur: the move cannot help
                 wave_sync();
                 if (lane == 0) {
                     ordl[lo] = (uint16_t)y; ordl[hi] = (uint16_t)x;
@@ -212,6 +247,7 @@ order_search_kernel(const SearchParams p)
             OS_EACH(OS_F)
             wave_sync();
             double sfx = 0.0, mloc = sum_c;                   // k = 0: F_0 + S_0 = all class time
+            int kb = 0;                                       // where this lane's maximum is attained
 #define OS_SUFFIX(kk)                                                                     \
             if constexpr (7 - kk < T) {                                                   \
                 constexpr int j = 7 - kk;                                                 \
@@ -220,7 +256,8 @@ order_search_kernel(const SearchParams p)
                     const double a = k <= R ? A[k] : 0.0;                                 \
                     const double inc = wave_incl_scan_f64_dpp(a);                         \
                     const double tot = lane63_f64(inc);                                   \
-                    if (k <= R) mloc = fmax(mloc, OS_F_OF(j) + (sfx + (tot - inc + a)));  \
+                    const double cand = OS_F_OF(j) + (sfx + (tot - inc + a));             \
+                    if (k <= R && cand > mloc) { mloc = cand; kb = k; }                   \
                     sfx += tot;                                                           \
                 }                                                                         \
             }
@@ -228,15 +265,21 @@ order_search_kernel(const SearchParams p)
             OS_EACH(OS_SUFFIX)
             const double m = wave_max_f64_dpp(mloc);
 
-            if (it < 0) {
-                m_cur = m;
-                if (lane == 0 && p.start_makespan) p.start_makespan[b] = m;
 #define OS_KEEP(k) if constexpr (k < T) { kap_##k = kn_##k; }
-                OS_EACH(OS_KEEP)
-            } else if (m < m_cur) {
+            if (first || __builtin_amdgcn_readfirstlane((int)(m < m_cur))) {
                 m_cur = m;
-                ++n_acc;
+                const unsigned long long at = __ballot(mloc == m);
+                kstar = at ? __builtin_amdgcn_readlane(kb, __builtin_ctzll(at)) : 0;
                 OS_EACH(OS_KEEP)
+                if (first) {
+                    if (lane == 0 && p.start_makespan) p.start_makespan[b] = m;
+                    first = false;
+                } else {
+                    ++n_acc;
+                    // the moves after this one, under the new k*
+                    const unsigned long long later = cur == 63 ? 0ull : ~0ull << (cur + 1);
+                    todo = __ballot(mv_hi >= 0 && kstar > mv_lo && kstar <= mv_hi + 1) & later;
+                }
             } else {
                 const double tx = t[x], ty = t[y];
 #define OS_SWAP_BACK(k) OS_SWAP_X(k, tx, ty)
