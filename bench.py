@@ -9,8 +9,10 @@ every sample under its TAC order (``tictac_tac_simulate``, the fused form of
 are resident in device memory before the timed region starts.
 
 Prints one JSON line: timing-sample schedules per second, the roofline record of the
-dominant kernel (TAC), the dependency-propagation bandwidth on the stress preset, and
-the CPU oracle timed on a bounded sample of the same workload.
+dominant kernel (TAC), the dependency-propagation bandwidth on the stress preset, the
+side legs on the same samples (random, TIC and TAC orders compared, several channels, the
+time-oracle estimator, the order search) and the CPU oracle timed on a bounded sample of the
+same workload.
 """
 
 from __future__ import annotations
