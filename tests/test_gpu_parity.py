@@ -512,6 +512,19 @@ def test_full_batch_properties(tt, name, B):
     for b0 in range(0, B, blk):
         ref = closed_form_shared(depb, tic_order, op[b0:b0 + blk], rv[b0:b0 + blk])
         assert np.array_equal(m2[b0:b0 + blk], ref)
+    # order search on the whole batch from random orders: permutations, never worse than the start,
+    # the makespan it reports is the one of the order it returns, sampled rows equal the oracle
+    rnd = wl.random_orders(d, 0, B)
+    moves = np.random.default_rng(3).integers(0, R, size=(192, 2)).astype(np.int32)
+    best, mb, ms, acc = tt.order_search(h, cuda(rnd), cuda(moves), gop, grv)
+    assert torch.equal(torch.sort(best.long(), dim=1).values, torch.arange(R, device="cuda").expand(B, R))
+    assert bool((mb <= ms).all()) and bool(((acc > 0) == (mb < ms)).all())
+    assert torch.equal(tt.simulate(h, best, gop, grv)[0], mb)
+    assert torch.equal(tt.simulate(h, cuda(rnd), gop, grv)[0], ms)
+    rows = subset_rows(B, 12 if name == "resnet50" else 64)
+    exp = oracle.order_search(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, rnd[rows], moves, op[rows], rv[rows])
+    for a, b_ in zip((best, mb, ms, acc), exp):
+        assert np.array_equal(a[rows].cpu().numpy(), b_)
 
 
 def test_stress_full_size_first_rounds(tt):
