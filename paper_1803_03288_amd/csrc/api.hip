@@ -31,6 +31,36 @@ void set_error(const char *fmt, ...)
         }                                                                                    \
     } while (0)
 
+// Pinned host memory for the transfers of tictac_build_deps: one block per calling thread,
+// grown on demand and kept until the thread's next larger request (pinning costs milliseconds,
+// and copies from or to pageable memory are staged by the runtime and take three to four
+// times as long).  NULL when the request is empty, beyond the cap, or cannot be pinned: the
+// caller then copies from or to its own pageable memory.  The block is free again once the
+// stream has been synchronised, which tictac_build_deps does before it returns.
+static thread_local void *g_stage = nullptr;
+static thread_local size_t g_stage_bytes = 0;
+constexpr size_t kStageMax = (size_t)96 << 20;
+
+static void *stage(size_t bytes)
+{
+    if (bytes == 0 || bytes > kStageMax) return nullptr;
+    if (bytes <= g_stage_bytes) return g_stage;
+    if (g_stage) {
+        (void)hipHostFree(g_stage);
+        g_stage = nullptr;
+        g_stage_bytes = 0;
+    }
+    const size_t want = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
+    void *q = nullptr;
+    if (hipHostMalloc(&q, want, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_stage = q;
+    g_stage_bytes = want;
+    return q;
+}
+
 // Collects host arrays (and device-only reservations) into one device block: one
 // allocation and one host-to-device copy instead of one of each per array.
 struct Packer {
@@ -69,7 +99,12 @@ struct Packer {
         if (e != hipSuccess) return e;
         for (const Fix &f : fixes) *f.dst = static_cast<char *>(*block) + f.off;
         if (host.empty()) return hipSuccess;
-        return hipMemcpyAsync(*block, host.data(), host.size(), hipMemcpyHostToDevice, s);
+        const void *src = host.data();
+        if (void *st = stage(host.size())) {
+            memcpy(st, host.data(), host.size());
+            src = st;
+        }
+        return hipMemcpyAsync(*block, src, host.size(), hipMemcpyHostToDevice, s);
     }
 };
 
@@ -375,14 +410,21 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     graph.add(&d->d_src, src);
     const size_t dep_words = (size_t)n * d->W;
     graph.reserve(&d->d_dep, dep_words * 8);
+    // (sized for the copy back of the rows as well, so that the block is not replaced while a copy is under way)
+    (void)stage(std::max(graph.host.size(), dep_words * 8));
     HIP_TRY(graph.commit(&d->d_graph_block, s));
     if (dep_words) HIP_TRY(launch_propagate(*d, s));
 
     // ---- classes of identical rows among the compute ops ----
     std::vector<uint64_t> rows((size_t)d->N * d->W);
     if (!rows.empty()) {
-        std::vector<uint64_t> all(dep_words);
-        HIP_TRY(hipMemcpyAsync(all.data(), d->d_dep, dep_words * 8, hipMemcpyDeviceToHost, s));
+        std::vector<uint64_t> pageable;
+        uint64_t *all = static_cast<uint64_t *>(stage(dep_words * 8));   // stream order: after the copy of the graph block out of it
+        if (!all) {
+            pageable.resize(dep_words);
+            all = pageable.data();
+        }
+        HIP_TRY(hipMemcpyAsync(all, d->d_dep, dep_words * 8, hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         for (int32_t v = 0; v < n; ++v)
             if (comp_col[v] >= 0)

@@ -13,6 +13,7 @@
 // level order ("positions"); the slice of the most recent RING positions is kept in an LDS
 // ring, so that inputs from recent levels cost an LDS read and only long edges go to
 // memory.
+#include "device_utils.h"
 #include "internal.h"
 
 namespace tictac {
@@ -349,6 +350,72 @@ _Pragma("unroll")                                                               
 #undef K1_REQUEST
 }
 
+// Narrow graphs (no level wider than 64 / WC nodes, all nodes and their records in LDS): one
+// wave per slice and no barrier at all.  The LDS operations of a wave are carried out in the
+// order in which they are issued, so a row written at one level can be read by another lane at
+// the next without a wait in between; the record of the next level's node is read from LDS a
+// level ahead, which leaves one LDS round trip per level: the reads of the input rows.  Rows go
+// to memory as they are computed and are never read back here.
+template <int WC>
+__global__ void __launch_bounds__(64)
+propagate_nodes_wave(const PropParams p)
+{
+    extern __shared__ uint64_t ring[];          // rows [ring + 2][WC] (the last two all zero), records [M][2], level bounds [L + 1], input lists
+    const int W = p.W, L = p.n_levels, M = p.M;
+    const int w = threadIdx.x % WC, sub = threadIdx.x / WC;
+    const int gw = slice_of_block() * WC + w;
+    int4 *recs = reinterpret_cast<int4 *>(ring + (size_t)(p.ring + 2) * WC);
+    int32_t *lvl = reinterpret_cast<int32_t *>(recs + (size_t)2 * M);
+    int32_t *fov = lvl + (L + 1);
+    if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
+    const int4 *src = reinterpret_cast<const int4 *>(p.frecs);
+    for (int i = threadIdx.x; i < 2 * M; i += 64) recs[i] = src[i];
+    for (int i = threadIdx.x; i <= L; i += 64) lvl[i] = p.nlvl_ptr[i];
+    for (int i = threadIdx.x; i < p.fovf_lds; i += 64) fov[i] = p.fovf[i];
+    __syncthreads();
+    if (L == 0) return;
+
+    int beg = lvl[0], end = lvl[1], end2 = lvl[min(2, L)];
+    int4 ra = make_int4(0, 0, 0, 0), rb = ra;
+    if (beg + sub < end) { ra = recs[(size_t)(beg + sub) * 2]; rb = recs[(size_t)(beg + sub) * 2 + 1]; }
+    for (int lv = 0; lv < L; ++lv) {
+        // the record of the next level's node and the bound after it, a level ahead
+        int4 na = make_int4(0, 0, 0, 0), nb = na;
+        if (lv + 1 < L && end + sub < end2) { na = recs[(size_t)(end + sub) * 2]; nb = recs[(size_t)(end + sub) * 2 + 1]; }
+        const int end3 = lvl[min(lv + 3, L)];
+        const int pos = beg + sub;
+        if (pos < end) {
+            const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;
+            const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + ra.x);
+            const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + ra.y);
+            const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + ra.z);
+            const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + ra.w);
+            uint64_t bits = (rb.x >> 6) == gw ? 1ull << (rb.x & 63) : 0ull;
+            bits |= (rb.y >> 6) == gw ? 1ull << (rb.y & 63) : 0ull;
+            uint64_t val = bits | v0 | v1 | v2 | v3;
+            const int ovf_beg = rb.w;
+            if (ovf_beg >= 0) {                       // any other node: all inputs from its list (every node is in the ring)
+                const int ovf_cnt = fov[ovf_beg];
+                for (int e = 1; e <= ovf_cnt; ++e) {
+                    const int x = fov[ovf_beg + e];
+                    if (x < 0) {
+                        const int i = ~x;
+                        if ((i >> 6) == gw) val |= 1ull << (i & 63);
+                    } else {
+                        val |= ring[(size_t)x * WC + w];
+                    }
+                }
+            }
+            if (gw >= W) val = 0;
+            ring[(size_t)pos * WC + w] = val;
+            if (gw < W) p.dep[(size_t)rb.z * W + gw] = val;
+        }
+        wave_sync();
+        beg = end; end = end2; end2 = end3;
+        ra = na; rb = nb;
+    }
+}
+
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto
 __global__ void __launch_bounds__(256)
 expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep)
@@ -380,6 +447,20 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     if (!wide && !d.d_frecs) return hipErrorInvalidValue;
     const int ring = d.k1_ring;
     p.ring = ring;
+    // one wave per slice when no level is wider than a wave and everything fits in LDS
+    if (!wide && threads == 64 && d.M <= ring && (d.fovf_len == 0 || p.fovf_lds > 0)) {
+        const size_t lds_w = (size_t)(ring + 2) * WC * 8 + (size_t)d.M * 32 + (size_t)(d.n_node_levels + 1) * 4 +
+                             (size_t)p.fovf_lds * 4;
+        if (lds_w <= 150 * 1024) {
+            if (lds_w > 48 * 1024) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_nodes_wave<WC>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+                if (e != hipSuccess) return e;
+            }
+            hipLaunchKernelGGL(propagate_nodes_wave<WC>, dim3(blocks), dim3(64), lds_w, s, p);
+            return hipGetLastError();
+        }
+    }
     size_t lds = (size_t)ring * WC * 8;
     if (wide) lds += (size_t)4 * per_pass * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
     else lds += (size_t)2 * WC * 8 + (size_t)4 * RPT * per_pass * 16 + (size_t)2 * (WIN_LEVELS + WIN_MARGIN) * 4 +
