@@ -215,6 +215,31 @@ def main() -> int:
                                "samples_improved": int((from_tac[3] > 0).sum())}}
         del rnd, sr_, from_tac
 
+    # ---- the same samples stored as float32 (converted on load, float64 arithmetic) ----
+    f32 = None
+    if not args.no_compare and d.n_recv > 0:
+        gop32, grv32 = gop.float(), grv.float()
+        rec32 = {}
+        for leg in ("tac_simulate", "simulate"):
+            fms = []
+            for i in range(5):
+                a, b = ev(), ev()
+                a.record()
+                if leg == "tac_simulate":
+                    r32 = tt.tac_simulate(h, gop32, grv32)
+                else:
+                    r32s = tt.simulate(h, r32[0], gop32, grv32)
+                b.record()
+                torch.cuda.synchronize()
+                if i >= 1:
+                    fms.append(a.elapsed_time(b))
+            rec32[leg + "_ms"] = float(np.mean(fms))
+        m32, m64 = r32[4], out[0]
+        f32 = dict(rec32, hbm_bytes_per_sample=4.0 * (d.n_compute + d.n_recv),
+                   max_rel_makespan_difference_from_float64_input=float(((m32 - m64).abs() / m64).max()),
+                   orders_equal_to_float64_input=float((r32[0] == tt.tac_priority(h, gop, grv)[0]).all(dim=1).double().mean()))
+        del gop32, grv32, r32, r32s
+
     # ---- time oracle estimator: minimum over five measured runs of the whole op_time array ----
     time_oracle = None
     if not args.no_compare:
@@ -325,7 +350,7 @@ def main() -> int:
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{d.name} preset (seed {d.seed}): N={d.n_compute} compute ops, R={d.n_recv} recvs, "
                                f"B={B} timing samples; step = build_deps + TIC + fused TAC/simulate"},
-        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels, "time_oracle_min": time_oracle, "order_search": search,
+        "roofline": roofline, "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels, "time_oracle_min": time_oracle, "order_search": search, "float32_storage": f32,
         "cpu_baseline": cpu,
         "mean_scheduling_efficiency": mean_eff,
     }

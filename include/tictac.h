@@ -17,6 +17,8 @@
  *   7. the time oracle estimate from measured runs         (Sec. 5)
  *   8. a search for better orders by proposed exchanges,
  *      measured by 4                                       (Sec. 3.1, 4.3)
+ * 3 and 4 also take the timing samples as float32 arrays (tictac_simulate_f32,
+ * tictac_tac_simulate_f32).
  *
  * Conventions
  *   - "host" pointers are ordinary memory, "device" pointers are HIP device
@@ -157,6 +159,23 @@ int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time,
                         int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus,
                         double *makespan, double *eff, double *U, double *L, double *S,
                         tictac_stream stream);
+
+/*
+ * The two calls above with the timing arrays stored as float32 (half the bytes of the pass over
+ * the samples).  Every value is converted to float64 when it is loaded and all sums and
+ * comparisons are float64, so the results are those of the float64 calls on the converted values:
+ * orders are the TAC orders of the rounded times, and makespans differ from those of unrounded
+ * float64 times by the rounding of the inputs (below 1e-6 relative; the float32 bound is 1e-3).
+ *   op_time [B][N], recv_time [B][n_recv]   device, float32, row-major
+ * Everything else as in tictac_simulate and tictac_tac_simulate (outputs are float64).
+ */
+int tictac_simulate_f32(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                        const float *op_time, const float *recv_time, double *makespan, double *eff,
+                        double *U, double *L, double *S, tictac_stream stream);
+int tictac_tac_simulate_f32(const tictac_dag *dag, int32_t B, const float *op_time, const float *recv_time,
+                            int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus,
+                            double *makespan, double *eff, double *U, double *L, double *S,
+                            tictac_stream stream);
 
 /*
  * tictac_simulate with several channels (Sec. 4.1: a device has one channel per parameter

@@ -30,6 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
+    "tictac_simulate_f32", "tictac_tac_simulate_f32",
     "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min", "tictac_order_search",
     "tictac_last_error", "tictac_version",
 )
@@ -129,10 +130,11 @@ def tic_priority(dag: Dag) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     return prio, order, rank
 
 
-def _check_times(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor) -> int:
+def _check_times(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, allow_f32: bool = False) -> int:
     B = recv_time.shape[0]
     assert op_time.is_cuda and recv_time.is_cuda
-    assert op_time.dtype == torch.float64 and recv_time.dtype == torch.float64
+    assert op_time.dtype == recv_time.dtype
+    assert op_time.dtype == torch.float64 or (allow_f32 and op_time.dtype == torch.float32)
     assert op_time.is_contiguous() and recv_time.is_contiguous()
     assert tuple(op_time.shape) == (B, dag.n_compute), (tuple(op_time.shape), (B, dag.n_compute))
     assert tuple(recv_time.shape) == (B, dag.n_recv)
@@ -154,9 +156,9 @@ def tac_priority(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_
 
 
 def simulate(dag: Dag, order: torch.Tensor, op_time: torch.Tensor, recv_time: torch.Tensor):
-    """``tictac_simulate``: ``(makespan, eff, U, L, S)``, float64 CUDA tensors ``[B]``.
-    ``order`` is int32 ``[R]`` (shared) or ``[B][R]``."""
-    B = _check_times(dag, op_time, recv_time)
+    """``tictac_simulate`` (``tictac_simulate_f32`` for float32 timing arrays): ``(makespan, eff, U, L, S)``,
+    float64 CUDA tensors ``[B]``.  ``order`` is int32 ``[R]`` (shared) or ``[B][R]``."""
+    B = _check_times(dag, op_time, recv_time, allow_f32=True)
     R = dag.n_recv
     assert order.is_cuda and order.dtype == torch.int32 and order.is_contiguous()
     if order.dim() == 1:
@@ -166,8 +168,9 @@ def simulate(dag: Dag, order: torch.Tensor, op_time: torch.Tensor, recv_time: to
         assert tuple(order.shape) == (B, R)
         stride = R
     out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
-    _check(lib().tictac_simulate(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride), _dev(op_time),
-                                 _dev(recv_time), *(_dev(o) for o in out), _stream()))
+    fn = lib().tictac_simulate_f32 if op_time.dtype == torch.float32 else lib().tictac_simulate
+    _check(fn(dag._h, ctypes.c_int32(B), _dev(order), ctypes.c_int32(stride), _dev(op_time), _dev(recv_time),
+              *(_dev(o) for o in out), _stream()))
     return tuple(out)
 
 
@@ -237,17 +240,18 @@ def straggler_effect(makespan: torch.Tensor, w: int) -> torch.Tensor:
 
 def tac_simulate(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_rank: bool = False,
                  want_sel: bool = False):
-    """``tictac_tac_simulate``: TAC and the iteration under its order in one pass.
-    Returns ``(order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S)``."""
-    B = _check_times(dag, op_time, recv_time)
+    """``tictac_tac_simulate`` (``tictac_tac_simulate_f32`` for float32 timing arrays): TAC and the iteration
+    under its order in one pass.  Returns ``(order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S)``."""
+    B = _check_times(dag, op_time, recv_time, allow_f32=True)
     R = dag.n_recv
     order = torch.empty((B, R), dtype=torch.int32, device="cuda")
     rank = torch.empty((B, R), dtype=torch.int32, device="cuda") if want_rank else None
     sel_P = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
     sel_M = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
     out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
-    _check(lib().tictac_tac_simulate(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order),
-                                     _dev(rank), _dev(sel_P), _dev(sel_M), *(_dev(o) for o in out), _stream()))
+    fn = lib().tictac_tac_simulate_f32 if op_time.dtype == torch.float32 else lib().tictac_tac_simulate
+    _check(fn(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order), _dev(rank), _dev(sel_P),
+              _dev(sel_M), *(_dev(o) for o in out), _stream()))
     return (order, rank, sel_P, sel_M) + tuple(out)
 
 

@@ -574,7 +574,7 @@ int tictac_tic_priority(const tictac_dag *dag, int32_t *prio, int32_t *order, in
     return TICTAC_OK;
 }
 
-static int check_batch(const Dag *d, int32_t B, const double *op_time, const double *recv_time)
+static int check_batch(const Dag *d, int32_t B, const void *op_time, const void *recv_time)
 {
     if (B < 0) { set_error("B = %d", B); return TICTAC_ERR_BAD_CSR; }
     if (B > 0 && d->N > 0 && !op_time) { set_error("op_time is NULL"); return TICTAC_ERR_NULL; }
@@ -596,9 +596,9 @@ int tictac_tac_priority(const tictac_dag *dag, int32_t B, const double *op_time,
     return TICTAC_OK;
 }
 
-int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
-                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, double *makespan,
-                        double *eff, double *U, double *L, double *S, tictac_stream stream)
+static int tac_simulate_any(const tictac_dag *dag, int32_t B, const void *op_time, const void *recv_time, bool f32,
+                            int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, double *makespan,
+                            double *eff, double *U, double *L, double *S, tictac_stream stream)
 {
     if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
     Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
@@ -607,13 +607,30 @@ int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time,
     if (B == 0) return TICTAC_OK;
     if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
     TacArgs a{B, op_time, recv_time, order, rank, sel_P, sel_Mplus, true, makespan, eff, U, L, S};
+    a.f32 = f32;
     HIP_TRY(launch_tac(*d, a, (hipStream_t)stream));
     return TICTAC_OK;
 }
 
-int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
-                    const double *op_time, const double *recv_time, double *makespan, double *eff, double *U,
-                    double *L, double *S, tictac_stream stream)
+int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                        int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, double *makespan,
+                        double *eff, double *U, double *L, double *S, tictac_stream stream)
+{
+    return tac_simulate_any(dag, B, op_time, recv_time, false, order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S,
+                            stream);
+}
+
+int tictac_tac_simulate_f32(const tictac_dag *dag, int32_t B, const float *op_time, const float *recv_time,
+                            int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus, double *makespan,
+                            double *eff, double *U, double *L, double *S, tictac_stream stream)
+{
+    return tac_simulate_any(dag, B, op_time, recv_time, true, order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S,
+                            stream);
+}
+
+static int simulate_any(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                        const void *op_time, const void *recv_time, bool f32, double *makespan, double *eff, double *U,
+                        double *L, double *S, tictac_stream stream)
 {
     if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
     Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
@@ -627,8 +644,23 @@ int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int3
     if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
     if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
     SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
+    a.f32 = f32;
     HIP_TRY(launch_simulate(*d, a, (hipStream_t)stream));
     return TICTAC_OK;
+}
+
+int tictac_simulate(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                    const double *op_time, const double *recv_time, double *makespan, double *eff, double *U,
+                    double *L, double *S, tictac_stream stream)
+{
+    return simulate_any(dag, B, order, order_stride, op_time, recv_time, false, makespan, eff, U, L, S, stream);
+}
+
+int tictac_simulate_f32(const tictac_dag *dag, int32_t B, const int32_t *order, int32_t order_stride,
+                        const float *op_time, const float *recv_time, double *makespan, double *eff, double *U,
+                        double *L, double *S, tictac_stream stream)
+{
+    return simulate_any(dag, B, order, order_stride, op_time, recv_time, true, makespan, eff, U, L, S, stream);
 }
 
 int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channels, const int32_t *channel_of_recv,

@@ -129,24 +129,67 @@ __device__ __forceinline__ int wave_max_i32_dpp(int v)
 }
 #undef TT_DPP_SCAN
 
+// A row of a timing array that is stored as float64 or as float32.  A float32 value is converted
+// when it is loaded; every sum and comparison is float64.
+struct TimeRow {
+    const void *p;
+    bool f32;
+    __device__ __forceinline__ double operator[](int j) const
+    {
+        return f32 ? (double)static_cast<const float *>(p)[j] : static_cast<const double *>(p)[j];
+    }
+    __device__ __forceinline__ const float *as_f32() const { return static_cast<const float *>(p); }
+    __device__ __forceinline__ const double *as_f64() const { return static_cast<const double *>(p); }
+};
+__device__ __forceinline__ TimeRow time_row(const void *base, size_t first, bool f32)
+{
+    return TimeRow{f32 ? static_cast<const void *>(static_cast<const float *>(base) + first)
+                       : static_cast<const void *>(static_cast<const double *>(base) + first), f32};
+}
+
+// Four consecutive elements with one load (two for float64).  Rows start at any element, so the
+// vector types carry the alignment of one element; the class table is read the same way.
+typedef float tt_f32x4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef double tt_f64x2 __attribute__((ext_vector_type(2), aligned(8)));
+typedef int tt_i32x4 __attribute__((ext_vector_type(4), aligned(4)));
+
+__device__ __forceinline__ void load4(const double *__restrict__ q, double (&x)[4])
+{
+    const tt_f64x2 a = *reinterpret_cast<const tt_f64x2 *>(q), b = *reinterpret_cast<const tt_f64x2 *>(q + 2);
+    x[0] = a.x; x[1] = a.y; x[2] = b.x; x[3] = b.y;
+}
+__device__ __forceinline__ void load4(const float *__restrict__ q, double (&x)[4])
+{
+    const tt_f32x4 a = *reinterpret_cast<const tt_f32x4 *>(q);
+    x[0] = (double)a.x; x[1] = (double)a.y; x[2] = (double)a.z; x[3] = (double)a.w;
+}
+
 // totals[cls_of[j]] += row[j] for j in [0, N), totals in LDS, by one wave.  A lane takes four
 // consecutive columns at a time and first adds up runs of equal class in registers: columns of
 // one class tend to sit next to each other, and every LDS add of several lanes to one address
 // is served one lane after the other.
-__device__ __forceinline__ void class_totals(double *totals, const double *__restrict__ row,
+template <typename T>
+__device__ __forceinline__ void class_totals(double *totals, const T *__restrict__ row,
                                              const int32_t *__restrict__ cls_of, int N, int lane)
 {
     for (int j0 = lane * 4; j0 < N; j0 += 64 * 4 * 2) {          // two groups of four in flight per lane
         double x[2][4];
         int c[2][4];
 #pragma unroll
-        for (int g = 0; g < 2; ++g)
+        for (int g = 0; g < 2; ++g) {
+            const int j = j0 + g * 256;
+            if (j + 3 < N) {
+                load4(row + j, x[g]);
+                const tt_i32x4 q = *reinterpret_cast<const tt_i32x4 *>(cls_of + j);
+                c[g][0] = q.x; c[g][1] = q.y; c[g][2] = q.z; c[g][3] = q.w;
+            } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int j = j0 + g * 256 + i;
-                x[g][i] = j < N ? row[j] : 0.0;
-                c[g][i] = j < N ? cls_of[j] : -1;
+                for (int i = 0; i < 4; ++i) {
+                    x[g][i] = j + i < N ? (double)row[j + i] : 0.0;
+                    c[g][i] = j + i < N ? cls_of[j + i] : -1;
+                }
             }
+        }
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             double acc = x[g][0];
@@ -164,6 +207,13 @@ __device__ __forceinline__ void class_totals(double *totals, const double *__res
             if (cur >= 0) atomicAdd(&totals[cur], acc);
         }
     }
+}
+
+__device__ __forceinline__ void class_totals(double *totals, const TimeRow &row, const int32_t *__restrict__ cls_of,
+                                             int N, int lane)
+{
+    if (row.f32) class_totals(totals, row.as_f32(), cls_of, N, lane);
+    else class_totals(totals, row.as_f64(), cls_of, N, lane);
 }
 
 __device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t x)

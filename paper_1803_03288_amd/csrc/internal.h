@@ -103,12 +103,13 @@ hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank
 
 struct TacArgs {
     int32_t B;
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set (converted on load; the arithmetic is float64)
     int32_t *order, *rank;
     double *sel_P, *sel_Mplus;
     // fused simulation outputs; all NULL = TAC only
     bool simulate;
     double *makespan, *eff, *U, *L, *S;
+    bool f32 = false;
 };
 hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s);
 // register-resident variant for graphs with few classes; returns hipErrorNotSupported when
@@ -120,8 +121,9 @@ struct SimArgs {
     int32_t B;
     const int32_t *order;
     int32_t order_stride;
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
     double *makespan, *eff, *U, *L, *S;
+    bool f32 = false;
 };
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
 hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s);

@@ -37,7 +37,8 @@ struct TacKernelParams {
     const int32_t *cls_cnt0;    // [C]
     const int32_t *cls_ptr;     // [C+1]
     const int32_t *cls_cols;    // [N]
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
+    int32_t f32;
     int32_t *order, *rank;
     double *sel_P, *sel_Mplus;
     int32_t simulate;
@@ -100,8 +101,8 @@ tac_kernel(const TacKernelParams p)
 
     for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
         if (p.only_flagged && p.only_flagged[b] == 0) continue;   // uniform over the workgroup
-        const double *rt = p.recv_time + (size_t)b * R;
-        const double *ot = p.op_time + (size_t)b * N;
+        const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
+        const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         __syncthreads();   // previous sample's LDS fully consumed
 
         // ---- per-sample init ----
@@ -375,13 +376,14 @@ hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s)
         // nothing to order; the iteration is the compute ops back to back
         if (!a.simulate) return hipSuccess;
         SimArgs sa{a.B, nullptr, 0, a.op_time, a.recv_time, a.makespan, a.eff, a.U, a.L, a.S};
+        sa.f32 = a.f32;
         return launch_simulate(d, sa, s);
     }
     TacKernelParams p{};
     p.B = a.B; p.R = d.R; p.W = d.W; p.C = d.C; p.Cpad = d.Cpad; p.N = d.N;
     p.cls_dep = d.d_cls_dep; p.cls_depT = d.d_cls_depT; p.cls_cnt0 = d.d_cls_cnt0;
     p.cls_ptr = d.d_cls_ptr; p.cls_cols = d.d_cls_cols;
-    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.op_time = a.op_time; p.recv_time = a.recv_time; p.f32 = a.f32 ? 1 : 0;
     p.order = a.order; p.rank = a.rank; p.sel_P = a.sel_P; p.sel_Mplus = a.sel_Mplus;
     p.simulate = a.simulate ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;

@@ -51,7 +51,8 @@ struct TacRegParams {
     const int32_t *col_cls;     // [N]   class of every op_time column; NULL: gather by member lists
     const int32_t *run_ptr;     // [C+1]
     const int32_t *run_lo, *run_hi;
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
+    int32_t f32;
     int32_t *order, *rank;
     int32_t simulate;
     double *makespan, *eff, *U, *L, *S;
@@ -127,8 +128,8 @@ tac_reg_kernel(const TacRegParams p)
 
     const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
-        const double *rt = p.recv_time + (size_t)b * R;
-        const double *ot = p.op_time + (size_t)b * N;
+        const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
+        const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         wave_sync();                        // LDS of the previous sample is no longer read
 
         // ---- a. transfer times ----
@@ -559,7 +560,7 @@ hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t 
     p.cls_dep = d.d_cls_dep; p.cls_cnt0 = d.d_cls_cnt0; p.cls_isum = d.d_cls_isum;
     p.cls_ptr = d.d_cls_ptr; p.cls_cols = d.d_cls_cols;
     p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;
-    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.op_time = a.op_time; p.recv_time = a.recv_time; p.f32 = a.f32 ? 1 : 0;
     p.order = a.order; p.rank = a.rank;
     p.simulate = a.simulate ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;

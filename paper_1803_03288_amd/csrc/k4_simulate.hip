@@ -23,7 +23,8 @@ struct SimKernelParams {
     const int32_t *order;       // [R] or [B][R]
     int32_t order_stride;
     const int32_t *kappa;       // [C] for a shared order, else NULL
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
+    int32_t f32;
     double *makespan, *eff, *U, *L, *S;
 };
 
@@ -67,8 +68,8 @@ simulate_kernel(const SimKernelParams p)
     int32_t *pos = reinterpret_cast<int32_t *>(red + 16);   // [R] 1-based position of recv r
 
     for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
-        const double *rt = p.recv_time + (size_t)b * R;
-        const double *ot = p.op_time + (size_t)b * N;
+        const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
+        const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
         __syncthreads();
         for (int k = tid; k < R; k += BS) {
@@ -142,7 +143,8 @@ struct SimWaveParams {
     const int32_t *order;
     int32_t order_stride;
     const int32_t *kappa;       // [C] for a shared order, else NULL
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
+    int32_t f32;
     double *makespan, *eff, *U, *L, *S;
 };
 
@@ -166,8 +168,8 @@ simulate_wave_kernel(const SimWaveParams p)
 
     const int gwave = blockIdx.x * kSimWaves + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
-        const double *rt = p.recv_time + (size_t)b * R;
-        const double *ot = p.op_time + (size_t)b * N;
+        const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
+        const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
         wave_sync();                        // LDS of the previous sample is no longer read
 
@@ -303,7 +305,7 @@ static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N;
     p.col_cls = d.d_col_cls; p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;
     p.order = a.order; p.order_stride = a.order_stride; p.kappa = kappa;
-    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.op_time = a.op_time; p.recv_time = a.recv_time; p.f32 = a.f32 ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
     if (K <= 1) return launch_sim_wave<1>(p, d, s);
     if (K <= 2) return launch_sim_wave<2>(p, d, s);
@@ -342,7 +344,8 @@ struct SimChanParams {
     const int32_t *chan;        // [R] channel of every recv, 0 <= chan < n_channels <= 64
     const int32_t *order;
     int32_t order_stride;
-    const double *op_time, *recv_time;
+    const void *op_time, *recv_time;    // float64, or float32 when f32 is set
+    int32_t f32;
     double *makespan, *eff, *U, *L, *S;
 };
 
@@ -362,8 +365,8 @@ simulate_channels_kernel(const SimChanParams p)
 
     const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
-        const double *rt = p.recv_time + (size_t)b * R;
-        const double *ot = p.op_time + (size_t)b * N;
+        const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
+        const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
         wave_sync();
 
@@ -499,7 +502,7 @@ hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N; p.n_channels = n_channels;
     p.col_cls = d.d_col_cls; p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;
     p.chan = chan; p.order = a.order; p.order_stride = a.order_stride;
-    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.op_time = a.op_time; p.recv_time = a.recv_time; p.f32 = a.f32 ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
     switch (KT) {
     case 1: return launch_sim_chan<1>(p, d, s);
@@ -598,7 +601,7 @@ hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
     p.B = a.B; p.R = d.R; p.W = d.W; p.C = d.C; p.N = d.N;
     p.cls_dep = d.d_cls_dep; p.cls_ptr = d.d_cls_ptr; p.cls_cols = d.d_cls_cols;
     p.order = a.order; p.order_stride = a.order_stride; p.kappa = nullptr;
-    p.op_time = a.op_time; p.recv_time = a.recv_time;
+    p.op_time = a.op_time; p.recv_time = a.recv_time; p.f32 = a.f32 ? 1 : 0;
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
     if (a.order_stride == 0 && d.R > 0 && d.C > 0) {
         hipError_t e = ensure_workspace(&d, ((size_t)d.R + d.C) * sizeof(int32_t));

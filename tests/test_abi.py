@@ -24,7 +24,7 @@ def L():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "tictac.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tictac_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(tictac_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(L):
@@ -88,6 +88,11 @@ def test_null_handle_is_rejected(L):
     assert L.tictac_straggler_effect(ctypes.c_int32(-1), ctypes.c_int32(2), None, None, None) == -9
     assert L.tictac_straggler_effect(ctypes.c_int32(8), ctypes.c_int32(2), None, None, None) == -1
     assert L.tictac_straggler_effect(ctypes.c_int32(3), ctypes.c_int32(4), None, None, None) == 0     # no whole group
+    # float32 timing arrays: no handle
+    assert L.tictac_simulate_f32(None, ctypes.c_int32(1), None, ctypes.c_int32(0), None, None, None, None, None, None,
+                                 None, None) == -1
+    assert L.tictac_tac_simulate_f32(None, ctypes.c_int32(1), None, None, None, None, None, None, None, None, None,
+                                     None, None, None) == -1
     # order search: no handle
     assert L.tictac_order_search(None, ctypes.c_int32(1), None, ctypes.c_int32(0), ctypes.c_int32(0), None, None, None,
                                  None, None, None, None, None) == -1

@@ -435,6 +435,47 @@ def test_order_search_limits(tt):
     assert got[0].shape == (0, 2)
 
 
+@pytest.mark.parametrize("name,k", [("tiny", 256), ("resnet50", 48), ("vgg16", 512), ("inception3", 4), ("layered70", 64),
+                                    ("jobs", 64), ("toy", 16), ("single", 8), ("funnel", 16), ("r129", 32)])
+def test_float32_timing_arrays(tt, name, k):
+    """tictac_tac_simulate_f32 and tictac_simulate_f32: the timing samples stored as float32.  The
+    oracle is given the same rounded values (as float64), so orders must be bit-exact and, the
+    rounded preset times still being multiples of 2**-30 s, so must every float64 output; against
+    the unrounded float64 samples the makespans agree within the float32 bound of 1e-3 relative.
+    Includes samples with zero transfer times (the general TAC kernel) and per-sample orders."""
+    makers = dict(SMALL)
+    makers.update(EXTRA)
+    d, h, dep = get(tt, name, makers.get(name))
+    R = d.n_recv
+    B = min(k, d.batch)
+    op, rv = wl.timing_samples(d, 0, B)
+    rng = np.random.default_rng(41)
+    rv = rv.copy()
+    rv[rng.random(rv.shape) < 0.02] = 0.0                      # a few zero-length transfers
+    op32, rv32 = op.astype(np.float32), rv.astype(np.float32)
+    op64, rv64 = op32.astype(np.float64), rv32.astype(np.float64)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    eo, er, eP, eM = oracle.tac(dep, d.recv_ids, op64, rv64)
+    exp = oracle.simulate(*args, eo, op64, rv64)
+    got = tt.tac_simulate(h, cuda(op32), cuda(rv32), want_rank=True, want_sel=True)
+    assert np.array_equal(got[0].cpu().numpy(), eo) and np.array_equal(got[1].cpu().numpy(), er)
+    assert np.array_equal(got[2].cpu().numpy(), eP)
+    gM = got[3].cpu().numpy()
+    assert np.array_equal(np.isinf(gM), np.isinf(eM)) and np.array_equal(gM[np.isfinite(eM)], eM[np.isfinite(eM)])
+    for a, b, nm in zip(got[4:], exp, "m E U L S".split()):
+        assert np.array_equal(a.cpu().numpy(), b), f"{name}: fused {nm}"
+    # the same samples unrounded: within the float32 bound
+    ref = tt.simulate(h, got[0], cuda(op), cuda(rv))[0].cpu().numpy()
+    assert np.allclose(got[4].cpu().numpy(), ref, rtol=1e-3, atol=0.0)
+    # simulate alone: per-sample random orders and one shared order
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    for o in (orders, orders[0]):
+        exp = oracle.simulate(*args, o, op64, rv64)
+        got = tt.simulate(h, cuda(o), cuda(op32), cuda(rv32))
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: simulate {nm}"
+
+
 def test_time_oracle_min(tt):
     """Minimum over measured runs, element by element against the oracle: even and odd lengths
     (two-element and one-element loads), one run, many runs, a batch of timing rows."""
