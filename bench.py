@@ -53,7 +53,7 @@ def parse() -> argparse.Namespace:
 # HBM bytes per launch of the fused TAC + simulation kernel, FETCH_SIZE + WRITE_SIZE of the two
 # counter runs summarised in profiles/bench_resnet50_hbm_counters.md (scaled by the copy probe).
 # Only valid for the kernel and workload those runs measured; None otherwise.
-TAC_TRAFFIC_BYTES = {("resnet50", 65536): 696.82e6 + 89.74e6}
+TAC_TRAFFIC_BYTES = {("resnet50", 65536): 730.35e6 + 94.49e6}
 
 # peaks of MI355X used for the roofline records
 HBM_PEAK_GBS = 8000.0
