@@ -58,6 +58,8 @@ SMALL = {
     "relabel": lambda: wl.relabel(wl.layered_dag(12, levels=8, width=6, fan_in=(1, 3), back=2, n_recv=40,
                                                  attach=(1, 4)), 5)[0],
     "chain": lambda: wl.chain_dag(33),
+    # the largest graph the wave-per-sample kernels take: 512 recvs, 512 classes (eight per lane)
+    "chain512": lambda: wl.chain_dag(512, name="chain512"),
     "jobs": lambda: wl.independent_jobs_dag(9),
     "funnel": lambda: wl.funnel_dag(6, 9),
     "toy": wl.toy_dag,
@@ -185,7 +187,7 @@ def test_tac_and_simulate_presets(tt, name, k):
     run_tac_sim_parity(tt, d, h, dep, op, rv, name)
 
 
-@pytest.mark.parametrize("name", ["layered70", "relabel", "chain", "jobs", "funnel", "toy", "case2", "single",
+@pytest.mark.parametrize("name", ["layered70", "relabel", "chain", "chain512", "jobs", "funnel", "toy", "case2", "single",
                                   "mini_stress"])
 def test_tac_and_simulate_small_graphs(tt, name):
     d, h, dep = get(tt, name, SMALL[name])
@@ -291,8 +293,8 @@ def test_random_order_baseline_and_straggler_effect(tt):
         assert np.array_equal(tt.straggler_effect(big, w).cpu().numpy(), oracle.straggler(big.cpu().numpy(), w))
 
 
-@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "single", "r64", "r129", "resnet50",
-                                  "inception3"])
+@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "single", "r64", "r129", "chain512",
+                                  "resnet50", "inception3"])
 def test_several_channels(tt, name):
     """tictac_simulate_channels against the oracle: 1, 2, 3, 4 and 64 channels (and a channel per
     recv where there are at most 64), random and round-robin assignments, per-sample and
@@ -302,7 +304,7 @@ def test_several_channels(tt, name):
     makers["r129"] = lambda: wl.layered_dag(159, levels=7, width=9, fan_in=(1, 3), back=2, n_recv=129, attach=(1, 3))
     d, h, dep = get(tt, name, makers.get(name))
     R = d.n_recv
-    B = {"resnet50": 24, "inception3": 4}.get(name, 37)
+    B = {"resnet50": 24, "inception3": 4, "chain512": 9}.get(name, 37)
     op, rv = wl.timing_samples(d, 0, B)
     rng = np.random.default_rng(17)
     orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
@@ -367,8 +369,8 @@ EXTRA = {
 }
 
 
-@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "case2", "single", "chain", "r64",
-                                  "r129", "resnet50", "vgg16", "inception3"])
+@pytest.mark.parametrize("name", ["tiny", "layered70", "jobs", "funnel", "toy", "case2", "single", "chain", "chain512",
+                                  "r64", "r129", "resnet50", "vgg16", "inception3"])
 def test_order_search(tt, name):
     """tictac_order_search against the oracle: the orders the samples end with, both makespans
     and the number of kept exchanges, from random start orders per sample and from the TIC
@@ -378,7 +380,7 @@ def test_order_search(tt, name):
     makers.update(EXTRA)
     d, h, dep = get(tt, name, makers.get(name))
     R = d.n_recv
-    B, n_moves = {"resnet50": (10, 48), "vgg16": (40, 48), "inception3": (3, 24)}.get(name, (37, 150))
+    B, n_moves = {"resnet50": (10, 48), "vgg16": (40, 48), "inception3": (3, 24), "chain512": (9, 80)}.get(name, (37, 150))
     print(f"[order_search] {name}: R={R} B={B} moves={n_moves}", flush=True)
     op, rv = wl.timing_samples(d, 0, B)
     rng = np.random.default_rng(29)
@@ -420,6 +422,20 @@ def test_order_search_limits(tt):
                         torch.zeros((1, ds.n_compute), dtype=torch.float64, device="cuda"),
                         torch.zeros((1, ds.n_recv), dtype=torch.float64, device="cuda"))
     assert e.value.code == -9
+    # one recv more than the kernel takes; the single-channel simulation still serves such a graph
+    d513, h513, _ = get(tt, "chain513", lambda: wl.chain_dag(513, name="chain513"))
+    op513, rv513 = wl.timing_samples(d513, 0, 3)
+    o513 = torch.arange(513, dtype=torch.int32, device="cuda")
+    with pytest.raises(TicTacError) as e:
+        tt.order_search(h513, o513, mv, cuda(op513), cuda(rv513))
+    assert e.value.code == -9
+    with pytest.raises(TicTacError) as e:
+        tt.simulate_channels(h513, 2, np.zeros(513, np.int32), o513, cuda(op513), cuda(rv513))
+    assert e.value.code == -9
+    exp = oracle.simulate(d513.n_ops, d513.row_ptr, d513.col_idx, d513.recv_ids, np.arange(513, dtype=np.int32), op513, rv513)
+    got = tt.simulate(h513, o513, cuda(op513), cuda(rv513))
+    for a, b in zip(got, exp):
+        assert np.array_equal(a.cpu().numpy(), b)
     dn = wl.no_recv_dag(17)
     hn = tt.build_deps(dn.n_ops, dn.row_ptr, dn.col_idx, dn.recv_ids)
     with pytest.raises(TicTacError) as e:
@@ -436,7 +452,7 @@ def test_order_search_limits(tt):
 
 
 @pytest.mark.parametrize("name,k", [("tiny", 256), ("resnet50", 48), ("vgg16", 512), ("inception3", 4), ("layered70", 64),
-                                    ("jobs", 64), ("toy", 16), ("single", 8), ("funnel", 16), ("r129", 32)])
+                                    ("jobs", 64), ("toy", 16), ("single", 8), ("funnel", 16), ("r129", 32), ("chain512", 6)])
 def test_float32_timing_arrays(tt, name, k):
     """tictac_tac_simulate_f32 and tictac_simulate_f32: the timing samples stored as float32.  The
     oracle is given the same rounded values (as float64), so orders must be bit-exact and, the
