@@ -269,7 +269,7 @@ static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
     size_t wave_bytes = ((size_t)3 * d.R + 1) * 8 + (size_t)levels * d.R * 2;
     wave_bytes = (wave_bytes + 15) & ~(size_t)15;
     const size_t lds = wave_bytes * kSimWaves;
-    if (lds > 64 * 1024) return hipErrorNotSupported;
+    if (lds > 150 * 1024) return hipErrorNotSupported;     // 160 KB of LDS per compute unit
     p.wave_bytes = (int32_t)wave_bytes;
     hipError_t e;
     if (lds > 48 * 1024) {
