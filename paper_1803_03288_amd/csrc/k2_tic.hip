@@ -79,20 +79,40 @@ tic_rank_kernel(int32_t R, const int32_t *__restrict__ prio, int32_t *order, int
 
 // Small graphs in one launch of one workgroup: thread i owns recv i, takes the minimum of
 // |dep| over the classes (compute ops with identical rows) whose row holds i, and ranks
-// itself by counting.  depT is the transposed class table [W][Cpad].
+// itself by counting.  depT is the transposed class table [W][Cpad].  When the table and the
+// class sizes fit (lds_words > 0: W * Cpad words, then C counts), the workgroup first copies them
+// to LDS with all its threads, so that the loop over the classes does not wait on memory.
 __global__ void __launch_bounds__(1024)
-tic_small_kernel(int32_t R, int32_t C, int32_t Cpad, const uint64_t *__restrict__ depT,
+tic_small_kernel(int32_t R, int32_t C, int32_t Cpad, int32_t lds_words, const uint64_t *__restrict__ depT,
                  const int32_t *__restrict__ cnt0, int32_t *prio, int32_t *order, int32_t *rank)
 {
+    extern __shared__ uint64_t tic_table[];         // [lds_words] depT, then [C] counts
     __shared__ int32_t tile[1024];
     const int32_t i = threadIdx.x;
+    if (lds_words > 0) {
+        int32_t *cnt_l = reinterpret_cast<int32_t *>(tic_table + lds_words);
+        for (int32_t x = i; x < lds_words; x += blockDim.x) tic_table[x] = depT[x];
+        for (int32_t c = i; c < C; c += blockDim.x) cnt_l[c] = cnt0[c];
+        __syncthreads();
+    }
     int32_t m = TICTAC_PRIO_INF;
     if (i < R) {
-        const uint64_t *col = depT + (size_t)(i >> 6) * Cpad;   // the same word for the 64 lanes of a wave
         const int sh = i & 63;
-        for (int32_t c = 0; c < C; ++c) {
-            const int32_t k = cnt0[c];
-            if (((col[c] >> sh) & 1ull) && k > 1) m = min(m, k);
+        if (lds_words > 0) {
+            const uint64_t *col = tic_table + (size_t)(i >> 6) * Cpad;
+            const int32_t *cnt_l = reinterpret_cast<const int32_t *>(tic_table + lds_words);
+#pragma unroll 4
+            for (int32_t c = 0; c < C; ++c) {
+                const int32_t k = cnt_l[c];
+                if (((col[c] >> sh) & 1ull) && k > 1) m = min(m, k);
+            }
+        } else {
+            const uint64_t *col = depT + (size_t)(i >> 6) * Cpad;   // the same word for the 64 lanes of a wave
+#pragma unroll 8
+            for (int32_t c = 0; c < C; ++c) {
+                const int32_t k = cnt0[c];
+                if (((col[c] >> sh) & 1ull) && k > 1) m = min(m, k);
+            }
         }
         prio[i] = m;
     }
@@ -114,9 +134,13 @@ hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank
     const int32_t R = d.R;
     if (R == 0) return hipSuccess;
     if (R <= 1024 && d.C <= 8192 && d.d_cls_depT && d.d_cls_cnt0) {
-        const int threads = (R + 63) / 64 * 64;
-        hipLaunchKernelGGL(tic_small_kernel, dim3(1), dim3(threads), 0, s, R, d.C, d.Cpad, d.d_cls_depT,
-                           d.d_cls_cnt0, prio, order, rank);
+        int threads = (R + 63) / 64 * 64;
+        const size_t words = (size_t)d.W * d.Cpad;
+        const size_t lds = words * 8 + (size_t)d.C * 4;
+        const bool in_lds = lds <= 40 * 1024;
+        if (in_lds && threads < 256) threads = 256;     // more threads for the copy
+        hipLaunchKernelGGL(tic_small_kernel, dim3(1), dim3(threads), in_lds ? lds : 0, s, R, d.C, d.Cpad,
+                           in_lds ? (int32_t)words : 0, d.d_cls_depT, d.d_cls_cnt0, prio, order, rank);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(fill_i32, dim3((R + 255) / 256), dim3(256), 0, s, prio, R, (int32_t)TICTAC_PRIO_INF);
