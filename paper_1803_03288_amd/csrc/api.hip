@@ -440,16 +440,29 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     std::vector<int32_t> cnt0(d->C, 0);
     std::vector<uint64_t> depT((size_t)d->W * d->Cpad, 0);
     d->cls_nnz = 0;
-    for (int32_t c = 0; c < d->C; ++c)
+    // (the transpose in blocks of 16 classes: the block of rows stays in cache and every word row
+    // of depT receives 128 consecutive bytes at a time)
+    for (int32_t c0 = 0; c0 < d->C; c0 += 16) {
+        const int32_t c1 = std::min(d->C, c0 + 16);
         for (int32_t w = 0; w < d->W; ++w) {
-            uint64_t x = cls_dep[(size_t)c * d->W + w];
-            cnt0[c] += __builtin_popcountll(x);
-            depT[(size_t)w * d->Cpad + c] = x;
+            uint64_t *dst = &depT[(size_t)w * d->Cpad];
+            for (int32_t c = c0; c < c1; ++c) {
+                const uint64_t x = cls_dep[(size_t)c * d->W + w];
+                cnt0[c] += __builtin_popcountll(x);
+                dst[c] = x;
+            }
         }
+    }
     for (int32_t c = 0; c < d->C; ++c) d->cls_nnz += cnt0[c];
     // runs [lo, hi) of consecutive recv indices of every class row, and the sum of its indices
-    std::vector<int32_t> run_ptr(1, 0), run_lo, run_hi, isum(d->C, 0);
-    for (int32_t c = 0; c < d->C; ++c) {
+    // (only the kernels for graphs with at most 1 024 recvs and 512 classes use them)
+    const bool want_runs = d->R <= 1024 && d->C <= 512;
+    std::vector<int32_t> run_ptr, run_lo, run_hi, isum;
+    if (want_runs) {
+        run_ptr.assign(1, 0);
+        isum.assign(d->C, 0);
+    }
+    for (int32_t c = 0; want_runs && c < d->C; ++c) {
         const uint64_t *row = &cls_dep[(size_t)c * d->W];
         int32_t i = 0;
         int64_t sum = 0;
@@ -474,7 +487,10 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         isum[c] = (int32_t)sum;
     }
     Packer cls;
-    if (d->R <= 1024) cls.add(&d->d_cls_isum, isum);   // index sums stay below 2^20
+    cls.host.reserve((cls_dep.size() + depT.size()) * 8 +
+                     (isum.size() + run_ptr.size() + 2 * run_lo.size() + cnt0.size() + cls_ptr.size() + cls_cols.size() +
+                      (size_t)d->N) * 4 + 16 * 256);
+    cls.add(&d->d_cls_isum, isum);      // index sums stay below 2^20 (nothing when the runs are not built)
     d->max_members = 0;
     for (int32_t c = 0; c < d->C; ++c) d->max_members = std::max(d->max_members, cls_ptr[c + 1] - cls_ptr[c]);
     cls.add(&d->d_run_ptr, run_ptr);

@@ -553,7 +553,7 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
 
 hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t s)
 {
-    if (d.R == 0 || d.R > 1024 || d.C > 8 * 64 || a.sel_P || a.sel_Mplus || !d.d_cls_isum)
+    if (d.R == 0 || d.R > 1024 || d.C > 8 * 64 || a.sel_P || a.sel_Mplus || !d.d_cls_isum || !d.d_run_ptr)
         return hipErrorNotSupported;
     TacRegParams p{};
     p.B = a.B; p.R = d.R; p.W = d.W; p.C = d.C; p.N = d.N;

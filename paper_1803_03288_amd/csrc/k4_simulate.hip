@@ -299,7 +299,7 @@ static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_
     const int K = (d.C + 63) / 64;
     const int KT = K <= 4 ? K : (K <= 6 ? 6 : 8);     // the instantiation that is launched below
     // (the class totals are summed in the space of F and A: one double per class slot must fit)
-    if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || (size_t)64 * KT > 2 * (size_t)d.R + 1)
+    if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || !d.d_run_ptr || (size_t)64 * KT > 2 * (size_t)d.R + 1)
         return hipErrorNotSupported;
     SimWaveParams p{};
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N;
@@ -497,7 +497,7 @@ hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels
     if (a.B == 0) return hipSuccess;
     const int K = (d.C + 63) / 64;
     const int KT = K <= 4 ? (K < 1 ? 1 : K) : (K <= 6 ? 6 : 8);
-    if (d.R == 0 || d.R > 512 || K > 8 || n_channels > 64 || (d.C > 0 && !d.d_col_cls)) return hipErrorNotSupported;
+    if (d.R == 0 || d.R > 512 || K > 8 || n_channels > 64 || (d.C > 0 && (!d.d_col_cls || !d.d_run_ptr))) return hipErrorNotSupported;
     SimChanParams p{};
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N; p.n_channels = n_channels;
     p.col_cls = d.d_col_cls; p.run_ptr = d.d_run_ptr; p.run_lo = d.d_run_lo; p.run_hi = d.d_run_hi;

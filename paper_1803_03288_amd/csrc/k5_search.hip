@@ -342,7 +342,7 @@ hipError_t launch_order_search(Dag &d, const SearchArgs &a, hipStream_t s)
 {
     const int KC = (d.C + 63) / 64, KR = (d.R + 63) / 64;
     const int K = KC > KR ? KC : KR;
-    if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || !d.d_cls_dep) return hipErrorNotSupported;
+    if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || !d.d_cls_dep || !d.d_run_ptr) return hipErrorNotSupported;
     SearchParams p{};
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N; p.W = d.W; p.n_moves = a.n_moves;
     p.col_cls = d.d_col_cls; p.cls_dep = d.d_cls_dep;
