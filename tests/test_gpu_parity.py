@@ -3,6 +3,8 @@ seeded inputs.  Integer outputs (bitsets, TIC priorities, orders, ranks) must be
 bit-exact; float64 outputs within 1e-5 relative (they are in fact exact on the presets,
 whose times are multiples of 2**-30 s)."""
 
+import os
+
 import numpy as np
 import pytest
 
@@ -224,7 +226,40 @@ def test_word_boundaries_and_ragged_batches(tt, n_recv):
         run_tac_sim_parity(tt, d, h, dep, op, rv, f"{name}/B{B}")
 
 
-@pytest.mark.parametrize("seed", range(16))
+def run_other_calls_parity(tt, d, h, dep, op, rv, rng, tag):
+    """Order search, several channels and float32 storage against the oracle on one graph."""
+    R, B = d.n_recv, rv.shape[0]
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    gop, grv = cuda(op), cuda(rv)
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    gord = cuda(orders)
+    if R <= 512 and h.n_classes <= 512:
+        moves = rng.integers(0, R, size=(60, 2)).astype(np.int32)
+        exp = oracle.order_search(*args, orders, moves, op, rv)
+        got = tt.order_search(h, gord, cuda(moves), gop, grv)
+        for a, b, nm in zip(got, exp, ("best_order", "best_makespan", "start_makespan", "n_accepted")):
+            assert np.array_equal(a.cpu().numpy(), b), f"{tag}: search {nm}"
+        n_ch = int(rng.integers(1, 6))
+        chan = rng.integers(0, n_ch, size=R).astype(np.int32)
+        exp = oracle.simulate_channels(*args, n_ch, chan, orders, op, rv)
+        got = tt.simulate_channels(h, n_ch, chan, gord, gop, grv)
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            assert np.array_equal(a.cpu().numpy(), b), f"{tag}: {n_ch} channels {nm}"
+    op32, rv32 = op.astype(np.float32), rv.astype(np.float32)
+    op64, rv64 = op32.astype(np.float64), rv32.astype(np.float64)
+    eo = oracle.tac(dep, d.recv_ids, op64, rv64)[0]
+    exp = oracle.simulate(*args, eo, op64, rv64)
+    got = tt.tac_simulate(h, cuda(op32), cuda(rv32))
+    assert np.array_equal(got[0].cpu().numpy(), eo), f"{tag}: float32 order"
+    for a, b, nm in zip(got[4:], exp, "m E U L S".split()):
+        assert np.array_equal(a.cpu().numpy(), b), f"{tag}: float32 fused {nm}"
+    exp = oracle.simulate(*args, orders, op64, rv64)
+    got = tt.simulate(h, gord, cuda(op32), cuda(rv32))
+    for a, b, nm in zip(got, exp, "m E U L S".split()):
+        assert np.array_equal(a.cpu().numpy(), b), f"{tag}: float32 simulate {nm}"
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("TICTAC_TEST_SEEDS", "32"))))
 def test_random_graphs(tt, seed):
     """Seeded random layered graphs of varied shape (1 to 200 recvs, shallow and deep, sparse and
     dense attachment), each with ordinary samples and with samples drawn from three values
@@ -245,6 +280,8 @@ def test_random_graphs(tt, seed):
     op3 = rng.integers(0, 3, size=(B, d.n_compute)).astype(np.float64) * 0.5
     rv3 = rng.integers(1, 3, size=(B, R)).astype(np.float64) * 0.5
     run_tac_sim_parity(tt, d, h, dep, op3, rv3, f"random{seed}/ties")
+    run_other_calls_parity(tt, d, h, dep, op, rv, rng, f"random{seed}")
+    run_other_calls_parity(tt, d, h, dep, op3, rv3, rng, f"random{seed}/ties")
     h.close()
 
 
