@@ -10,6 +10,8 @@
 //     busy_0 = A_0,   busy_k = max(busy_{k-1}, F_k) + A_k,
 // A_k = total time of the classes with kappa = k, whatever ready op it picks first
 // (a predecessor of a released op was released no later).  makespan = max(busy_R, F_R).
+#include <algorithm>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -127,10 +129,11 @@ simulate_kernel(const SimKernelParams p)
 }
 
 // The same computation with one wavefront per sample, for graphs with at most 8 classes per
-// lane and at most 512 recvs.  Lane l owns the classes l, l + 64, ...; a workgroup is four
-// independent waves.  Per sample: the transfer times and the order are read coalesced; the
-// op_time row is read once, coalesced, every column adding itself to the total of its class
-// in LDS; kappa of a class is the maximum of the positions of its recvs, taken run by run of
+// lane and at most 512 recvs.  Lane l owns the classes l, l + 64, ... and the positions l,
+// l + 64, ... of the order; a workgroup is four independent waves.  Per sample: the transfer
+// times and the order are requested first, into registers, then the op_time row is read once,
+// coalesced, every run of columns of one class adding itself to the total of its class in LDS
+// (so one trip to memory per sample is waited for, not three); kappa of a class is the maximum of the positions of its recvs, taken run by run of
 // consecutive recv indices from a sparse table of range maxima over the position array (or read
 // from a table when all samples share one order); then A by kappa, and
 //     makespan = max over k of F_k + (A_k + ... + A_R),   F_0 = 0,
@@ -153,7 +156,7 @@ constexpr int kSimWaves = 4;
 #define SW_EACH_K(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
 template <int KT>
-__global__ void __launch_bounds__(64 * kSimWaves)
+__global__ void __launch_bounds__(64 * kSimWaves, KT <= 3 ? 5 : (KT <= 4 ? 4 : 2))
 simulate_wave_kernel(const SimWaveParams p)
 {
     extern __shared__ double smem[];
@@ -166,6 +169,26 @@ simulate_wave_kernel(const SimWaveParams p)
     double *csum = F;                                       // [64 KT] class totals while they are summed (spans F and A)
     uint16_t *pos = reinterpret_cast<uint16_t *>(A + (R + 1));   // [levels][R] range maxima of the 1-based positions
 
+    // Per class slot, fixed for the launch: kappa from the table when all samples share one order,
+    // else the first two runs of the class row (lo | hi << 16; longer rows read the rest from memory).
+#define SW_RUNS(k)                                                                        \
+    int rb_##k = 0, re_##k = 0;                                                           \
+    unsigned ra_##k = 0, rc_##k = 0;                                                      \
+    if constexpr (k < KT) {                                                               \
+        const int c = k * 64 + lane;                                                      \
+        if (c < C) {                                                                      \
+            if (p.kappa) {                                                                \
+                ra_##k = (unsigned)p.kappa[c];                                            \
+            } else {                                                                      \
+                rb_##k = p.run_ptr[c];                                                    \
+                re_##k = p.run_ptr[c + 1];                                                \
+                if (re_##k > rb_##k) ra_##k = (unsigned)p.run_lo[rb_##k] | ((unsigned)p.run_hi[rb_##k] << 16);              \
+                if (re_##k > rb_##k + 1) rc_##k = (unsigned)p.run_lo[rb_##k + 1] | ((unsigned)p.run_hi[rb_##k + 1] << 16);  \
+            }                                                                             \
+        }                                                                                 \
+    }
+    SW_EACH_K(SW_RUNS)
+
     const int gwave = blockIdx.x * kSimWaves + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
         const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
@@ -173,8 +196,15 @@ simulate_wave_kernel(const SimWaveParams p)
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
         wave_sync();                        // LDS of the previous sample is no longer read
 
-        // ---- transfer times, class totals ----
-        for (int r = lane; r < R; r += 64) { t[r] = rt[r]; pos[r] = 0; }
+        // ---- everything the sample reads from memory is requested here: the transfer times and
+        // the order into registers (position slot q: r = q * 64 + lane), then the op_time row ----
+#define SW_REQUEST(q)                                                                     \
+        double rt_##q = 0.0;                                                              \
+        int or_##q = -1;                                                                  \
+        if constexpr (q < KT) {                                                           \
+            if (q * 64 + lane < R) { rt_##q = rt[q * 64 + lane]; or_##q = ord[q * 64 + lane]; } \
+        }
+        SW_EACH_K(SW_REQUEST)
         for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
         wave_sync();
         class_totals(csum, ot, p.col_cls, N, lane);
@@ -183,27 +213,33 @@ simulate_wave_kernel(const SimWaveParams p)
         SW_EACH_K(SW_DECL)
 #define SW_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
         SW_EACH_K(SW_TOTAL)
+#define SW_TIMES(q) if constexpr (q < KT) { if (q * 64 + lane < R) { t[q * 64 + lane] = rt_##q; pos[q * 64 + lane] = 0; } }
+        SW_EACH_K(SW_TIMES)
         wave_sync();
 
         // ---- positions, F ----
         double fc = 0.0;
-        for (int base = 0; base < R; base += 64) {
-            const int s = base + lane;
-            const int r = s < R ? ord[s] : -1;
-            const bool ok = (unsigned)r < (unsigned)R;      // an invalid entry is skipped, never dereferenced
-            if (ok) pos[r] = (uint16_t)(s + 1);
-            const double x = ok ? t[r] : 0.0;
-            const double inc = wave_incl_scan_f64_dpp(x);
-            if (s < R) F[s] = fc + inc;
-            fc += lane63_f64(inc);
+#define SW_PLACE(q)                                                                       \
+        if constexpr (q < KT) {                                                           \
+            if (q * 64 < R) {                                                             \
+                const int s = q * 64 + lane;                                              \
+                const int r = or_##q;                                                     \
+                const bool ok = (unsigned)r < (unsigned)R;  /* an invalid entry is skipped, never dereferenced */ \
+                if (ok) pos[r] = (uint16_t)(s + 1);                                       \
+                const double x = ok ? t[r] : 0.0;                                         \
+                const double inc = wave_incl_scan_f64_dpp(x);                             \
+                if (s < R) F[s] = fc + inc;                                               \
+                fc += lane63_f64(inc);                                                    \
+            }                                                                             \
         }
+        SW_EACH_K(SW_PLACE)
         const double Ftot = fc;
         for (int j = lane; j <= R; j += 64) A[j] = 0.0;
         wave_sync();
 
         // ---- kappa ----
         if (p.kappa) {
-#define SW_KAPPA_TABLE(k) if constexpr (k < KT) { if (k * 64 + lane < C) kap_##k = p.kappa[k * 64 + lane]; }
+#define SW_KAPPA_TABLE(k) if constexpr (k < KT) { kap_##k = (int)ra_##k; }
             SW_EACH_K(SW_KAPPA_TABLE)
         } else {
             // level j of the table: maximum over [i, min(i + 2^j, R))
@@ -214,17 +250,21 @@ simulate_wave_kernel(const SimWaveParams p)
                 for (int i = lane; i < R; i += 64) cur[i] = max(prev[i], prev[min(i + h, R - 1)]);
                 wave_sync();
             }
+#define SW_RANGE_MAX(lo, hi)                                                              \
+                    {                                                                     \
+                        const int j_ = 31 - __builtin_clz((hi) - (lo));                   \
+                        const uint16_t *lv_ = pos + (size_t)j_ * R;                       \
+                        m = max(m, max((int)lv_[lo], (int)lv_[(hi) - (1 << j_)]));        \
+                    }
 #define SW_KAPPA_RUNS(k)                                                                  \
             if constexpr (k < KT) {                                                       \
-                const int c = k * 64 + lane;                                              \
-                if (c < C) {                                                              \
-                    const int rend = p.run_ptr[c + 1];                                    \
+                if (k * 64 + lane < C) {                                                  \
                     int m = 0;                                                            \
-                    for (int q = p.run_ptr[c]; q < rend; ++q) {                           \
+                    if (re_##k > rb_##k) SW_RANGE_MAX((int)(ra_##k & 0xffffu), (int)(ra_##k >> 16))          \
+                    if (re_##k > rb_##k + 1) SW_RANGE_MAX((int)(rc_##k & 0xffffu), (int)(rc_##k >> 16))      \
+                    for (int q = rb_##k + 2; q < re_##k; ++q) {                           \
                         const int lo = p.run_lo[q], hi = p.run_hi[q];                     \
-                        const int j = 31 - __builtin_clz(hi - lo);                        \
-                        const uint16_t *lv = pos + (size_t)j * R;                         \
-                        m = max(m, max((int)lv[lo], (int)lv[hi - (1 << j)]));             \
+                        SW_RANGE_MAX(lo, hi)                                              \
                     }                                                                     \
                     kap_##k = m;                                                          \
                 }                                                                         \
@@ -296,7 +336,7 @@ static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
 // hipErrorNotSupported: the graph is outside what the wave kernel handles
 static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_t *kappa, hipStream_t s)
 {
-    const int K = (d.C + 63) / 64;
+    const int K = std::max((d.C + 63) / 64, (d.R + 63) / 64);   // slots per lane: classes, and positions of the order
     const int KT = K <= 4 ? K : (K <= 6 ? 6 : 8);     // the instantiation that is launched below
     // (the class totals are summed in the space of F and A: one double per class slot must fit)
     if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || !d.d_run_ptr || (size_t)64 * KT > 2 * (size_t)d.R + 1)
