@@ -159,8 +159,11 @@ def main() -> int:
         comparison = {}
         for name_, r_ in legs.items():
             m_, e_ = r_[0], r_[1]
+            qm_ = torch.quantile(m_, torch.tensor([0.05, 0.5, 0.95], dtype=torch.float64, device="cuda"))
+            qe_ = torch.quantile(e_, torch.tensor([0.05, 0.5, 0.95], dtype=torch.float64, device="cuda"))
             rec = {"mean_makespan_s": float(m_.mean()), "mean_efficiency": float(e_.mean()),
-                   "min_efficiency": float(e_.min())}
+                   "min_efficiency": float(e_.min()),
+                   "makespan_s_p05_p50_p95": [float(x) for x in qm_], "efficiency_p05_p50_p95": [float(x) for x in qe_]}
             for w_ in (2, 4, 8, 16):
                 s_ = tt.straggler_effect(m_, w_)
                 rec[f"straggler_w{w_}"] = {"mean": float(s_.mean()), "max": float(s_.max())}

@@ -40,17 +40,6 @@ __device__ __forceinline__ double wave_max_f64(double v)
     return v;
 }
 
-// inclusive prefix sum over the lanes of a wave
-__device__ __forceinline__ double wave_incl_scan_f64(double v)
-{
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double u = __shfl_up(v, off);
-        if (lane_id() >= off) v += u;
-    }
-    return v;
-}
-
 // ---- the same reductions and scans through data-parallel-primitive moves (no LDS traffic) ----
 // A wave64 is four rows of 16 lanes.  row_shr:n moves a value n lanes up inside a row;
 // row_bcast:15 hands lane 15 of every row to the whole next row, row_bcast:31 hands lane 31
@@ -216,31 +205,10 @@ __device__ __forceinline__ void class_totals(double *totals, const TimeRow &row,
     else class_totals(totals, row.as_f64(), cls_of, N, lane);
 }
 
-__device__ __forceinline__ uint64_t readfirstlane_u64(uint64_t x)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
 __device__ __forceinline__ int wave_min_i32(int v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
-    return v;
-}
-
-__device__ __forceinline__ int wave_max_i32(int v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
-    return v;
-}
-
-__device__ __forceinline__ int wave_sum_i32(int v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
 }
 
