@@ -99,6 +99,13 @@ tac_kernel(const TacKernelParams p)
         cnt = reinterpret_cast<int32_t *>(Mp + R);
     }
 
+    if (p.only_flagged) {
+        // as a rule no sample of the workgroup is flagged: its threads look at one flag each and leave
+        int any = 0;
+        for (long long b = blockIdx.x + (long long)tid * gridDim.x; b < p.B; b += (long long)BS * gridDim.x)
+            any |= p.only_flagged[b];
+        if (!__syncthreads_or(any)) return;
+    }
     for (int b = blockIdx.x; b < p.B; b += gridDim.x) {
         if (p.only_flagged && p.only_flagged[b] == 0) continue;   // uniform over the workgroup
         const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
