@@ -244,11 +244,12 @@ def tac_simulate(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_
     under its order in one pass.  Returns ``(order, rank, sel_P, sel_Mplus, makespan, eff, U, L, S)``."""
     B = _check_times(dag, op_time, recv_time, allow_f32=True)
     R = dag.n_recv
-    order = torch.empty((B, R), dtype=torch.int32, device="cuda")
-    rank = torch.empty((B, R), dtype=torch.int32, device="cuda") if want_rank else None
+    # (one allocation per dtype: the outputs are rows of two blocks)
+    ints = torch.empty((2 if want_rank else 1, B, R), dtype=torch.int32, device="cuda")
+    order, rank = ints[0], (ints[1] if want_rank else None)
     sel_P = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
     sel_M = torch.empty((B, R), dtype=torch.float64, device="cuda") if want_sel else None
-    out = [torch.empty(B, dtype=torch.float64, device="cuda") for _ in range(5)]
+    out = torch.empty((5, B), dtype=torch.float64, device="cuda").unbind(0)
     fn = lib().tictac_tac_simulate_f32 if op_time.dtype == torch.float32 else lib().tictac_tac_simulate
     _check(fn(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order), _dev(rank), _dev(sel_P),
               _dev(sel_M), *(_dev(o) for o in out), _stream()))
