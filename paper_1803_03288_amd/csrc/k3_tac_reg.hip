@@ -66,15 +66,19 @@ struct TacRegParams {
 // per compute unit leaves the most LDS to the per-wave arrays.
 constexpr int kRegWavesMax = 12;
 constexpr int reg_waves(int KT) { return KT <= 4 ? 4 : kRegWavesMax; }
+// Words per lane in the LDS table of class rows: the KT words of a lane sit next to each other,
+// with one word of padding when KT is even, so that the lanes of a wave reading their k-th word
+// fall into different banks (an even stride puts every 32 / gcd(stride, 32)-th lane on one bank).
+constexpr int row_stride(int KT) { return (KT % 2 == 0) ? KT + 1 : KT; }
 constexpr int CNT1 = 1 << 20;          // one unit of the outstanding count in `packed`
 constexpr int IDX_MASK = CNT1 - 1;
 
-// lowest outstanding recv of class (lane, k); rows: [2W][64][KT] halves, alive: [2W] halves in LDS
+// lowest outstanding recv of class (lane, k); rows: [2W][64][row_stride(KT)] halves, alive: [2W] halves in LDS
 template <int KT>
 __device__ __forceinline__ int first_alive(const uint32_t *rows, const uint32_t *alive, int W, int lane, int k)
 {
     for (int h = 0; h < 2 * W; ++h) {
-        const uint32_t x = rows[(h * 64 + lane) * KT + k] & alive[h];
+        const uint32_t x = rows[(h * 64 + lane) * row_stride(KT) + k] & alive[h];
         if (x) return h * 32 + __builtin_ctz(x);
     }
     return INT32_MAX;
@@ -94,19 +98,20 @@ tac_reg_kernel(const TacRegParams p)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // ---- LDS: class rows shared by the workgroup, then one private region per wave ----
-    uint32_t *rows = reinterpret_cast<uint32_t *>(smem);            // [2W][64][KT]
-    const int rows_doubles = (2 * W * 64 * KT + 1) / 2;
+    constexpr int KS = row_stride(KT);
+    uint32_t *rows = reinterpret_cast<uint32_t *>(smem);            // [2W][64][KS]
+    const int rows_doubles = (2 * W * 64 * KS + 1) / 2;
     double *mine = smem + rows_doubles + (size_t)wave * p.wave_doubles;
     double *t = mine;                       // [R+1]  Time(recv); after the loop: class time by release position
     double *P = t + (R + 1);                // [R+1]  P; after the loop: positions, then the ends of the transfers
     int32_t *ordl = reinterpret_cast<int32_t *>(P + (R + 1));       // [R] order built so far
     uint32_t *aliveh = reinterpret_cast<uint32_t *>(ordl + R);      // [2W] outstanding recvs
 
-    for (int idx = threadIdx.x; idx < 2 * W * 64 * KT; idx += blockDim.x) {
-        const int h = idx / (64 * KT), rem = idx % (64 * KT);
-        const int l = rem / KT, k = rem % KT;
+    for (int idx = threadIdx.x; idx < 2 * W * 64 * KS; idx += blockDim.x) {
+        const int h = idx / (64 * KS), rem = idx % (64 * KS);
+        const int l = rem / KS, k = rem % KS;
         const int c = k * 64 + l;
-        const uint64_t x = c < C ? p.cls_dep[(size_t)c * W + (h >> 1)] : 0ull;
+        const uint64_t x = (k < KT && c < C) ? p.cls_dep[(size_t)c * W + (h >> 1)] : 0ull;
         rows[idx] = (h & 1) ? (uint32_t)(x >> 32) : (uint32_t)x;
     }
     __syncthreads();                        // the only workgroup barrier
@@ -123,7 +128,7 @@ tac_reg_kernel(const TacRegParams p)
     }
     TT_EACH_K(TT_INIT_CONST)
 
-    const uint32_t *rows_lane = rows + lane * KT;      // this lane's KT words of half-row 0
+    const uint32_t *rows_lane = rows + lane * KS;      // this lane's KT words of half-row 0
     double *csum = P;                                  // [64 KT] class totals while they are summed (spans P, ordl, aliveh)
 
     const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
@@ -239,7 +244,7 @@ tac_reg_kernel(const TacRegParams p)
                     const int r_ = __builtin_amdgcn_readlane(r_l, i);                     \
                     const int tlo = __builtin_amdgcn_readlane(__double2loint(t_l), i);    \
                     const int thi = __builtin_amdgcn_readlane(__double2hiint(t_l), i);    \
-                    const uint32_t *rbm = rows_lane + (r_ >> 5) * (64 * KT);              \
+                    const uint32_t *rbm = rows_lane + (r_ >> 5) * (64 * KS);              \
                     const int shm = r_ & 31;                                              \
                     TT_EACH_K(TT_M_SUB)                                                   \
                 }                                                                         \
@@ -301,7 +306,7 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_APPLY()                                                                        \
             {                                                                             \
                 *ord_next++ = best;                     /* every lane writes the same value */ \
-                const uint32_t *rb = rows_lane + (best >> 5) * (64 * KT);                 \
+                const uint32_t *rb = rows_lane + (best >> 5) * (64 * KS);                 \
                 const int delta = CNT1 + (best & IDX_MASK);    /* the mask tells the compiler it fits 24 bits */ \
                 uint32_t hmax = 0;                                                        \
                 TT_EACH_K(TT_UPDATE)                                                      \
@@ -431,8 +436,8 @@ tac_reg_kernel(const TacRegParams p)
                             double v = TT_INF, u = TT_INF;
 #define TT_MPLUS(k)                                                                       \
                             if constexpr (k < KT) {                                   \
-                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KT + k] >> (a & 31);       \
-                                const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KT + k] >> (best & 31); \
+                                const uint32_t ra = rows[((a >> 5) * 64 + lane) * KS + k] >> (a & 31);       \
+                                const uint32_t rb2 = rows[((best >> 5) * 64 + lane) * KS + k] >> (best & 31); \
                                 if (pk_##k >= 0 && (ra & 1u)) v = fmin(v, M_##k);     \
                                 if (pk_##k >= 0 && (rb2 & 1u)) u = fmin(u, M_##k);    \
                             }
@@ -518,7 +523,7 @@ template <int KT>
 static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
 {
     // LDS: shared rows + per wave t [R+1], P [R+1], ordl [R] i32, outstanding set [2W] u32
-    const size_t rows_doubles = ((size_t)2 * d.W * 64 * KT + 1) / 2;
+    const size_t rows_doubles = ((size_t)2 * d.W * 64 * row_stride(KT) + 1) / 2;
     const size_t per_wave = 2 * ((size_t)d.R + 1) + ((size_t)d.R + 2 * d.W + 1) / 2 + 1;
     // as many waves as LDS allows, at most reg_waves(KT)
     int waves = reg_waves(KT);
