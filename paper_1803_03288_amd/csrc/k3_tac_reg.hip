@@ -62,9 +62,9 @@ struct TacRegParams {
 };
 
 // Waves per workgroup.  The class rows in LDS are shared by the workgroup, so with many classes
-// per lane (large rows, many registers: three waves per SIMD at most) one large workgroup
-// per compute unit leaves the most LDS to the per-wave arrays.
-constexpr int kRegWavesMax = 12;
+// per lane (large rows, many registers) one large workgroup per compute unit leaves the most
+// LDS to the per-wave arrays; sixteen waves cap the registers at 128 per lane, four waves per SIMD.
+constexpr int kRegWavesMax = 16;
 constexpr int reg_waves(int KT) { return KT <= 4 ? 4 : kRegWavesMax; }
 // Words per lane in the LDS table of class rows: the KT words of a lane sit next to each other,
 // with one word of padding when KT is even, so that the lanes of a wave reading their k-th word
