@@ -529,6 +529,51 @@ def test_float32_timing_arrays(tt, name, k):
             assert np.array_equal(a.cpu().numpy(), b), f"{name}: simulate {nm}"
 
 
+@pytest.mark.parametrize("name", ["tiny", "layered70", "resnet50", "r129"])
+def test_times_that_are_not_quantised(tt, name):
+    """Lognormal times as they come (sums round differently in different orders): float64 outputs
+    within 1e-5 relative of the oracle's.  The simulation, the several-channel simulation and the
+    search take no decision that rounding could turn (the search is compared through the makespan of
+    the order it returns); TAC can, where two sums that are equal in exact arithmetic are formed in
+    different ways, so its orders are compared sample by sample, and an order that differs must
+    still be a permutation whose makespan the oracle confirms."""
+    makers = dict(SMALL)
+    makers.update(EXTRA)
+    d, h, dep = get(tt, name, makers.get(name))
+    R, B = d.n_recv, 48
+    rng = np.random.default_rng(77)
+    op = rng.lognormal(np.log(1e-3), 0.5, size=(B, d.n_compute))
+    rv = rng.lognormal(np.log(2e-3), 0.7, size=(B, R))
+    gop, grv = cuda(op), cuda(rv)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+
+    def close(got, exp, what):
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-9 if nm in "ES" else 0.0,
+                                       err_msg=f"{name}: {what} {nm}")
+
+    close(tt.simulate(h, cuda(orders), gop, grv), oracle.simulate(*args, orders, op, rv), "simulate")
+    chan = rng.integers(0, 3, size=R).astype(np.int32)
+    close(tt.simulate_channels(h, 3, chan, cuda(orders), gop, grv),
+          oracle.simulate_channels(*args, 3, chan, orders, op, rv), "three channels")
+    got = tt.tac_simulate(h, gop, grv, want_rank=True)
+    go = got[0].cpu().numpy()
+    assert np.array_equal(np.sort(go, axis=1), np.tile(np.arange(R, dtype=np.int32), (B, 1)))
+    eo = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    same = (go == eo).all(axis=1)
+    print(f"[unquantised] {name}: {int(same.sum())} of {B} TAC orders equal to the oracle's", flush=True)
+    assert same.mean() >= 0.9
+    close(got[4:], oracle.simulate(*args, go, op, rv), "fused, under the order the GPU chose")
+    moves = rng.integers(0, R, size=(40, 2)).astype(np.int32)
+    best, mb, ms, acc = tt.order_search(h, cuda(orders), cuda(moves), gop, grv)
+    bo = best.cpu().numpy()
+    assert np.array_equal(np.sort(bo, axis=1), np.tile(np.arange(R, dtype=np.int32), (B, 1)))
+    np.testing.assert_allclose(mb.cpu().numpy(), oracle.simulate(*args, bo, op, rv)[0], rtol=RTOL)
+    np.testing.assert_allclose(ms.cpu().numpy(), oracle.simulate(*args, orders, op, rv)[0], rtol=RTOL)
+    assert bool((mb <= ms).all())
+
+
 def test_time_oracle_min(tt):
     """Minimum over measured runs, element by element against the oracle: even and odd lengths
     (two-element and one-element loads), one run, many runs, a batch of timing rows."""
