@@ -367,7 +367,60 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         int32_t ring = 64;
         while (ring < M && (ring < 2 * kK1Rpt * per_pass || (size_t)ring * 2 * d->k1_wc * 8 <= 64 * 1024)) ring *= 2;
         d->k1_ring = ring;
-        if (max_width <= per_pass) {
+        // level-major records (see internal.h): when a workgroup has more than one wave, the padding at
+        // most quadruples the records, and sixteen levels of slots fit a ring of 64 KB
+        int32_t lring = 0;
+        if (max_width <= per_pass && threads > 64 && (int64_t)n_node_levels * per_pass <= (int64_t)4 * M + 8192) {
+            lring = 64;
+            while ((size_t)lring * 2 * d->k1_wc * 8 <= 64 * 1024 && lring < n_node_levels * per_pass) lring *= 2;
+            if (lring < 16 * per_pass && lring < n_node_levels * per_pass) lring = 0;
+        }
+        d->k1_lring = lring;
+        if (lring > 0) {
+            const int32_t P = per_pass, row_bytes = d->k1_wc * 8, zero_row = lring * row_bytes;
+            std::vector<int32_t> slot_of(M);            // position -> slot
+            for (int32_t l = 0; l < n_node_levels; ++l)
+                for (int32_t q = nlvl_ptr[l]; q < nlvl_ptr[l + 1]; ++q) slot_of[q] = l * P + (q - nlvl_ptr[l]);
+            Dag::FastRec none;
+            for (int j = 0; j < 4; ++j) none.in[j] = zero_row;
+            none.rcv[0] = none.rcv[1] = -1;
+            none.op = -1;
+            none.ovf = -1;
+            std::vector<Dag::FastRec> lrecs((size_t)n_node_levels * P, none);
+            std::vector<int32_t> lfovf;
+            for (int32_t l = 0; l < n_node_levels; ++l)
+                for (int32_t q = nlvl_ptr[l]; q < nlvl_ptr[l + 1]; ++q) {
+                    const Dag::NodeRec &r = nodes[q];
+                    Dag::FastRec &f = lrecs[slot_of[q]];
+                    tmp.clear();
+                    for (int j = 0; j < 6; ++j) if (r.in[j] != INT32_MIN) tmp.push_back(r.in[j]);
+                    if (r.ovf_beg >= 0)
+                        for (int32_t e = 1; e <= ovf_idx[r.ovf_beg]; ++e) tmp.push_back(ovf_idx[r.ovf_beg + e]);
+                    int nn = 0, nr = 0;
+                    bool resident = true;       // every node input is still in the ring while level l is computed
+                    for (int32_t &x : tmp) {
+                        if (x < 0) { ++nr; continue; }
+                        ++nn;
+                        x = slot_of[x];
+                        resident = resident && (int64_t)x >= (int64_t)(l + 1) * P - lring;
+                    }
+                    f.op = r.op;
+                    if (nn <= 4 && nr <= 2 && resident) {
+                        int a = 0, b = 0;
+                        for (int32_t x : tmp) {
+                            if (x < 0) f.rcv[b++] = ~x;
+                            else f.in[a++] = (x & (lring - 1)) * row_bytes;
+                        }
+                    } else {
+                        f.ovf = (int32_t)lfovf.size();
+                        lfovf.push_back((int32_t)tmp.size());
+                        lfovf.insert(lfovf.end(), tmp.begin(), tmp.end());
+                    }
+                }
+            graph.add(&d->d_lrecs, lrecs);
+            graph.add(&d->d_lfovf, lfovf);
+            d->lfovf_len = (int32_t)lfovf.size();
+        } else if (max_width <= per_pass) {
             const int32_t row_bytes = d->k1_wc * 8, zero_row = ring * row_bytes;
             std::vector<Dag::FastRec> frecs(M);
             std::vector<int32_t> fovf;

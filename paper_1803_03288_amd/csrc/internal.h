@@ -59,6 +59,15 @@ struct Dag {
     FastRec *d_frecs = nullptr;     // [M] (not built when a level is wider than one pass)
     int32_t *d_fovf = nullptr;
     int32_t fovf_len = 0;
+    // Level-major form of the same records for graphs whose levels fill most of a pass: level l
+    // owns the slots l * P .. l * P + P - 1 (P = k1_threads / k1_wc), slot l * P + j holds the j-th node
+    // of the level, the others a record with op = -1.  Positions, ring offsets and the input
+    // lists (lfovf) count slots.  Not built (NULL) when the padding would cost too much or the
+    // graph takes another kernel.
+    FastRec *d_lrecs = nullptr;     // [n_node_levels * P]
+    int32_t *d_lfovf = nullptr;
+    int32_t lfovf_len = 0;
+    int32_t k1_lring = 0;           // slots held in LDS (a power of two, at least 16 levels)
     int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]

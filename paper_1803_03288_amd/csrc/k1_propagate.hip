@@ -416,6 +416,104 @@ propagate_nodes_wave(const PropParams p)
     }
 }
 
+// Level-major records (see internal.h): thread group j of the workgroup takes slot l * P + j at
+// level l, so a level needs no bounds and no bookkeeping of positions, and the records need no
+// staging in LDS: every thread reads its own record straight from memory, eight levels ahead,
+// into eight register sets used in turn.  A level is then: the reads of the input rows from the
+// ring, the OR, the write of the row to the ring and to memory, one barrier.  Memory
+// operations of a wave complete in the order in which they were issued, and a level issues at
+// least the two loads of a record, so "at most fourteen outstanding" before the barrier of a level
+// means that this wave's stores of eight levels ago and earlier are in memory; the ring holds at
+// least sixteen levels, hence a row that has left the ring can be read from memory.
+// all inputs of a node that does not fit a record, from its list (in LDS when fov is not NULL):
+// recv bits, rows still in the ring (slots from safe_from on), older rows from memory.  The
+// arguments are passed one by one: a kernel whose parameter block has its address taken reads
+// every pointer of it through generic loads, which wait for LDS and memory alike.
+__device__ __noinline__ uint64_t other_inputs(const int32_t *lfovf, const int32_t *fov, const uint64_t *ring,
+                                              const Dag::FastRec *lrecs, uint64_t *dep, int W, int beg,
+                                              int safe_from, uint32_t rmask, int WC, int w, int gw)
+{
+    const int32_t *list = fov ? fov : lfovf;
+    const int cnt = list[beg];
+    uint64_t val = 0;
+    for (int e = 1; e <= cnt; ++e) {
+        const int x = list[beg + e];
+        if (x < 0) {
+            const int i = ~x;
+            if ((i >> 6) == gw) val |= 1ull << (i & 63);
+        } else if (x >= safe_from) {
+            val |= ring[((uint32_t)x & rmask) * WC + w];
+        } else {
+            val |= __hip_atomic_load(&dep[(size_t)lrecs[x].op * W + gw], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    return val;
+}
+
+struct LevelParams {
+    int32_t n_levels, W, P, ring;       // P slots per level; ring: slots held in LDS (power of two)
+    const Dag::FastRec *lrecs;          // [n_levels * P]
+    const int32_t *lfovf;
+    int32_t lfovf_lds;                  // > 0: that many entries of lfovf (all of them) are copied to LDS
+    uint64_t *dep;
+};
+
+#define KL_EACH(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
+
+template <int WC>
+__global__ void __launch_bounds__(1024)
+propagate_levels(const LevelParams p)
+{
+    extern __shared__ uint64_t ring[];          // rows [ring + 2][WC] (the last two all zero), then the input lists
+    const int W = p.W, L = p.n_levels, P = p.P;
+    const int w = threadIdx.x % WC, sub = threadIdx.x / WC;
+    const int gw = slice_of_block() * WC + w;
+    const uint32_t rmask = (uint32_t)p.ring - 1u;
+    int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * WC);
+    if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < p.lfovf_lds; i += blockDim.x) fov[i] = p.lfovf[i];
+    __syncthreads();
+    if (L == 0) return;
+
+    // record of level l for this thread group (levels past the end: the last level again, never used)
+#define KL_LOAD(a, b, l)                                                                  \
+    {                                                                                     \
+        const int4 *q_ = reinterpret_cast<const int4 *>(p.lrecs + (size_t)min((l), L - 1) * P + sub); \
+        a = q_[0]; b = q_[1];                                                             \
+    }
+#define KL_DECL(i) int4 a##i, b##i; KL_LOAD(a##i, b##i, i)
+    KL_EACH(KL_DECL)
+
+    // (the next record of a set is requested after the last use of the set, into the same registers)
+#define KL_STEP(i)                                                                        \
+    {                                                                                     \
+        const int l = l0 + i;                                                             \
+        if (l < L && b##i.z >= 0) {                                                       \
+            const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;             \
+            const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + a##i.x);      \
+            const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + a##i.y);      \
+            const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + a##i.z);      \
+            const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + a##i.w);      \
+            uint64_t bits = (b##i.x >> 6) == gw ? 1ull << (b##i.x & 63) : 0ull;           \
+            bits |= (b##i.y >> 6) == gw ? 1ull << (b##i.y & 63) : 0ull;                   \
+            uint64_t val = bits | v0 | v1 | v2 | v3;                                      \
+            if (b##i.w >= 0 && gw < W)                                                    \
+                val |= other_inputs(p.lfovf, p.lfovf_lds > 0 ? fov : nullptr, ring, p.lrecs, p.dep, W, b##i.w, \
+                                    (l + 1) * P - p.ring, rmask, WC, w, gw);              \
+            if (gw >= W) val = 0;                                                         \
+            ring[(((uint32_t)(l * P + sub)) & rmask) * WC + w] = val;                     \
+            if (gw < W) p.dep[(size_t)b##i.z * W + gw] = val;                             \
+        }                                                                                 \
+        KL_LOAD(a##i, b##i, l + 8)                                                        \
+        asm volatile("s_waitcnt vmcnt(14)" ::: "memory");                                 \
+        lds_barrier();                                                                    \
+    }
+    for (int l0 = 0; l0 < L; l0 += 8) { KL_EACH(KL_STEP) }
+#undef KL_STEP
+#undef KL_DECL
+#undef KL_LOAD
+}
+
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto
 __global__ void __launch_bounds__(256)
 expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep)
@@ -444,7 +542,23 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     const int per_pass = threads / WC;
     const int blocks = (d.W + WC - 1) / WC;
     const bool wide = d.max_node_level_width > per_pass;
-    if (!wide && !d.d_frecs) return hipErrorInvalidValue;
+    if (!wide && !d.d_frecs && !d.d_lrecs) return hipErrorInvalidValue;
+    if (d.d_lrecs) {
+        // level-major records: no staging, no chunks
+        LevelParams q;
+        q.n_levels = d.n_node_levels; q.W = d.W; q.P = per_pass; q.ring = d.k1_lring;
+        q.lrecs = d.d_lrecs; q.lfovf = d.d_lfovf; q.dep = d.d_dep;
+        q.lfovf_lds = d.lfovf_len <= 4096 ? d.lfovf_len : 0;
+        const size_t lds_l = (size_t)(d.k1_lring + 2) * WC * 8 + (size_t)q.lfovf_lds * 4;
+        if (lds_l > 150 * 1024) return hipErrorInvalidValue;
+        if (lds_l > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_levels<WC>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_l);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(propagate_levels<WC>, dim3(blocks), dim3(threads), lds_l, s, q);
+        return hipGetLastError();
+    }
     const int ring = d.k1_ring;
     p.ring = ring;
     // one wave per slice when no level is wider than a wave and everything fits in LDS
