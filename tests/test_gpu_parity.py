@@ -74,6 +74,11 @@ SMALL = {
     "long_edges": lambda: wl.deep_narrow_dag(22, levels=2500, width=4, n_recv=60),
     # the same with wider rows (W = 3 words, four-word slices)
     "long_edges_w3": lambda: wl.deep_narrow_dag(23, levels=1300, width=4, n_recv=150),
+    # levels of a hundred ops (several waves per workgroup: the level-major kernel) with edges that reach
+    # back past the rows kept in LDS, for one-, two- and four-word slices
+    "deep_w1": lambda: wl.deep_narrow_dag(24, levels=700, width=100, n_recv=60),
+    "deep_w2": lambda: wl.deep_narrow_dag(25, levels=400, width=70, n_recv=100),
+    "deep_w3": lambda: wl.deep_narrow_dag(26, levels=500, width=40, n_recv=150),
 }
 PRESETS = ["tiny", "resnet50", "vgg16", "inception3", "stress"]
 
