@@ -463,6 +463,8 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     graph.add(&d->d_src, src);
     const size_t dep_words = (size_t)n * d->W;
     graph.reserve(&d->d_dep, dep_words * 8);
+    if (d->k1_lring > 0)
+        graph.reserve(&d->d_k1_sink, (size_t)((d->W + d->k1_wc - 1) / d->k1_wc) * d->k1_threads * 8);
     // (sized for the copy back of the rows as well, so that the block is not replaced while a copy is under way)
     (void)stage(std::max(graph.host.size(), dep_words * 8));
     HIP_TRY(graph.commit(&d->d_graph_block, s));

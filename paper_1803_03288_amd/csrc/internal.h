@@ -68,6 +68,7 @@ struct Dag {
     int32_t *d_lfovf = nullptr;
     int32_t lfovf_len = 0;
     int32_t k1_lring = 0;           // slots held in LDS (a power of two, at least 16 levels)
+    uint64_t *d_k1_sink = nullptr;  // [slices * k1_threads] one word per thread: where a thread without a node stores
     int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]

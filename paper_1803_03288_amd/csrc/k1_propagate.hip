@@ -422,9 +422,11 @@ propagate_nodes_wave(const PropParams p)
 // into eight register sets used in turn.  A level is then: the reads of the input rows from the
 // ring, the OR, the write of the row to the ring and to memory, one barrier.  Memory
 // operations of a wave complete in the order in which they were issued, and a level issues at
-// least the two loads of a record, so "at most fourteen outstanding" before the barrier of a level
-// means that this wave's stores of eight levels ago and earlier are in memory; the ring holds at
-// least sixteen levels, hence a row that has left the ring can be read from memory.
+// exactly two loads (the record of eight levels on) and one store (a thread without a node stores
+// a zero to a word of its own), so "at most twenty-one outstanding" before the barrier of a level
+// means that this wave's stores of seven levels ago and earlier are in memory, and that the record
+// of the next level has arrived; the ring holds at least sixteen levels, hence a row that has left
+// the ring can be read from memory.
 // all inputs of a node that does not fit a record, from its list (in LDS when fov is not NULL):
 // recv bits, rows still in the ring (slots from safe_from on), older rows from memory.  The
 // arguments are passed one by one: a kernel whose parameter block has its address taken reads
@@ -456,6 +458,7 @@ struct LevelParams {
     const int32_t *lfovf;
     int32_t lfovf_lds;                  // > 0: that many entries of lfovf (all of them) are copied to LDS
     uint64_t *dep;
+    uint64_t *sink;                     // [gridDim.x * blockDim.x]
 };
 
 #define KL_EACH(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
@@ -484,10 +487,13 @@ propagate_levels(const LevelParams p)
 #define KL_DECL(i) int4 a##i, b##i; KL_LOAD(a##i, b##i, i)
     KL_EACH(KL_DECL)
 
+    uint64_t *const sink = p.sink + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     // (the next record of a set is requested after the last use of the set, into the same registers)
 #define KL_STEP(i)                                                                        \
     {                                                                                     \
-        const int l = l0 + i;                                                             \
+        const int l = lbase + i;                                                          \
+        uint64_t val = 0;                                                                 \
+        uint64_t *dst = sink;               /* past the last level and without a node: a zero to the sink */ \
         if (l < L && b##i.z >= 0) {                                                       \
             const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;             \
             const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + a##i.x);      \
@@ -496,19 +502,27 @@ propagate_levels(const LevelParams p)
             const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + a##i.w);      \
             uint64_t bits = (b##i.x >> 6) == gw ? 1ull << (b##i.x & 63) : 0ull;           \
             bits |= (b##i.y >> 6) == gw ? 1ull << (b##i.y & 63) : 0ull;                   \
-            uint64_t val = bits | v0 | v1 | v2 | v3;                                      \
+            val = bits | v0 | v1 | v2 | v3;                                               \
             if (b##i.w >= 0 && gw < W)                                                    \
                 val |= other_inputs(p.lfovf, p.lfovf_lds > 0 ? fov : nullptr, ring, p.lrecs, p.dep, W, b##i.w, \
                                     (l + 1) * P - p.ring, rmask, WC, w, gw);              \
             if (gw >= W) val = 0;                                                         \
             ring[(((uint32_t)(l * P + sub)) & rmask) * WC + w] = val;                     \
-            if (gw < W) p.dep[(size_t)b##i.z * W + gw] = val;                             \
+            if (gw < W) dst = &p.dep[(size_t)b##i.z * W + gw];                            \
         }                                                                                 \
+        *dst = val;                                                                       \
         KL_LOAD(a##i, b##i, l + 8)                                                        \
-        asm volatile("s_waitcnt vmcnt(14)" ::: "memory");                                 \
+        asm volatile("s_waitcnt vmcnt(21)" ::: "memory");                                 \
         lds_barrier();                                                                    \
     }
-    for (int l0 = 0; l0 < L; l0 += 8) { KL_EACH(KL_STEP) }
+    // (32 levels per trip of the loop: the compiler drains every outstanding load and store at the
+    // head of a loop that carries loaded registers round, which should be rare)
+    for (int l0 = 0; l0 < L; l0 += 32) {
+        { const int lbase = l0;      KL_EACH(KL_STEP) }
+        { const int lbase = l0 + 8;  KL_EACH(KL_STEP) }
+        { const int lbase = l0 + 16; KL_EACH(KL_STEP) }
+        { const int lbase = l0 + 24; KL_EACH(KL_STEP) }
+    }
 #undef KL_STEP
 #undef KL_DECL
 #undef KL_LOAD
@@ -547,7 +561,8 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
         // level-major records: no staging, no chunks
         LevelParams q;
         q.n_levels = d.n_node_levels; q.W = d.W; q.P = per_pass; q.ring = d.k1_lring;
-        q.lrecs = d.d_lrecs; q.lfovf = d.d_lfovf; q.dep = d.d_dep;
+        q.lrecs = d.d_lrecs; q.lfovf = d.d_lfovf; q.dep = d.d_dep; q.sink = d.d_k1_sink;
+        if (!q.sink) return hipErrorInvalidValue;
         q.lfovf_lds = d.lfovf_len <= 4096 ? d.lfovf_len : 0;
         const size_t lds_l = (size_t)(d.k1_lring + 2) * WC * 8 + (size_t)q.lfovf_lds * 4;
         if (lds_l > 150 * 1024) return hipErrorInvalidValue;
