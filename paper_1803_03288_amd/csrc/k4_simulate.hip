@@ -379,7 +379,7 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
 // arrival array (runs of the class rows), the last step by comparing every class with every
 // class (lane l owns classes l, l + 64, ...; the pairs (rho, time) are broadcast from LDS).
 struct SimChanParams {
-    int32_t B, R, C, N, n_waves, wave_bytes, levels, n_channels;
+    int32_t B, R, C, N, n_waves, wave_bytes, levels, n_channels, chan_bytes;
     const int32_t *col_cls, *run_ptr, *run_lo, *run_hi;
     const int32_t *chan;        // [R] channel of every recv, 0 <= chan < n_channels <= 64
     const int32_t *order;
@@ -396,12 +396,29 @@ simulate_channels_kernel(const SimChanParams p)
     extern __shared__ double smem[];
     const int R = p.R, C = p.C, N = p.N;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    double *mine = reinterpret_cast<double *>(reinterpret_cast<char *>(smem) + (size_t)wave * p.wave_bytes);
+    int32_t *chan_l = reinterpret_cast<int32_t *>(smem);    // [R] channel of every recv, shared by the waves
+    double *mine = reinterpret_cast<double *>(reinterpret_cast<char *>(smem) + p.chan_bytes + (size_t)wave * p.wave_bytes);
     double *t = mine;                       // [R]          Time(recv)
     double *arr = t + R;                    // [levels][R]  level 0: arrival of recv r; level j: maxima over [i, i + 2^j)
     // [64 KT][2] (rho, class time), 16-byte aligned; first the class totals while they are summed
     double *pairs = arr + (size_t)p.levels * R + (((size_t)(1 + p.levels) * R) & 1);
     double *csum = pairs;
+    for (int r = threadIdx.x; r < R; r += blockDim.x) chan_l[r] = p.chan[r];
+    __syncthreads();
+    // the first two runs of every class row (lo | hi << 16), fixed for the launch; longer rows read the rest
+#define SC_RUNS(k)                                                                        \
+    int rb_##k = 0, re_##k = 0;                                                           \
+    unsigned ra_##k = 0, rc_##k = 0;                                                      \
+    if constexpr (k < KT) {                                                               \
+        const int c = k * 64 + lane;                                                      \
+        if (c < C) {                                                                      \
+            rb_##k = p.run_ptr[c];                                                        \
+            re_##k = p.run_ptr[c + 1];                                                    \
+            if (re_##k > rb_##k) ra_##k = (unsigned)p.run_lo[rb_##k] | ((unsigned)p.run_hi[rb_##k] << 16);              \
+            if (re_##k > rb_##k + 1) rc_##k = (unsigned)p.run_lo[rb_##k + 1] | ((unsigned)p.run_hi[rb_##k + 1] << 16);  \
+        }                                                                                 \
+    }
+    SW_EACH_K(SC_RUNS)
 
     const int gwave = blockIdx.x * (blockDim.x >> 6) + wave;
     for (int b = gwave; b < p.B; b += p.n_waves) {
@@ -410,8 +427,15 @@ simulate_channels_kernel(const SimChanParams p)
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
         wave_sync();
 
-        // ---- transfer times, class totals ----
-        for (int r = lane; r < R; r += 64) { t[r] = rt[r]; arr[r] = 0.0; }
+        // ---- transfer times and the order are requested first, into registers (position slot q:
+        // q * 64 + lane), then the op_time row ----
+#define SC_REQUEST(q)                                                                     \
+        double rt_##q = 0.0;                                                              \
+        int or_##q = -1;                                                                  \
+        if constexpr (q < KT) {                                                           \
+            if (q * 64 + lane < R) { rt_##q = rt[q * 64 + lane]; or_##q = ord[q * 64 + lane]; } \
+        }
+        SW_EACH_K(SC_REQUEST)
         for (int c = lane; c < 64 * KT; c += 64) csum[c] = 0.0;
         wave_sync();
         class_totals(csum, ot, p.col_cls, N, lane);
@@ -420,27 +444,32 @@ simulate_channels_kernel(const SimChanParams p)
         SW_EACH_K(SC_DECL)
 #define SC_TOTAL(k) if constexpr (k < KT) { ct_##k = csum[k * 64 + lane]; }
         SW_EACH_K(SC_TOTAL)
+#define SC_TIMES(q) if constexpr (q < KT) { if (q * 64 + lane < R) { t[q * 64 + lane] = rt_##q; arr[q * 64 + lane] = 0.0; } }
+        SW_EACH_K(SC_TIMES)
         wave_sync();
 
         // ---- arrivals: per channel, prefix sums over the positions of the order ----
         double carry = 0.0;                 // lane c: time queued on channel c so far
         double sum_r = 0.0;
-        for (int base = 0; base < R; base += 64) {
-            const int s = base + lane;
-            const int r = s < R ? ord[s] : -1;
-            const bool ok = (unsigned)r < (unsigned)R;      // an invalid entry is skipped, never dereferenced
-            const int cl = ok ? p.chan[r] : -1;
-            const double x = ok ? t[r] : 0.0;
-            double a = 0.0;
-            for (int c = 0; c < p.n_channels; ++c) {
-                const double inc = wave_incl_scan_f64_dpp(cl == c ? x : 0.0);
-                const double before = readlane_f64(carry, c);
-                if (cl == c) a = before + inc;
-                if (lane == c) carry += lane63_f64(inc);
-            }
-            if (ok) arr[r] = a;
-            sum_r += x;
+#define SC_ARRIVE(q)                                                                      \
+        if constexpr (q < KT) {                                                           \
+            if (q * 64 < R) {                                                             \
+                const int r = or_##q;                                                     \
+                const bool ok = (unsigned)r < (unsigned)R;  /* an invalid entry is skipped, never dereferenced */ \
+                const int cl = ok ? chan_l[r] : -1;                                       \
+                const double x = ok ? t[r] : 0.0;                                         \
+                double a = 0.0;                                                           \
+                for (int c = 0; c < p.n_channels; ++c) {                                  \
+                    const double inc = wave_incl_scan_f64_dpp(cl == c ? x : 0.0);         \
+                    const double before = readlane_f64(carry, c);                         \
+                    if (cl == c) a = before + inc;                                        \
+                    if (lane == c) carry += lane63_f64(inc);                              \
+                }                                                                         \
+                if (ok) arr[r] = a;                                                       \
+                sum_r += x;                                                               \
+            }                                                                             \
         }
+        SW_EACH_K(SC_ARRIVE)
         sum_r = wave_sum_f64_dpp(sum_r);
         const double last_arrival = wave_max_f64_dpp(lane < p.n_channels ? carry : 0.0);   // = largest channel sum
         wave_sync();
@@ -453,17 +482,22 @@ simulate_channels_kernel(const SimChanParams p)
             for (int i = lane; i < R; i += 64) cur[i] = fmax(prev[i], prev[min(i + h, R - 1)]);
             wave_sync();
         }
+#define SC_RANGE_MAX(lo, hi)                                                              \
+                {                                                                         \
+                    const int j_ = 31 - __builtin_clz((hi) - (lo));                       \
+                    const double *lv_ = arr + (size_t)j_ * R;                             \
+                    m = fmax(m, fmax(lv_[lo], lv_[(hi) - (1 << j_)]));                    \
+                }
 #define SC_RHO(k)                                                                         \
         if constexpr (k < KT) {                                                           \
             const int c = k * 64 + lane;                                                  \
             if (c < C) {                                                                  \
-                const int rend = p.run_ptr[c + 1];                                        \
                 double m = 0.0;                                                           \
-                for (int q = p.run_ptr[c]; q < rend; ++q) {                               \
+                if (re_##k > rb_##k) SC_RANGE_MAX((int)(ra_##k & 0xffffu), (int)(ra_##k >> 16))         \
+                if (re_##k > rb_##k + 1) SC_RANGE_MAX((int)(rc_##k & 0xffffu), (int)(rc_##k >> 16))     \
+                for (int q = rb_##k + 2; q < re_##k; ++q) {                               \
                     const int lo = p.run_lo[q], hi = p.run_hi[q];                         \
-                    const int j = 31 - __builtin_clz(hi - lo);                            \
-                    const double *lv = arr + (size_t)j * R;                               \
-                    m = fmax(m, fmax(lv[lo], lv[hi - (1 << j)]));                         \
+                    SC_RANGE_MAX(lo, hi)                                                  \
                 }                                                                         \
                 rho_##k = m;                                                              \
             }                                                                             \
@@ -507,9 +541,11 @@ static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
     const size_t wave_bytes = (((size_t)d.R * (1 + levels) + 1 + (size_t)128 * KT) * 8 + 15) & ~(size_t)15;
     int waves = 4;
     while (waves > 1 && wave_bytes * waves > 40 * 1024) waves >>= 1;
-    const size_t lds = wave_bytes * waves;
-    if (lds > 64 * 1024) return hipErrorNotSupported;
+    const size_t chan_bytes = ((size_t)d.R * 4 + 15) & ~(size_t)15;
+    const size_t lds = chan_bytes + wave_bytes * waves;
+    if (lds > 150 * 1024) return hipErrorNotSupported;     // 160 KB of LDS per compute unit
     p.wave_bytes = (int32_t)wave_bytes;
+    p.chan_bytes = (int32_t)chan_bytes;
     hipError_t e;
     if (lds > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(simulate_channels_kernel<KT>),
@@ -535,7 +571,7 @@ static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
 hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;
-    const int K = (d.C + 63) / 64;
+    const int K = std::max((d.C + 63) / 64, (d.R + 63) / 64);   // slots per lane: classes, and positions of the order
     const int KT = K <= 4 ? (K < 1 ? 1 : K) : (K <= 6 ? 6 : 8);
     if (d.R == 0 || d.R > 512 || K > 8 || n_channels > 64 || (d.C > 0 && (!d.d_col_cls || !d.d_run_ptr))) return hipErrorNotSupported;
     SimChanParams p{};
