@@ -108,6 +108,35 @@ struct Packer {
     }
 };
 
+int device_cu_count(int device)
+{
+    static thread_local int known_device = -1, known_count = 0;
+    if (device == known_device) return known_count;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        n = 256;
+    }
+    known_device = device;
+    known_count = n;
+    return n;
+}
+
+hipError_t cached_blocks_per_cu(int *per_cu, const void *kernel, int threads, size_t lds)
+{
+    struct Entry { const void *kernel; int threads; size_t lds; int per_cu; };
+    static thread_local std::vector<Entry> known;
+    for (const Entry &e : known)
+        if (e.kernel == kernel && e.threads == threads && e.lds == lds) { *per_cu = e.per_cu; return hipSuccess; }
+    int n = 0;
+    const hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds);
+    if (err != hipSuccess) return err;
+    if (n < 1) n = 1;
+    if (known.size() < 256) known.push_back({kernel, threads, lds, n});
+    *per_cu = n;
+    return hipSuccess;
+}
+
 hipError_t ensure_workspace(Dag *d, size_t bytes)
 {
     if (bytes <= d->work_bytes) return hipSuccess;

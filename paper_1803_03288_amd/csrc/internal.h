@@ -102,6 +102,12 @@ struct Dag {
 
 hipError_t ensure_workspace(Dag *d, size_t bytes);
 
+// Number of compute units of a device and the number of workgroups of a kernel that fit one,
+// asked of the runtime once and remembered (the queries cost microseconds on every launch
+// otherwise).  The occupancy is remembered per (kernel, threads, dynamic LDS bytes).
+int device_cu_count(int device);
+hipError_t cached_blocks_per_cu(int *per_cu, const void *kernel, int threads, size_t lds);
+
 // ---- kernel launchers (each returns the HIP status of its launches) ----
 
 // op.dep for every op (Sec. 4.1)

@@ -541,13 +541,10 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tac_reg_kernel<KT>, 64 * waves, lds);
+    e = cached_blocks_per_cu(&per_cu, reinterpret_cast<const void *>(tac_reg_kernel<KT>), 64 * waves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    int n_cu = 256;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
-        n_cu = prop.multiProcessorCount;
+    const int n_cu = device_cu_count(d.device);
     int grid = per_cu * n_cu;                       // one resident set of workgroups, no tail
     const int need = (p.B + waves - 1) / waves;
     if (grid > need) grid = need;

@@ -318,13 +318,10 @@ static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, simulate_wave_kernel<KT>, 64 * kSimWaves, lds);
+    e = cached_blocks_per_cu(&per_cu, reinterpret_cast<const void *>(simulate_wave_kernel<KT>), 64 * kSimWaves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    int n_cu = 256;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
-        n_cu = prop.multiProcessorCount;
+    const int n_cu = device_cu_count(d.device);
     int grid = per_cu * n_cu;
     const int need = (p.B + kSimWaves - 1) / kSimWaves;
     if (grid > need) grid = need;
@@ -553,13 +550,10 @@ static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, simulate_channels_kernel<KT>, 64 * waves, lds);
+    e = cached_blocks_per_cu(&per_cu, reinterpret_cast<const void *>(simulate_channels_kernel<KT>), 64 * waves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    int n_cu = 256;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
-        n_cu = prop.multiProcessorCount;
+    const int n_cu = device_cu_count(d.device);
     int grid = per_cu * n_cu;
     const int need = (p.B + waves - 1) / waves;
     if (grid > need) grid = need;

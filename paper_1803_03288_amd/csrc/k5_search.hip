@@ -323,13 +323,10 @@ static hipError_t launch_search_t(SearchParams &p, const Dag &d, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, order_search_kernel<T>, 64 * kSearchWaves, lds);
+    e = cached_blocks_per_cu(&per_cu, reinterpret_cast<const void *>(order_search_kernel<T>), 64 * kSearchWaves, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    int n_cu = 256;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, d.device) == hipSuccess && prop.multiProcessorCount > 0)
-        n_cu = prop.multiProcessorCount;
+    const int n_cu = device_cu_count(d.device);
     int grid = per_cu * n_cu;
     const int need = (p.B + kSearchWaves - 1) / kSearchWaves;
     if (grid > need) grid = need;
