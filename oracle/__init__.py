@@ -103,20 +103,27 @@ def tic(dep: np.ndarray, recv_ids) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     return prio, order, rank
 
 
-def tac(dep: np.ndarray, recv_ids, op_time, recv_time, max_rounds: int = -1, comparator_mode: int = 0):
+def tac(dep: np.ndarray, recv_ids, op_time, recv_time, max_rounds: int = -1, comparator_mode: int = 0,
+        alive0=None):
     """Sec. 4.3, Algorithm 3, for every row of ``op_time [B][N]`` / ``recv_time [B][R]``.
+    ``alive0 [B][R]`` (optional) marks the recvs that are still outstanding when the loop starts
+    (default: all of them, as the algorithm states); steps are then counted from that set.
     Returns ``(order, rank, sel_P, sel_Mplus)``, each ``[B][R]``."""
     dep = np.ascontiguousarray(dep, dtype=np.uint64)
     recv_ids, op_time, recv_time = _i32(recv_ids), _f64(op_time), _f64(recv_time)
     n, R = dep.shape[0], recv_ids.size
     B = recv_time.shape[0]
     assert op_time.shape == (B, n - R) and recv_time.shape == (B, R)
+    a0 = None
+    if alive0 is not None:
+        a0 = np.ascontiguousarray(alive0, dtype=np.uint8)
+        assert a0.shape == (B, R)
     order = np.full((B, R), -1, dtype=np.int32)
     rank = np.full((B, R), -1, dtype=np.int32)
     sel_P = np.full((B, R), np.nan)
     sel_Mplus = np.full((B, R), np.nan)
     rc = _load().oracle_tac(ctypes.c_int(n), ctypes.c_int(R), _p(dep), _p(recv_ids), ctypes.c_int(B), _p(op_time),
-                            _p(recv_time), ctypes.c_int(max_rounds), ctypes.c_int(comparator_mode),
+                            _p(recv_time), _p(a0), ctypes.c_int(max_rounds), ctypes.c_int(comparator_mode),
                             _p(order), _p(rank), _p(sel_P), _p(sel_Mplus))
     _check(rc, "oracle_tac")
     return order, rank, sel_P, sel_Mplus

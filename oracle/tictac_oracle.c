@@ -257,16 +257,21 @@ static int precedes(int a, int b, const double *P, const double *Mrecv, const do
  * Sec. 4.3, Algorithm 3 (TAC) for B timing samples.
  *   op_time [B][N]: column j = j-th compute op in ascending op id
  *   recv_time [B][R]: column i = recv i
- *   max_rounds < 0: run to the end; otherwise stop after that many selections
+ *   alive0: NULL, or [B][R] with 1 = recv i of sample b is still outstanding when the
+ *           loop starts.  Algorithm 3 starts with every recv in R; its loop body (the
+ *           property update of Algorithm 1 on the current R, then the choice of the
+ *           minimum) depends on nothing but the current R, so starting from a smaller R
+ *           yields the rounds that follow a prefix which removed the other recvs.
+ *   max_rounds < 0: run until R is empty; otherwise stop after that many selections
  *                   (remaining order entries and ranks are -1)
- *   order [B][R] step -> recv; rank [B][R] recv -> step;
+ *   order [B][R] step -> recv (steps counted from the start set); rank [B][R] recv -> step;
  *   sel_P, sel_Mplus [B][R] (may be NULL): P and M+ of each recv in the round in
  *   which it was selected.
  * Every round recomputes Algorithm 1 from scratch over the whole graph.
  * ---------------------------------------------------------------------- */
 int oracle_tac(int n, int R, const uint64_t *dep, const int32_t *recv_ids, int B, const double *op_time,
-               const double *recv_time, int max_rounds, int comparator_mode, int32_t *order,
-               int32_t *rank, double *sel_P, double *sel_Mplus)
+               const double *recv_time, const uint8_t *alive0, int max_rounds, int comparator_mode,
+               int32_t *order, int32_t *rank, double *sel_P, double *sel_Mplus)
 {
     const int N = n - R;
     int32_t *ri = recv_index_of_op(n, R, recv_ids);
@@ -283,13 +288,17 @@ int oracle_tac(int n, int R, const uint64_t *dep, const int32_t *recv_ids, int B
         depsets_free(&s);
         return ORACLE_ERR_MEM;
     }
-    const int rounds = (max_rounds < 0 || max_rounds > R) ? R : max_rounds;
     for (int b = 0; b < B; ++b) {
         const double *ot = op_time + (size_t)b * N, *rt = recv_time + (size_t)b * R;
         int32_t *ord = order + (size_t)b * R, *rk = rank + (size_t)b * R;
-        int j = 0;
+        int j = 0, outstanding = 0;
         for (int v = 0; v < n; ++v) time[v] = (ri[v] >= 0) ? rt[ri[v]] : ot[j++];
-        for (int i = 0; i < R; ++i) { alive[i] = 1; ord[i] = -1; rk[i] = -1; }
+        for (int i = 0; i < R; ++i) {
+            alive[i] = alive0 ? (alive0[(size_t)b * R + i] != 0) : 1;
+            outstanding += alive[i];
+            ord[i] = -1; rk[i] = -1;
+        }
+        const int rounds = (max_rounds < 0 || max_rounds > outstanding) ? outstanding : max_rounds;
         for (int step = 0; step < rounds; ++step) {
             update_properties(n, R, &s, ri, time, recv_ids, alive, M, P, Mplus);
             for (int i = 0; i < R; ++i) Mrecv[i] = M[recv_ids[i]];   /* = Time(recv i) while outstanding */

@@ -233,8 +233,20 @@ tac_kernel(const TacKernelParams p)
                 __syncthreads();
                 for (int c = tid; c < C; c += BS) {
                     if (cnt[c] < 2) continue;
-                    const unsigned long long mbits = (unsigned long long)__double_as_longlong(M[c]);
                     const uint64_t *row = p.cls_dep + (size_t)c * W;
+                    // M of the class as Algorithm 1 forms it: the sum over its outstanding recvs in
+                    // ascending index.  (The running M[c] is kept by subtraction; with transfer times of
+                    // zero outstanding, its rounding residue can be negative or positive where the
+                    // fresh sum is exactly 0, which would change both the minimum and exact ties.)
+                    double Mc = 0.0;
+                    for (int w = 0; w < W; ++w) {
+                        uint64_t x = row[w] & alive[w];
+                        while (x) {
+                            Mc += t[w * 64 + __builtin_ctzll(x)];
+                            x &= x - 1;
+                        }
+                    }
+                    const unsigned long long mbits = (unsigned long long)__double_as_longlong(Mc);
                     for (int w = 0; w < W; ++w) {
                         uint64_t x = row[w] & alive[w];
                         while (x) {

@@ -7,6 +7,7 @@ from __future__ import annotations
 
 import itertools
 import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List
 
 import numpy as np
@@ -107,3 +108,40 @@ def closed_form_makespan(depb: np.ndarray, dag, order: np.ndarray, op_time: np.n
 
 def all_orders(R: int) -> np.ndarray:
     return np.array(list(itertools.permutations(range(R))), dtype=np.int32).reshape(-1, R)
+
+
+def oracle_tac_rows(dep, recv_ids, op, rv, threads: int = 8, **kw):
+    """``oracle.tac`` on the rows of ``op`` / ``rv``, the rows dealt to a few host threads (the
+    oracle itself is single-threaded and the samples are independent; ctypes releases the
+    interpreter lock during the call).  ``alive0`` in ``kw`` is split along with the rows."""
+    import oracle
+    B = rv.shape[0]
+    threads = max(1, min(threads, B))
+    bounds = np.linspace(0, B, threads + 1).astype(int)
+    alive0 = kw.pop("alive0", None)
+
+    def part(i):
+        lo, hi = bounds[i], bounds[i + 1]
+        a0 = None if alive0 is None else alive0[lo:hi]
+        return oracle.tac(dep, recv_ids, op[lo:hi], rv[lo:hi], alive0=a0, **kw)
+
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(part, range(threads)))
+    return tuple(np.concatenate([p[j] for p in parts], axis=0) for j in range(4))
+
+
+def oracle_rounds_after_prefix(dep, recv_ids, op_row, rv_row, order_row, ks, threads: int = 8):
+    """For every k in ``ks``: the recv that Algorithm 3 selects, with its P and M+, when the recvs
+    ``order_row[:k]`` have been removed, i.e. round k of the sample as the oracle sees it after the
+    given prefix.  Returns ``(selected [len(ks)], P, Mplus)``."""
+    R = order_row.shape[0]
+    ks = list(ks)
+    alive0 = np.ones((len(ks), R), dtype=np.uint8)
+    for j, k in enumerate(ks):
+        alive0[j, order_row[:k]] = 0
+    op = np.repeat(op_row[None, :], len(ks), axis=0)
+    rv = np.repeat(rv_row[None, :], len(ks), axis=0)
+    o, _, sP, sM = oracle_tac_rows(dep, recv_ids, op, rv, threads=threads, alive0=alive0, max_rounds=1)
+    sel = o[:, 0]
+    rows = np.arange(len(ks))
+    return sel, sP[rows, sel], sM[rows, sel]

@@ -15,7 +15,7 @@ torch = pytest.importorskip("torch")
 import oracle
 from paper_1803_03288_amd import workloads as wl
 
-from helpers import dep_bool
+from helpers import dep_bool, oracle_rounds_after_prefix, oracle_tac_rows
 
 RTOL = 1e-5
 
@@ -611,88 +611,198 @@ def test_power_of_two_scaling_and_determinism(tt):
 # --------------------------------------------------------------------------
 
 def closed_form_shared(depb_comp, order, op, rv):
-    """vectorised closed form of the makespan for one shared order (see helpers)."""
+    """Makespan of every sample under one shared order, recomputed from the oracle's dep matrix
+    alone: kappa of an op = last position among its recvs, A_k = time of the ops with kappa = k,
+    makespan = max_k (F_k + A_k + ... + A_R) (see helpers.closed_form_makespan)."""
+    import scipy.sparse as sp
     R = order.size
-    pos = np.zeros(R, dtype=np.int64)
-    pos[order] = np.arange(1, R + 1)
-    kappa = (depb_comp * pos[None, :]).max(axis=1) if R else np.zeros(depb_comp.shape[0], dtype=np.int64)
-    onehot = np.zeros((depb_comp.shape[0], R + 1))
-    onehot[np.arange(depb_comp.shape[0]), kappa] = 1.0
-    A = op @ onehot
+    N = depb_comp.shape[0]
+    pos = np.zeros(R, dtype=np.int32)
+    pos[order] = np.arange(1, R + 1, dtype=np.int32)
+    kappa = np.zeros(N, dtype=np.int64)
+    for n0 in range(0, N, 8192):
+        blk = depb_comp[n0:n0 + 8192]
+        kappa[n0:n0 + 8192] = (blk * pos[None, :]).max(axis=1) if R else 0
+    onehot = sp.csr_matrix((np.ones(N), (np.arange(N), kappa)), shape=(N, R + 1))
+    A = np.asarray((onehot.T @ op.T).T)
     F = np.concatenate([np.zeros((op.shape[0], 1)), np.cumsum(rv[:, order], axis=1)], axis=1)
     S = np.cumsum(A[:, ::-1], axis=1)[:, ::-1]
     return np.maximum((F + S).max(axis=1), F[:, -1])
 
 
-@pytest.mark.parametrize("name,B", [("resnet50", 65536), ("vgg16", 262144)])
+def check_sampled_rounds(tt, d, dep, op_rows, rv_rows, orders, ks, tag, sel_P=None, sel_Mplus=None):
+    """Rounds `ks` of every given sample: the oracle, started from the recvs that the GPU's own order
+    has not removed before round k, must select what the GPU selected in round k (and, when the
+    per-round outputs are given, with the same P and M+)."""
+    for b in range(orders.shape[0]):
+        print(f"[rounds] {tag}: sample {b}, {len(ks)} oracle rounds", flush=True)
+        sel, eP, eM = oracle_rounds_after_prefix(dep, d.recv_ids, op_rows[b], rv_rows[b], orders[b], ks, threads=12)
+        got = orders[b][list(ks)]
+        assert np.array_equal(got, sel), f"{tag}: sample {b}: rounds {[k for k, a, e in zip(ks, got, sel) if a != e]} differ"
+        if sel_P is not None:
+            np.testing.assert_allclose(sel_P[b][sel], eP, rtol=RTOL, atol=0)
+            gM = sel_Mplus[b][sel]
+            assert np.array_equal(np.isinf(gM), np.isinf(eM))
+            np.testing.assert_allclose(gM[np.isfinite(eM)], eM[np.isfinite(eM)], rtol=RTOL, atol=0)
+
+
+STRESS_ROUNDS = list(range(16)) + [64, 512, 1024, 2048] + list(range(4080, 4096))
+
+
+@pytest.mark.parametrize("name,B", [("resnet50", 65536), ("vgg16", 262144), ("inception3", 65536), ("stress", 4096)])
 def test_full_batch_properties(tt, name, B):
-    """Whole batch of the preset: every order is a permutation, L <= m <= U, the makespan
-    equals the closed form recomputed in numpy from the oracle's dep matrix, and sampled
-    rows equal the oracle exactly."""
+    """Whole batch of the preset, in the launch configuration the benchmark times: every order is a
+    permutation, L <= m <= U, sampled rows equal the oracle exactly (on the stress preset, whose
+    4096 rounds per sample the oracle cannot run in full: sampled rounds of two rows, each started
+    from the GPU's own prefix), and the makespans under the shared TIC order equal the closed form
+    recomputed in numpy from the oracle's dep matrix on every sample."""
     d, h, dep = get(tt, name)
     assert B == d.batch
     print(f"[full] {name}: generating {B} samples", flush=True)
     op, rv = wl.timing_samples(d, 0, B)
     gop, grv = cuda(op), cuda(rv)
+    print(f"[full] {name}: tac_simulate", flush=True)
     res = tt.tac_simulate(h, gop, grv, want_rank=True)
     order, rank = res[0], res[1]
     m, e, U, L, S = (x.cpu().numpy() for x in res[4:])
     R = d.n_recv
     srt = torch.sort(order.long(), dim=1).values
     assert torch.equal(srt, torch.arange(R, device="cuda").expand(B, R))
+    del srt
     assert torch.equal(torch.gather(rank.long(), 1, order.long()), torch.arange(R, device="cuda").expand(B, R))
     assert (L <= m).all() and (m <= U).all() and (e >= 0).all() and (e <= 1).all()
-    # sampled rows against the oracle
-    rows = subset_rows(B, 24 if name == "resnet50" else 256)
-    eo = oracle.tac(dep, d.recv_ids, op[rows], rv[rows])[0]
-    assert np.array_equal(order[rows].cpu().numpy(), eo)
-    exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op[rows], rv[rows])
-    assert np.array_equal(m[rows], exp[0]) and np.array_equal(e[rows], exp[1])
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    if name == "stress":
+        rows = [0, B - 1]
+        go = order[rows].cpu().numpy()
+        check_sampled_rounds(tt, d, dep, op[rows], rv[rows], go, STRESS_ROUNDS, name)
+        exp = oracle.simulate(*args, go, op[rows], rv[rows])
+        assert np.array_equal(m[rows], exp[0]) and np.array_equal(e[rows], exp[1])
+    else:
+        # sampled rows against the oracle
+        rows = subset_rows(B, {"resnet50": 24, "vgg16": 256, "inception3": 32}[name])
+        print(f"[full] {name}: oracle on {len(rows)} rows", flush=True)
+        eo = oracle_tac_rows(dep, d.recv_ids, op[rows], rv[rows], threads=12)[0]
+        assert np.array_equal(order[rows].cpu().numpy(), eo)
+        exp = oracle.simulate(*args, eo, op[rows], rv[rows])
+        assert np.array_equal(m[rows], exp[0]) and np.array_equal(e[rows], exp[1])
     # shared TIC order on the whole batch against the closed form
+    print(f"[full] {name}: closed form on every sample", flush=True)
     tic_order = oracle.tic(dep, d.recv_ids)[1]
     m2 = tt.simulate(h, cuda(tic_order), gop, grv)[0].cpu().numpy()
     depb = dep_bool(dep, R)[d.compute_ids()]
-    blk = 8192
+    blk = 512 if name == "stress" else 8192
     for b0 in range(0, B, blk):
         ref = closed_form_shared(depb, tic_order, op[b0:b0 + blk], rv[b0:b0 + blk])
         assert np.array_equal(m2[b0:b0 + blk], ref)
+    if R > 512 or h.n_classes > 512:
+        return
     # order search on the whole batch from random orders: permutations, never worse than the start,
     # the makespan it reports is the one of the order it returns, sampled rows equal the oracle
+    print(f"[full] {name}: order search", flush=True)
     rnd = wl.random_orders(d, 0, B)
-    moves = np.random.default_rng(3).integers(0, R, size=(192, 2)).astype(np.int32)
+    n_moves = 48 if name == "inception3" else 192
+    moves = np.random.default_rng(3).integers(0, R, size=(n_moves, 2)).astype(np.int32)
     best, mb, ms, acc = tt.order_search(h, cuda(rnd), cuda(moves), gop, grv)
     assert torch.equal(torch.sort(best.long(), dim=1).values, torch.arange(R, device="cuda").expand(B, R))
     assert bool((mb <= ms).all()) and bool(((acc > 0) == (mb < ms)).all())
     assert torch.equal(tt.simulate(h, best, gop, grv)[0], mb)
     assert torch.equal(tt.simulate(h, cuda(rnd), gop, grv)[0], ms)
-    rows = subset_rows(B, 12 if name == "resnet50" else 64)
-    exp = oracle.order_search(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, rnd[rows], moves, op[rows], rv[rows])
+    rows = subset_rows(B, {"resnet50": 12, "vgg16": 64, "inception3": 3}[name])
+    exp = oracle.order_search(*args, rnd[rows], moves, op[rows], rv[rows])
     for a, b_ in zip((best, mb, ms, acc), exp):
         assert np.array_equal(a[rows].cpu().numpy(), b_)
 
 
-def test_stress_full_size_first_rounds(tt):
-    """Preset 5 at full size: the oracle cannot run all 4096 rounds of Algorithm 3 on a
-    100 000-op graph in reasonable time, so the first rounds of two samples are compared
-    (the oracle recomputes Algorithm 1 from scratch in each), plus permutation validity
-    and the simulation of a shared order on a few samples."""
+def test_stress_both_kernels_sampled_rounds(tt):
+    """Preset 5, two samples, through both TAC kernels that serve a graph of this size: the call
+    without per-round outputs and the call with them (sel_P, sel_Mplus).  The oracle cannot run
+    all 4096 rounds of Algorithm 3 on a 100 000-op graph in reasonable time, so sampled rounds
+    are compared, each started from the GPU's own prefix; the two GPU orders must be equal to
+    each other in full, and the simulation under them equal to the oracle's event-driven one."""
     d, h, dep = get(tt, "stress")
-    rows = [0, 4095]
+    rows = [1, 2049]
     op, rv = wl.sample_rows(d, rows)
-    print("[stress] GPU TAC on 2 samples", flush=True)
+    print("[stress] GPU TAC on 2 samples, without and with per-round outputs", flush=True)
     res = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True)
     order = res[0].cpu().numpy()
     assert np.array_equal(np.sort(order, axis=1), np.tile(np.arange(d.n_recv), (2, 1)))
-    print("[stress] oracle, first rounds", flush=True)
-    eo = oracle.tac(dep, d.recv_ids, op, rv, max_rounds=3)[0]
-    assert np.array_equal(order[:, :3], eo[:, :3])
+    res2 = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True, want_sel=True)
+    assert np.array_equal(res2[0].cpu().numpy(), order)
+    assert np.array_equal(res2[1].cpu().numpy(), res[1].cpu().numpy())
+    ks = list(range(8)) + [300, 1500, 3000] + list(range(4090, 4096))
+    check_sampled_rounds(tt, d, dep, op, rv, order, ks, "stress/sel", res2[2].cpu().numpy(), res2[3].cpu().numpy())
     print("[stress] simulate", flush=True)
     exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, order, op, rv)
     got = [x.cpu().numpy() for x in tt.simulate(h, cuda(order), cuda(op), cuda(rv))]
     for a, b in zip(got, exp):
         assert np.array_equal(a, b)
-    assert np.array_equal(res[4].cpu().numpy(), exp[0])
+    assert np.array_equal(res[4].cpu().numpy(), exp[0]) and np.array_equal(res2[4].cpu().numpy(), exp[0])
     tic_order = oracle.tic(dep, d.recv_ids)[1]
     exp2 = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, tic_order, op, rv)
     got2 = tt.simulate(h, cuda(tic_order), cuda(op), cuda(rv))
     assert np.array_equal(got2[0].cpu().numpy(), exp2[0])
+
+
+# --------------------------------------------------------------------------
+# graphs with thousands of classes: the TAC kernels that serve the stress preset, on graphs small
+# enough for the oracle to run every round
+# --------------------------------------------------------------------------
+
+MANY_CLASSES = {
+    # per-sample state beyond what one workgroup's LDS holds (about 9 600 classes, 160 recvs)
+    "mid_stress": lambda: wl.stress_dag(levels=50, width=400, n_recv=160, seed=31, batch=8),
+    # three words per row, recv count off the word boundary
+    "mid_stress_w3": lambda: wl.stress_dag(levels=30, width=300, n_recv=150, seed=32, batch=8),
+}
+
+
+@pytest.mark.parametrize("name", list(MANY_CLASSES))
+def test_many_classes_full_rounds(tt, name):
+    d, h, dep = get(tt, name, MANY_CLASSES[name])
+    print(f"[many] {name}: N={d.n_compute} R={d.n_recv} classes={h.n_classes}", flush=True)
+    assert h.n_classes > 4000
+    op, rv = wl.timing_samples(d, 0, 5)
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name)
+    # exact ties in the comparator, zero-time ops, and transfer times of zero (the literal path)
+    rng = np.random.default_rng(5)
+    op3 = rng.integers(0, 4, size=(3, d.n_compute)).astype(np.float64) * 0.25
+    rv3 = rng.integers(1, 4, size=(3, d.n_recv)).astype(np.float64) * 0.25
+    run_tac_sim_parity(tt, d, h, dep, op3, rv3, name + "/ties")
+    rv0 = rv3.copy()
+    rv0[rng.random(rv0.shape) < 0.2] = 0.0
+    run_tac_sim_parity(tt, d, h, dep, op3, rv0, name + "/zero-transfers")
+
+
+@pytest.mark.parametrize("name", ["layered70", "tiny", "r129", "mid_stress_w3"])
+def test_zero_transfer_times_that_are_not_quantised(tt, name):
+    """Lognormal times as they come, a fifth of the transfer times set to zero: the samples take the
+    literal selection path, in which M of a class is the fresh ascending sum over its outstanding
+    recvs, as in Algorithm 1 (a class whose outstanding recvs all have time zero has M = 0 exactly,
+    and M+ = 0 of its recvs ties exactly with other zeros).  Orders, ranks and the infinite entries
+    of M+ must equal the oracle's."""
+    makers = dict(SMALL)
+    makers.update(EXTRA)
+    makers.update(MANY_CLASSES)
+    d, h, dep = get(tt, name, makers.get(name))
+    R, B = d.n_recv, 4 if name.startswith("mid") else 40
+    rng = np.random.default_rng(123)
+    op = rng.lognormal(np.log(1e-3), 0.5, size=(B, d.n_compute))
+    rv = rng.lognormal(np.log(2e-3), 0.7, size=(B, R))
+    rv[rng.random(rv.shape) < 0.2] = 0.0
+    rv[0, :] = 0.0                                  # every transfer time zero
+    eo, er, eP, eM = oracle_tac_rows(dep, d.recv_ids, op, rv, threads=4)
+    for want_sel in (True, False):
+        got = tt.tac_simulate(h, cuda(op), cuda(rv), want_rank=True, want_sel=want_sel)
+        go = got[0].cpu().numpy()
+        diff = np.flatnonzero((go != eo).any(axis=1))
+        assert diff.size == 0, f"{name}: samples {diff.tolist()} differ (want_sel={want_sel})"
+        assert np.array_equal(got[1].cpu().numpy(), er)
+        if want_sel:
+            gM = got[3].cpu().numpy()
+            assert np.array_equal(np.isinf(gM), np.isinf(eM))
+            np.testing.assert_allclose(gM[np.isfinite(eM)], eM[np.isfinite(eM)], rtol=RTOL, atol=0)
+            np.testing.assert_allclose(got[2].cpu().numpy(), eP, rtol=RTOL, atol=0)
+        exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op, rv)
+        for a, b, nm in zip(got[4:], exp, "m E U L S".split()):
+            np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-9 if nm in "ES" else 0.0)

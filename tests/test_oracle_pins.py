@@ -390,6 +390,42 @@ def test_partial_rounds_prefix():
     assert (part[:, 5:] == -1).all()
 
 
+def test_start_set_continues_a_prefix():
+    """Algorithm 3's loop depends on nothing but the current set R of outstanding recvs, so
+    starting from R = (all recvs) minus the first k of an order reproduces the rest of that
+    order, round by round, with the same P and M+ values.  On the toy graph of Sec. 2.2 the
+    start set {recv2} leaves one round that selects recv2 with P = Time(op2) (op2's only
+    outstanding dependency) and no M+."""
+    d = wl.toy_dag()
+    dep = deps(d)
+    g = read_golden("fig1_toy.txt")
+    rv, op = g["recv_time"][None, :], g["op_time"][None, :]
+    o, r, sP, sM = oracle.tac(dep, d.recv_ids, op, rv, alive0=np.array([[0, 1]], dtype=np.uint8))
+    assert list(o[0]) == [1, -1] and list(r[0]) == [-1, 0]
+    assert sP[0, 1] == op[0, 1] and np.isinf(sM[0, 1])
+    for d in (wl.tiny_dag(), wl.layered_dag(11, levels=9, width=7, fan_in=(1, 3), back=3, n_recv=70, attach=(1, 3)),
+              wl.case2_dag()):
+        dep = deps(d)
+        R = d.n_recv
+        op, rv = wl.timing_samples(d, 0, 3)
+        full, _, fP, fM = oracle.tac(dep, d.recv_ids, op, rv)
+        for k in (0, 1, R // 2, R - 1, R):
+            alive0 = np.ones((3, R), dtype=np.uint8)
+            for b in range(3):
+                alive0[b, full[b, :k]] = 0
+            rest, rk, sP, sM = oracle.tac(dep, d.recv_ids, op, rv, alive0=alive0)
+            np.testing.assert_array_equal(rest[:, :R - k], full[:, k:])
+            assert (rest[:, R - k:] == -1).all()
+            for b in range(3):
+                sel = full[b, k:]
+                np.testing.assert_array_equal(sP[b, sel], fP[b, sel])
+                np.testing.assert_array_equal(sM[b, sel], fM[b, sel])
+                np.testing.assert_array_equal(rk[b, sel], np.arange(R - k))
+            one = oracle.tac(dep, d.recv_ids, op, rv, alive0=alive0, max_rounds=1)[0]
+            if k < R:
+                np.testing.assert_array_equal(one[:, 0], full[:, k])
+
+
 # --------------------------------------------------------------------------
 # Straggler effect (Sec. 6): longest wait over iteration time, per group of workers
 # --------------------------------------------------------------------------
