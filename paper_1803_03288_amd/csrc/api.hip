@@ -589,7 +589,92 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     for (int32_t c = 0; c < d->C; ++c)
         for (int32_t m = cls_ptr[c]; m < cls_ptr[c + 1]; ++m) col_cls[cls_cols[m]] = c;
     cls.add(&d->d_col_cls, col_cls);
+
+    // ---- tables of the bit-sliced TAC kernel (see internal.h), for graphs with many classes ----
+    const int32_t CW = (d->C + 63) / 64;
+    const bool want_sliced = d->R >= 1 && d->W <= 64 && CW <= 15 * 64 * 4 && !(d->C <= 8 * 64 && d->W <= 6) &&
+                             !tac_small_graph(d->R, d->W, d->C);
+    if (want_sliced) {
+        d->CW = CW;
+        d->CWpad = (CW + 15) / 16 * 16;
+        // parents: among the classes of the compute predecessors of an op, those with a strictly smaller dep
+        // that holds two recvs or more; the two largest are kept
+        std::vector<int32_t> par((size_t)d->C * 2, -1);
+        for (int32_t v = 0; v < n; ++v) {
+            if (comp_col[v] < 0) continue;
+            const int32_t cv = col_cls[comp_col[v]];
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+                const int32_t u = col_idx[e];
+                if (comp_col[u] < 0) continue;
+                const int32_t cu = col_cls[comp_col[u]];
+                if (cnt0[cu] < 2 || cnt0[cu] >= cnt0[cv]) continue;
+                int32_t *pv = &par[(size_t)cv * 2];
+                if (pv[0] == cu || pv[1] == cu) continue;
+                if (pv[0] < 0 || cnt0[cu] > cnt0[pv[0]]) { pv[1] = pv[0]; pv[0] = cu; }
+                else if (pv[1] < 0 || cnt0[cu] > cnt0[pv[1]]) pv[1] = cu;
+            }
+        }
+        std::vector<uint64_t> ndom0((size_t)d->CWpad * 2, 0);
+        std::vector<int32_t> nchild(d->C, 0);
+        for (int32_t c = 0; c < d->C; ++c)
+            for (int j = 0; j < 2; ++j) {
+                const int32_t u = par[(size_t)c * 2 + j];
+                if (u < 0) continue;
+                ndom0[(size_t)c >> 5] += 1ull << ((c & 31) * 2);
+                ++nchild[u];
+            }
+        std::vector<int32_t> cptr(d->C + 1, 0);
+        for (int32_t c = 0; c < d->C; ++c) cptr[c + 1] = cptr[c] + nchild[c];
+        std::vector<int32_t> cidx(cptr[d->C]), cfill(cptr.begin(), cptr.end() - 1);
+        for (int32_t c = 0; c < d->C; ++c)
+            for (int j = 0; j < 2; ++j) {
+                const int32_t u = par[(size_t)c * 2 + j];
+                if (u >= 0) cidx[cfill[u]++] = c;
+            }
+        std::vector<int4> crec(d->C);
+        std::vector<int32_t> child_ovf;
+        for (int32_t c = 0; c < d->C; ++c) {
+            const int32_t nc = nchild[c], *ch = cidx.data() + cptr[c];
+            int4 r = make_int4(nc, -1, -1, -1);
+            if (nc >= 1) r.y = ch[0];
+            if (nc >= 2) r.z = ch[1];
+            if (nc == 3) r.w = ch[2];
+            if (nc > 3) {
+                r.w = (int32_t)child_ovf.size();
+                child_ovf.insert(child_ovf.end(), ch + 2, ch + nc);
+            }
+            crec[c] = r;
+        }
+        // classes that depend on one recv (by recv, ascending class) and on none
+        std::vector<int32_t> single_ptr(d->R + 1, 0), single_cls, empty_cls, first_recv(d->C, -1);
+        for (int32_t c = 0; c < d->C; ++c) {
+            if (cnt0[c] == 0) empty_cls.push_back(c);
+            if (cnt0[c] != 1) continue;
+            for (int32_t w = 0; w < d->W; ++w)
+                if (const uint64_t x = cls_dep[(size_t)c * d->W + w]) { first_recv[c] = w * 64 + __builtin_ctzll(x); break; }
+            single_ptr[first_recv[c] + 1]++;
+        }
+        for (int32_t r = 0; r < d->R; ++r) single_ptr[r + 1] += single_ptr[r];
+        single_cls.resize(single_ptr[d->R]);
+        {
+            std::vector<int32_t> fill(single_ptr.begin(), single_ptr.end() - 1);
+            for (int32_t c = 0; c < d->C; ++c)
+                if (cnt0[c] == 1) single_cls[fill[first_recv[c]]++] = c;
+        }
+        d->n_empty_cls = (int32_t)empty_cls.size();
+        cls.add(&d->d_ndom0, ndom0);
+        cls.add(&d->d_cls_par, par);
+        cls.add(&d->d_crec, crec);
+        cls.add(&d->d_child_ovf, child_ovf);
+        cls.add(&d->d_single_ptr, single_ptr);
+        cls.add(&d->d_single_cls, single_cls);
+        cls.add(&d->d_empty_cls, empty_cls);
+        cls.reserve(&d->d_colbits, (size_t)d->R * d->CWpad * 8);
+        cls.reserve(&d->d_planes0, (size_t)13 * d->CWpad * 8);
+        cls.reserve(&d->d_live0, (size_t)d->CWpad * 8);
+    }
     HIP_TRY(cls.commit(&d->d_class_block, s));
+    if (want_sliced) HIP_TRY(launch_sliced_tables(*d, s));
     HIP_TRY(hipStreamSynchronize(s));   // host vectors go out of scope; the handle is complete
     return TICTAC_OK;
 }

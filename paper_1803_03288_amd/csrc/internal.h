@@ -91,6 +91,24 @@ struct Dag {
     int32_t *d_run_hi = nullptr;    // [n_runs]
     int32_t max_members = 0;        // largest class (ops)
 
+    // Tables of the bit-sliced TAC kernel (graphs with many classes; NULL / 0 otherwise).  Classes are
+    // taken 64 at a time ("class words"): bit c & 63 of word c >> 6 stands for class c.
+    int32_t CW = 0, CWpad = 0;      // class words, and the row length of the tables below
+    uint64_t *d_colbits = nullptr;  // [R][CWpad]   which classes hold recv r
+    uint64_t *d_planes0 = nullptr;  // [13][CWpad]  bit j of |dep| of every class (bit-sliced counts)
+    uint64_t *d_live0 = nullptr;    // [CWpad]      classes with |dep| >= 2
+    // "parents" of a class: up to two classes of predecessor ops whose dep is a strict subset with at
+    // least two recvs.  ndom0 holds the number of parents, two bits per class (class word w: bits of
+    // words 2w and 2w+1); crec lists the children of every class (the classes that name it as parent).
+    uint64_t *d_ndom0 = nullptr;    // [CWpad][2]
+    int32_t *d_cls_par = nullptr;   // [C][2] the parents (-1: none)
+    int4 *d_crec = nullptr;         // [C] {n_children, child, child, child}; more than three: w = offset of children 2.. in child_ovf
+    int32_t *d_child_ovf = nullptr;
+    int32_t *d_single_ptr = nullptr;// [R+1] classes whose dep is {r}: single_cls[single_ptr[r] .. single_ptr[r+1]), ascending
+    int32_t *d_single_cls = nullptr;
+    int32_t *d_empty_cls = nullptr; // classes with an empty dep
+    int32_t n_empty_cls = 0;
+
     // scratch owned by the handle (grown on demand, stream-ordered use)
     // the two allocations that hold every array above (graph tables + dep; class tables)
     void *d_graph_block = nullptr, *d_class_block = nullptr;
@@ -128,6 +146,19 @@ struct TacArgs {
     bool f32 = false;
 };
 hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s);
+// LDS bytes of the general TAC kernel with the per-sample state in LDS; graphs for which this is at most
+// 40 KB (and at most 1024 classes) run it with one wave per sample
+inline size_t tac_lds_state_bytes(int32_t R, int32_t W, int32_t C)
+{
+    return ((size_t)R * 2 + (R + 1) + 16 + (size_t)W * 2) * 8 + (size_t)C * 16 + (size_t)R * 8 + (size_t)C * 4;
+}
+inline bool tac_small_graph(int32_t R, int32_t W, int32_t C) { return tac_lds_state_bytes(R, W, C) <= 40 * 1024 && C <= 1024; }
+// bit-sliced variant for graphs with many classes (tables above); the same contract as launch_tac_reg
+bool tac_sliced_fits(const Dag &d);
+// (flags: the first flag_bytes of the handle's workspace, which the launcher grows as needed)
+hipError_t launch_tac_sliced(Dag &d, const TacArgs &a, size_t flag_bytes, int32_t **flags_out, hipStream_t s);
+// device-side construction of colbits, planes0 and live0 from cls_dep and cls_cnt0
+hipError_t launch_sliced_tables(const Dag &d, hipStream_t s);
 // register-resident variant for graphs with few classes; returns hipErrorNotSupported when
 // the graph does not fit it.  Samples it cannot order (a transfer time of zero) are marked
 // in flags[b] = 1 for the general kernel.

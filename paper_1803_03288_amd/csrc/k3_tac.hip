@@ -363,10 +363,8 @@ tac_kernel(const TacKernelParams p)
 
 static size_t tac_lds_bytes(const Dag &d, bool gstate)
 {
-    size_t dbl = (size_t)d.R * 2 + (d.R + 1) + 16 + (size_t)d.W * 2;
-    size_t bytes = dbl * 8;
-    if (!gstate) bytes += (size_t)d.C * 16 + (size_t)d.R * 8 + (size_t)d.C * 4;
-    return bytes;
+    if (!gstate) return tac_lds_state_bytes(d.R, d.W, d.C);
+    return ((size_t)d.R * 2 + (d.R + 1) + 16 + (size_t)d.W * 2) * 8;
 }
 
 static size_t tac_gstate_bytes(const Dag &d)
@@ -408,36 +406,51 @@ hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s)
     p.makespan = a.makespan; p.eff = a.eff; p.U = a.U; p.L = a.L; p.S = a.S;
     p.only_flagged = nullptr;
 
-    // graphs with few classes: register-resident kernel, then the general kernel for the
-    // samples it flagged (those with a transfer time of zero)
+    // graphs with few classes: register-resident kernel; graphs with many: bit-sliced kernel; then the
+    // general kernel for the samples either of them flagged (those with a transfer time of zero).
+    // The handle's workspace: one flag per sample first, the state of the running kernel after them.
+    const size_t flag_bytes = ((size_t)a.B * sizeof(int32_t) + 255) & ~(size_t)255;
+    const size_t lds_small = tac_lds_bytes(d, false);
+    const bool small = tac_small_graph(d.R, d.W, d.C);              // one wave per sample, state in LDS
+    const bool gstate = lds_small > 150 * 1024;                     // state in global memory
+    const int gstate_grid = a.B < 256 ? a.B : 256;
+    const size_t gstate_bytes = gstate ? tac_gstate_bytes(d) * (size_t)gstate_grid : 0;
     if (!a.sel_P && !a.sel_Mplus && d.C <= 8 * 64 && d.W <= 6) {
-        hipError_t e = ensure_workspace(&d, (size_t)a.B * sizeof(int32_t));
+        hipError_t e = ensure_workspace(&d, flag_bytes + gstate_bytes);
         if (e != hipSuccess) return e;
         int32_t *flags = static_cast<int32_t *>(d.d_work);
         e = launch_tac_reg(d, a, flags, s);
         if (e == hipSuccess) p.only_flagged = flags;
         else if (e != hipErrorNotSupported) return e;
     }
+    if (!p.only_flagged && !a.sel_P && !a.sel_Mplus && !small && tac_sliced_fits(d)) {
+        // (sized first for the general kernel's pass over the flagged samples, so that the block is not replaced
+        // between the two launches)
+        hipError_t e = ensure_workspace(&d, flag_bytes + gstate_bytes);
+        if (e != hipSuccess) return e;
+        int32_t *flags = nullptr;
+        e = launch_tac_sliced(d, a, flag_bytes, &flags, s);
+        if (e == hipSuccess) p.only_flagged = flags;
+        else if (e != hipErrorNotSupported) return e;
+    }
 
-    const size_t lds_small = tac_lds_bytes(d, false);
-    if (lds_small <= 40 * 1024 && d.C <= 1024) {
-        // one wave per sample, state in LDS
+    if (small) {
         const int grid = a.B < 256 * 16 ? a.B : 256 * 16;
         return launch_tac_t<64, false>(d, p, grid, lds_small, s);
     }
-    if (lds_small <= 150 * 1024) {
+    if (!gstate) {
         const int grid = a.B < 256 * 2 ? a.B : 256 * 2;
         return launch_tac_t<256, false>(d, p, grid, lds_small, s);
     }
     // state in global memory, one large workgroup per sample
     const size_t lds = tac_lds_bytes(d, true);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    const int grid = a.B < 256 ? a.B : 256;
     p.gstate_stride = tac_gstate_bytes(d);
-    hipError_t e = ensure_workspace(&d, p.gstate_stride * grid);
+    hipError_t e = ensure_workspace(&d, flag_bytes + gstate_bytes);
     if (e != hipSuccess) return e;
-    p.gstate = static_cast<char *>(d.d_work);
-    return launch_tac_t<1024, true>(d, p, grid, lds, s);
+    if (p.only_flagged) p.only_flagged = static_cast<int32_t *>(d.d_work);   // (the block did not move: it was sized for this)
+    p.gstate = static_cast<char *>(d.d_work) + flag_bytes;
+    return launch_tac_t<1024, true>(d, p, gstate_grid, lds, s);
 }
 
 }  // namespace tictac
