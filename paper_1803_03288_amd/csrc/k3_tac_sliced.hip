@@ -37,11 +37,11 @@
 namespace tictac {
 
 constexpr int kPlanes = 13;             // bit planes of a count: up to 8191 recvs in a dep
-constexpr int kEvCap = 256;             // events of one round kept in LDS; further ones go to memory
+constexpr int kEvPerWave = 16;          // events of one round and worker wave kept in LDS; further ones go to memory
 constexpr int kWorkersMax = 15;         // worker waves per workgroup, next to the control wave
 
 enum : int { REQ_DONE = 0, REQ_QEMPTY = 1, REQ_MPLUS = 2, REQ_FLUSH = 3 };
-enum : int { CT_EVN = 0, CT_REQ = 1, CT_BEST = 2, CT_R1 = 3, CT_R2 = 4, CT_CIDX = 5, CT_WORDS = 16 };
+enum : int { CT_REQ = 1, CT_BEST = 2, CT_R1 = 3, CT_R2 = 4, CT_CIDX = 5, CT_WORDS = 16 };
 
 struct SlicedParams {
     int32_t B, R, W, C, CW, CWpad, N;
@@ -68,9 +68,9 @@ struct SlicedParams {
     size_t scratch_stride;
 };
 
-struct EvEntry {                    // 16 bytes
+struct EvEntry {                    // 16 bytes: a class that fell to one outstanding recv, that recv, the class time
     int32_t cls;
-    int32_t sole_rank;              // recv index | rank among the events with that recv << 13
+    int32_t sole;
     double ct;
 };
 
@@ -153,19 +153,23 @@ tac_sliced_kernel(const SlicedParams p)
     double *A0 = cbase + 64;                        // [1]      time of the classes that depend on no recv
     unsigned long long *cmin = reinterpret_cast<unsigned long long *>(A0 + 1);     // [2]  minima of M (bit patterns)
     // (R + R + 1 + 64 + 1 + 2 doubles: a multiple of 16 bytes)
-    EvEntry *ev = reinterpret_cast<EvEntry *>(cmin + 2);                            // [kEvCap]
-    uint64_t *alive = reinterpret_cast<uint64_t *>(ev + kEvCap);                    // [W]
+    EvEntry *ev = reinterpret_cast<EvEntry *>(cmin + 2);                            // [kWorkersMax][kEvPerWave]
+    uint64_t *alive = reinterpret_cast<uint64_t *>(ev + kWorkersMax * kEvPerWave);  // [W]
     uint64_t *Qb = alive + W;                                                       // [W] outstanding recvs with P > 0
     int32_t *ctrl = reinterpret_cast<int32_t *>(Qb + W);                            // [CT_WORDS]
-    uint16_t *ordl = reinterpret_cast<uint16_t *>(ctrl + CT_WORDS);                 // [R] the order so far
+    int32_t *evcnt = ctrl + CT_WORDS;                                               // [16] events of the round, per worker wave
+    uint16_t *ordl = reinterpret_cast<uint16_t *>(evcnt + 16);                      // [R] the order so far
     uint16_t *stage = ordl + R + (R & 1);                                           // [64] members of Q of the chunk being scanned
 
     // ---- per-workgroup memory ----
     char *scr = p.scratch + (size_t)blockIdx.x * p.scratch_stride;
     double *ct = reinterpret_cast<double *>(scr);                                   // [C]
     uint64_t *ndom = reinterpret_cast<uint64_t *>(ct + C);                          // [CWpad][2]
-    int2 *spill = reinterpret_cast<int2 *>(ndom + (size_t)2 * CWpad);              // [C] events beyond kEvCap: (class, recv)
-    uint64_t *live_pub = reinterpret_cast<uint64_t *>(spill + C);                   // [CWpad]
+    // events beyond kEvPerWave of one wave and round, (class, recv): a region per worker wave, as large as the
+    // number of its classes
+    int2 *spill = reinterpret_cast<int2 *>(ndom + (size_t)2 * CWpad);              // [kWorkersMax][64 * 64 * KW]
+    uint64_t *live_pub = reinterpret_cast<uint64_t *>(spill + (size_t)kWorkersMax * 4096 * KW);     // [CWpad]
+    constexpr int kSpillPerWave = 4096 * KW;
     uint32_t *ndom32 = reinterpret_cast<uint32_t *>(ndom);
 
     // ---- worker state: KW class words per lane ----
@@ -190,7 +194,7 @@ tac_sliced_kernel(const SlicedParams p)
             t[r] = x;
             zero_seen |= !(x > 0.0);
         }
-        if (tid < CT_WORDS) ctrl[tid] = 0;
+        if (tid < CT_WORDS) { ctrl[tid] = 0; evcnt[tid] = 0; }
         const bool literal = __syncthreads_or(zero_seen) != 0;
         if (tid == 0) p.flags[b] = literal ? 1 : 0;
         if (literal) continue;              // uniform over the workgroup
@@ -245,71 +249,50 @@ tac_sliced_kernel(const SlicedParams p)
                 lds_only_barrier();         // the events of the previous round are in the list
 
                 // ---- the events of the previous round: class times into P, new members of Q ----
-                const int n = __builtin_amdgcn_readfirstlane(ctrl[CT_EVN]);
-                if (n > kEvCap) TS_REQUEST(REQ_FLUSH)       // entries in memory: wait until they have arrived
-                if (n > 0 && n <= 64) {
-                    // one event per lane.  The class times of the events with one recv are added to its P in
-                    // ascending class: rank of every event among those with its recv, then one pass per rank.
-                    int cls = INT32_MAX, sole = -1;
+                // Every worker wave has left its events in a region of its own, in an order that depends on
+                // nothing but the state of the round.  They are taken wave by wave, 64 at a time: the events of a
+                // chunk that name one recv add their class times to its P one after the other, in list order, so
+                // the sums do not depend on which wave was first.
+                const int cnt_w = lane < n_workers ? evcnt[lane] : 0;
+                int incl_w = cnt_w;
+                incl_w += dpp_i32<0x111, 0xf>(0, incl_w);
+                incl_w += dpp_i32<0x112, 0xf>(0, incl_w);
+                incl_w += dpp_i32<0x114, 0xf>(0, incl_w);
+                incl_w += dpp_i32<0x118, 0xf>(0, incl_w);          // (at most fifteen workers: the first row of lanes)
+                const int n = __builtin_amdgcn_readlane(incl_w, 15);
+                if (wave_max_i32_dpp(cnt_w) > kEvPerWave) TS_REQUEST(REQ_FLUSH)   // entries in memory: wait until they have arrived
+                for (int base = 0; base < n; base += 64) {
+                    const int pos = base + lane;
+                    const int m = min(64, n - base);
+                    // the wave whose region holds position pos, and the offset in it
+                    int wv = 0, off = 0;
+                    for (int v = 0; v < n_workers; ++v) {
+                        const int end_v = __builtin_amdgcn_readlane(incl_w, v), cnt_v = __builtin_amdgcn_readlane(cnt_w, v);
+                        if (pos < end_v && pos >= end_v - cnt_v) { wv = v; off = pos - (end_v - cnt_v); }
+                    }
+                    int sole = -1;
                     double x = 0.0;
-                    if (lane < n) { cls = ev[lane].cls; sole = ev[lane].sole_rank; x = ev[lane].ct; }
-                    int rank = 0;
-                    for (int i = 0; i < n; ++i) {
-                        const int si = __builtin_amdgcn_readlane(sole, i), ci = __builtin_amdgcn_readlane(cls, i);
-                        rank += (si == sole && ci < cls) ? 1 : 0;
+                    if (lane < m) {
+                        if (off < kEvPerWave) {
+                            sole = ev[wv * kEvPerWave + off].sole;
+                            x = ev[wv * kEvPerWave + off].ct;
+                        } else {
+                            const int2 q = spill[(size_t)wv * kSpillPerWave + off - kEvPerWave];
+                            sole = q.y;
+                            x = ct[q.x];
+                        }
                     }
-                    const int maxrank = wave_max_i32_dpp(lane < n ? rank : 0);
+                    int rank = 0;                   // earlier events of the chunk with the same recv
+                    for (int i = 0; i < m; ++i) {
+                        const int si = __builtin_amdgcn_readlane(sole, i);
+                        rank += (si == sole && i < lane) ? 1 : 0;
+                    }
+                    const int maxrank = wave_max_i32_dpp(lane < m ? rank : 0);
                     for (int j = 0; j <= maxrank; ++j) {
-                        if (lane < n && rank == j) P[sole] += x;
+                        if (lane < m && rank == j) P[sole] += x;
                         wave_sync();
                     }
-                    if (lane < n && P[sole] > 0.0) atomicOr((unsigned long long *)&Qb[sole >> 6], 1ull << (sole & 63));
-                    if (lane == 0) ctrl[CT_EVN] = 0;
-                    wave_sync();
-                } else if (n > 0) {
-                    // rank of every event among those with the same recv, by class
-                    int maxrank = 0;
-                    for (int base = 0; base < n; base += 64) {
-                        const int e = base + lane;
-                        int cls = INT32_MAX, sole = -1;
-                        if (e < n) {
-                            if (e < kEvCap) { cls = ev[e].cls; sole = ev[e].sole_rank; }
-                            else { const int2 q = spill[e - kEvCap]; cls = q.x; sole = q.y; }
-                        }
-                        int rank = 0;
-                        const int n_lds = min(n, kEvCap);
-                        for (int i = 0; i < n_lds; ++i) rank += ((ev[i].sole_rank & 0x1fff) == sole && ev[i].cls < cls) ? 1 : 0;
-                        for (int i = kEvCap; i < n; ++i) {
-                            const int2 q = spill[i - kEvCap];
-                            rank += ((q.y & 0x1fff) == sole && q.x < cls) ? 1 : 0;
-                        }
-                        if (e < n) {
-                            if (e < kEvCap) ev[e].sole_rank = sole | (rank << 13);
-                            else spill[e - kEvCap].y = sole | (rank << 13);
-                        }
-                        maxrank = max(maxrank, wave_max_i32_dpp(e < n ? rank : 0));
-                    }
-                    wave_sync();
-                    if (n > kEvCap) wait_memory();
-                    for (int j = 0; j <= maxrank; ++j) {
-                        for (int base = 0; base < n; base += 64) {
-                            const int e = base + lane;
-                            if (e < n) {
-                                int sr;
-                                double x;
-                                if (e < kEvCap) { sr = ev[e].sole_rank; x = ev[e].ct; }
-                                else { const int2 q = spill[e - kEvCap]; sr = q.y; x = ct[q.x]; }
-                                if ((sr >> 13) == j) {
-                                    const int r = sr & 0x1fff;
-                                    const double np = P[r] + x;
-                                    P[r] = np;
-                                    if (np > 0.0) atomicOr((unsigned long long *)&Qb[r >> 6], 1ull << (r & 63));
-                                }
-                            }
-                        }
-                        wave_sync();
-                    }
-                    if (lane == 0) ctrl[CT_EVN] = 0;
+                    if (lane < m && P[sole] > 0.0) atomicOr((unsigned long long *)&Qb[sole >> 6], 1ull << (sole & 63));
                     wave_sync();
                 }
 
@@ -571,6 +554,7 @@ tac_sliced_kernel(const SlicedParams p)
                 const int best = __builtin_amdgcn_readfirstlane(ctrl[CT_BEST]);
 
                 // ================= the counts of the classes that hold `best`; events =================
+                int my_events = 0;              // events of this wave in this round (uniform)
                 uint64_t anyl = 0ull;
 #pragma unroll
                 for (int k = 0; k < KW; ++k) anyl |= live[k];
@@ -643,13 +627,14 @@ tac_sliced_kernel(const SlicedParams p)
                             TS_SOLE(0, x0) TS_SOLE(1, x1) TS_SOLE(2, x2) TS_SOLE(3, x3)
 #undef TS_SOLE
                             if (lane < nb) {
-                                const int idx = atomicAdd(&ctrl[CT_EVN], 1);
-                                if (idx < kEvCap) {
-                                    ev[idx].cls = myc;
-                                    ev[idx].sole_rank = mysole;
-                                    ev[idx].ct = ctv;
+                                const int idx = my_events + lane;
+                                if (idx < kEvPerWave) {
+                                    EvEntry *q = ev + (wave - 1) * kEvPerWave + idx;
+                                    q->cls = myc;
+                                    q->sole = mysole;
+                                    q->ct = ctv;
                                 } else {
-                                    spill[idx - kEvCap] = make_int2(myc, mysole);
+                                    spill[(size_t)(wave - 1) * kSpillPerWave + idx - kEvPerWave] = make_int2(myc, mysole);
                                 }
                                 // this class no longer keeps its children out of the minimum of M
                                 const int nch = rec.x;
@@ -661,9 +646,11 @@ tac_sliced_kernel(const SlicedParams p)
                                                            __HIP_MEMORY_SCOPE_AGENT);
                                 }
                             }
+                            my_events += nb;
                         }
                     }
                 }
+                if (lane == 0) evcnt[wave - 1] = my_events;
             }
         }
 
@@ -776,14 +763,14 @@ bool tac_sliced_fits(const Dag &d)
 
 static size_t sliced_lds_bytes(const Dag &d)
 {
-    size_t b = ((size_t)2 * d.R + 68) * 8 + (size_t)kEvCap * sizeof(EvEntry) + (size_t)2 * d.W * 8 + CT_WORDS * 4;
+    size_t b = ((size_t)2 * d.R + 68) * 8 + (size_t)kWorkersMax * kEvPerWave * sizeof(EvEntry) + (size_t)2 * d.W * 8 + (CT_WORDS + 16) * 4;
     b += ((size_t)d.R + (d.R & 1) + 64) * 2;
     return (b + 15) & ~(size_t)15;
 }
 
-static size_t tac_sliced_scratch_stride(const Dag &d)
+static size_t tac_sliced_scratch_stride(const Dag &d, int KW)
 {
-    const size_t b = (size_t)d.C * 8 + (size_t)d.CWpad * 16 + (size_t)d.C * 8 + (size_t)d.CWpad * 8;
+    const size_t b = (size_t)d.C * 8 + (size_t)d.CWpad * 16 + (size_t)kWorkersMax * 4096 * KW * 8 + (size_t)d.CWpad * 8;
     return (b + 255) & ~(size_t)255;
 }
 
@@ -809,7 +796,7 @@ static hipError_t launch_sliced_k(SlicedParams &p, Dag &d, const TacArgs &a, siz
     if (per_cu < 1) per_cu = 1;
     int grid = per_cu * device_cu_count(d.device);
     if (grid > a.B) grid = a.B;
-    p.scratch_stride = tac_sliced_scratch_stride(d);
+    p.scratch_stride = tac_sliced_scratch_stride(d, KW);
     e = ensure_workspace(&d, flag_bytes + p.scratch_stride * (size_t)grid);
     if (e != hipSuccess) return e;
     p.flags = static_cast<int32_t *>(d.d_work);
