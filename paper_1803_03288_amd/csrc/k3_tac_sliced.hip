@@ -261,7 +261,7 @@ tac_sliced_kernel(const SlicedParams p)
                 incl_w += dpp_i32<0x118, 0xf>(0, incl_w);          // (at most fifteen workers: the first row of lanes)
                 const int n = __builtin_amdgcn_readlane(incl_w, 15);
                 if (wave_max_i32_dpp(cnt_w) > kEvPerWave) TS_REQUEST(REQ_FLUSH)   // entries in memory: wait until they have arrived
-                for (int base = 0; base < n; base += 64) {
+                for (int base = 0; base < n; base += 64) {      // (no event: nothing to do)
                     const int pos = base + lane;
                     const int m = min(64, n - base);
                     // the wave whose region holds position pos, and the offset in it
@@ -339,9 +339,10 @@ tac_sliced_kernel(const SlicedParams p)
                     int s_mpb_ok = 0;
                     bool scanned = false;
                     if (nq <= 64) {
-                        // One member of Q per lane.  Every lane finds, as if it were the best so far, the first
-                        // later member that would replace it (or that ties with it); the scan is then the walk
-                        // from member 0 along these links.  A tie on the way is left to the loop below.
+                        // One member of Q per lane.  The scan replaces its best so far by the first later member
+                        // that precedes it: all later members are compared with the best at once, and the scan
+                        // jumps to the first that precedes it, until none does.  A tie met before that is left to
+                        // the loop below.
                         {
                             int rk = first_rank;
                             uint64_t x = q_l;
@@ -355,20 +356,17 @@ tac_sliced_kernel(const SlicedParams p)
                         const int a_l = lane < nq ? (int)stage[lane] : 0;
                         const double P_l = P[a_l], t_l = t[a_l];
                         wave_sync();
-                        int link = 64;              // first later member that precedes this one; + 128: ties with it
-                        for (int j = 1; j < nq; ++j) {
-                            const double Pj = readlane_f64(P_l, j), tj = readlane_f64(t_l, j);
-                            const double xa = fmin(P_l, tj);                // min{P_B, M_A}: A = member j, B = this lane's
-                            const double ya = fmin(Pj, t_l);                // min{P_A, M_B}
-                            const bool open = j > lane && link == 64;
-                            link = (open && xa < ya) ? j : link;
-                            link = (open && xa == ya) ? j + 128 : link;
-                        }
                         int cur = 0;
                         for (;;) {
-                            const int nx = __builtin_amdgcn_readlane(link, cur);
-                            if (nx >= 64) { scanned = nx == 64; break; }
-                            cur = nx;
+                            const double Pc = readlane_f64(P_l, cur), tc = readlane_f64(t_l, cur);
+                            const double xa = fmin(Pc, t_l);                // min{P_B, M_A}: A = this lane's member, B = the best
+                            const double ya = fmin(P_l, tc);                // min{P_A, M_B}
+                            const bool later = lane > cur && lane < nq;
+                            const uint64_t lt = __ballot(later && xa < ya), eq = __ballot(later && xa == ya);
+                            const int first_lt = lt ? __builtin_ctzll(lt) : 64, first_eq = eq ? __builtin_ctzll(eq) : 64;
+                            if (first_eq < first_lt) break;                 // a tie comes first
+                            if (first_lt == 64) { scanned = true; break; }
+                            cur = first_lt;
                         }
                         if (scanned) s_best = __builtin_amdgcn_readlane(a_l, cur);
                     }
