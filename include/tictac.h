@@ -161,6 +161,23 @@ int tictac_tac_simulate(const tictac_dag *dag, int32_t B, const double *op_time,
                         tictac_stream stream);
 
 /*
+ * tictac_tac_simulate for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The call allocates nothing, neither on the
+ * first call nor later: the one flag per sample that its kernels pass between them lives in an array
+ * that is part of the library itself (4 MiB per GPU, held until the process ends).
+ *   - at most 2^20 samples per call, and only graphs that the wave-per-sample kernels serve (at
+ *     most 384 recvs and 512 classes of compute ops with identical dependency sets); anything else:
+ *     TICTAC_ERR_UNSUPPORTED and nothing is written;
+ *   - every call on one GPU uses the same array, so calls that overlap in time on one GPU (on
+ *     different streams or from different threads) race; calls on one stream do not;
+ *   - no per-round outputs (sel_P, sel_Mplus); everything else as in tictac_tac_simulate, and the
+ *     results are the same.
+ */
+int tictac_tac_simulate_noalloc(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                                int32_t *order, int32_t *rank, double *makespan, double *eff, double *U, double *L,
+                                double *S, tictac_stream stream);
+
+/*
  * The two calls above with the timing arrays stored as float32 (half the bytes of the pass over
  * the samples).  Every value is converted to float64 when it is loaded and all sums and
  * comparisons are float64, so the results are those of the float64 calls on the converted values:

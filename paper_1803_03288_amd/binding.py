@@ -30,6 +30,7 @@ EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
+    "tictac_tac_simulate_noalloc",
     "tictac_simulate_f32", "tictac_tac_simulate_f32",
     "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min", "tictac_order_search",
     "tictac_last_error", "tictac_version",
@@ -254,6 +255,20 @@ def tac_simulate(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, want_
     _check(fn(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order), _dev(rank), _dev(sel_P),
               _dev(sel_M), *(_dev(o) for o in out), _stream()))
     return (order, rank, sel_P, sel_M) + tuple(out)
+
+
+def tac_simulate_noalloc(dag: Dag, op_time: torch.Tensor, recv_time: torch.Tensor, out: Tuple[torch.Tensor, ...]):
+    """``tictac_tac_simulate_noalloc``: the call that allocates nothing.  ``out`` are the caller's tensors
+    ``(order [B][R] int32, rank [B][R] int32 or None, makespan, eff, U, L, S [B] float64)``; they are
+    written and returned."""
+    B = _check_times(dag, op_time, recv_time)
+    order, rank, m, e, U, L, S = out
+    assert order.dtype == torch.int32 and tuple(order.shape) == (B, dag.n_recv) and order.is_contiguous()
+    for x in (m, e, U, L, S):
+        assert x.dtype == torch.float64 and tuple(x.shape) == (B,) and x.is_contiguous()
+    _check(lib().tictac_tac_simulate_noalloc(dag._h, ctypes.c_int32(B), _dev(op_time), _dev(recv_time), _dev(order),
+                                             _dev(rank), _dev(m), _dev(e), _dev(U), _dev(L), _dev(S), _stream()))
+    return out
 
 
 def version() -> str:

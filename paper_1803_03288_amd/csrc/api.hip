@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <numeric>
 
 #include "internal.h"
@@ -794,6 +795,61 @@ static int tac_simulate_any(const tictac_dag *dag, int32_t B, const void *op_tim
     TacArgs a{B, op_time, recv_time, order, rank, sel_P, sel_Mplus, true, makespan, eff, U, L, S};
     a.f32 = f32;
     HIP_TRY(launch_tac(*d, a, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+// ---- the entry point that allocates nothing ----
+// Per-call memory of tictac_tac_simulate_noalloc: one flag per sample ("left to the general kernel").  The
+// array exists once per GPU for as long as the library is loaded; every call on a GPU uses it.
+constexpr int32_t kNoallocMaxB = 1 << 20;
+static __device__ __align__(256) int32_t scratch[kNoallocMaxB];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];         // device address of `scratch` on every device, 0 = not asked yet
+static std::mutex g_scratch_mutex;
+
+// the device address of the array on the current device (asked of the runtime once per device)
+static hipError_t scratch_address(int32_t **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = q;
+    }
+    *out = static_cast<int32_t *>(g_scratch_ptr[dev]);
+    return hipSuccess;
+}
+
+int tictac_tac_simulate_noalloc(const tictac_dag *dag, int32_t B, const double *op_time, const double *recv_time,
+                                int32_t *order, int32_t *rank, double *makespan, double *eff, double *U, double *L,
+                                double *S, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (B > kNoallocMaxB) {
+        set_error("B = %d: tictac_tac_simulate_noalloc takes at most %d samples per call", B, kNoallocMaxB);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    if (B == 0) return TICTAC_OK;
+    if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    int32_t *flags = nullptr;
+    HIP_TRY(scratch_address(&flags));
+    TacArgs a{B, op_time, recv_time, order, rank, nullptr, nullptr, true, makespan, eff, U, L, S};
+    a.ext_flags = flags;
+    const hipError_t e = launch_tac(*d, a, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) {
+        set_error("%d recvs, %d classes: tictac_tac_simulate_noalloc serves graphs with at most 512 classes of compute ops, "
+                  "384 recvs and per-sample state that fits the local memory of a compute unit", d->R, d->C);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    HIP_TRY(e);
     return TICTAC_OK;
 }
 

@@ -144,6 +144,9 @@ struct TacArgs {
     bool simulate;
     double *makespan, *eff, *U, *L, *S;
     bool f32 = false;
+    // when not NULL: one flag per sample in memory that the caller provides, and nothing may be allocated:
+    // graphs whose kernels need more per-call memory than that are refused (hipErrorNotSupported)
+    int32_t *ext_flags = nullptr;
 };
 hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s);
 // LDS bytes of the general TAC kernel with the per-sample state in LDS; graphs for which this is at most

@@ -415,6 +415,16 @@ hipError_t launch_tac(Dag &d, const TacArgs &a, hipStream_t s)
     const bool gstate = lds_small > 150 * 1024;                     // state in global memory
     const int gstate_grid = a.B < 256 ? a.B : 256;
     const size_t gstate_bytes = gstate ? tac_gstate_bytes(d) * (size_t)gstate_grid : 0;
+    if (a.ext_flags) {
+        // the caller's flags, no workspace: the register-resident kernel, then the one-wave kernel with its
+        // state in LDS for the samples that were flagged
+        if (a.sel_P || a.sel_Mplus || !small || !(d.C <= 8 * 64 && d.W <= 6)) return hipErrorNotSupported;
+        const hipError_t e = launch_tac_reg(d, a, a.ext_flags, s);
+        if (e != hipSuccess) return e;
+        p.only_flagged = a.ext_flags;
+        const int grid = a.B < 256 * 16 ? a.B : 256 * 16;
+        return launch_tac_t<64, false>(d, p, grid, lds_small, s);
+    }
     if (!a.sel_P && !a.sel_Mplus && d.C <= 8 * 64 && d.W <= 6) {
         hipError_t e = ensure_workspace(&d, flag_bytes + gstate_bytes);
         if (e != hipSuccess) return e;
