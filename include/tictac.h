@@ -99,6 +99,13 @@ int tictac_dag_copy_deps(const tictac_dag *dag, uint64_t *dst_device, tictac_str
  * Asynchronous on the stream. */
 int tictac_dag_recompute_deps(tictac_dag *dag, tictac_stream stream);
 
+/* The same for n_dags handles at once (Sec. 4.1, the propagation of tictac_build_deps).  One graph is a
+ * chain of dependent levels and leaves most of the chip idle; handles of graphs of one shape (as several
+ * handles of one graph are) are propagated side by side by a single launch, any others one after the
+ * other.  Every handle's op.dep is overwritten with the same values.  Asynchronous on the stream; the
+ * handles must not be used by other calls meanwhile. */
+int tictac_dag_recompute_deps_batch(tictac_dag *const *dags, int32_t n_dags, tictac_stream stream);
+
 int tictac_dag_free(tictac_dag *dag);
 
 /*

@@ -28,6 +28,7 @@ STATUS = {
 
 EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
+    "tictac_dag_recompute_deps_batch",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
     "tictac_tac_simulate_noalloc",
@@ -98,6 +99,19 @@ class Dag:
         _check(lib().tictac_dag_copy_deps(self._h, _dev(out), _stream()))
         return out
 
+    def deps_view(self) -> torch.Tensor:
+        """The handle's own op.dep (``tictac_dag_deps``, borrowed) as an int64 CUDA tensor ``[n_ops][W]``: writes
+        through it change the handle.  Valid until ``close``."""
+        ptr = ctypes.c_void_p()
+        _check(lib().tictac_dag_deps(self._h, ctypes.byref(ptr)))
+        n = self.n_ops * self.words
+        if n == 0 or not ptr.value:
+            return torch.empty((self.n_ops, self.words), dtype=torch.int64, device="cuda")
+        iface = {"shape": (self.n_ops, self.words), "typestr": "<i8", "data": (ptr.value, False), "version": 2,
+                 "strides": None}
+        holder = type("_Borrowed", (), {"__cuda_array_interface__": iface})()
+        return torch.as_tensor(holder, device="cuda")
+
     def recompute_deps(self) -> None:
         """``tictac_dag_recompute_deps``: run the propagation kernel again (for timing)."""
         _check(lib().tictac_dag_recompute_deps(self._h, _stream()))
@@ -112,6 +126,12 @@ class Dag:
             self.close()
         except Exception:
             pass
+
+
+def recompute_deps_batch(dags) -> None:
+    """``tictac_dag_recompute_deps_batch``: the propagation kernel for several handles in one launch."""
+    arr = (ctypes.c_void_p * len(dags))(*[d._h for d in dags])
+    _check(lib().tictac_dag_recompute_deps_batch(arr, ctypes.c_int32(len(dags)), _stream()))
 
 
 def build_deps(n_ops: int, row_ptr, col_idx, recv_ids) -> Dag:

@@ -398,11 +398,14 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         while (ring < M && (ring < 2 * kK1Rpt * per_pass || (size_t)ring * 2 * d->k1_wc * 8 <= 64 * 1024)) ring *= 2;
         d->k1_ring = ring;
         // level-major records (see internal.h): when a workgroup has more than one wave, the padding at
-        // most quadruples the records, and sixteen levels of slots fit a ring of 64 KB
+        // most quadruples the records, and sixteen levels of slots fit the ring: at most 64 KB, and 32 KB for
+        // one-word slices (many narrow workgroups: four of them then share a compute unit when several
+        // graphs are propagated by one launch)
         int32_t lring = 0;
         if (max_width <= per_pass && threads > 64 && (int64_t)n_node_levels * per_pass <= (int64_t)4 * M + 8192) {
+            const size_t ring_cap = d->k1_wc == 1 ? 32 * 1024 : 64 * 1024;
             lring = 64;
-            while ((size_t)lring * 2 * d->k1_wc * 8 <= 64 * 1024 && lring < n_node_levels * per_pass) lring *= 2;
+            while ((size_t)lring * 2 * d->k1_wc * 8 <= ring_cap && lring < n_node_levels * per_pass) lring *= 2;
             if (lring < 16 * per_pass && lring < n_node_levels * per_pass) lring = 0;
         }
         d->k1_lring = lring;
@@ -740,6 +743,26 @@ int tictac_dag_recompute_deps(tictac_dag *dag, tictac_stream stream)
     if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
     Dag *d = reinterpret_cast<Dag *>(dag);
     HIP_TRY(launch_propagate(*d, (hipStream_t)stream));
+    return TICTAC_OK;
+}
+
+int tictac_dag_recompute_deps_batch(tictac_dag *const *dags, int32_t n_dags, tictac_stream stream)
+{
+    if (n_dags < 0) { set_error("n_dags = %d is negative", n_dags); return TICTAC_ERR_UNSUPPORTED; }
+    if (n_dags == 0) return TICTAC_OK;
+    if (!dags) { set_error("dags is NULL"); return TICTAC_ERR_NULL; }
+    for (int32_t g = 0; g < n_dags; ++g)
+        if (!dags[g]) { set_error("dags[%d] is NULL", g); return TICTAC_ERR_NULL; }
+    Dag *const *ds = reinterpret_cast<Dag *const *>(dags);
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(ensure_workspace(ds[0], propagate_batch_staging_bytes(n_dags)));
+    const hipError_t e = launch_propagate_batch(ds, n_dags, ds[0]->d_work, s);
+    if (e == hipErrorNotSupported) {
+        // graphs of different shapes, or graphs that take another propagation kernel: one after the other
+        for (int32_t g = 0; g < n_dags; ++g) HIP_TRY(launch_propagate(*ds[g], s));
+        return TICTAC_OK;
+    }
+    HIP_TRY(e);
     return TICTAC_OK;
 }
 

@@ -130,6 +130,9 @@ hipError_t cached_blocks_per_cu(int *per_cu, const void *kernel, int threads, si
 
 // op.dep for every op (Sec. 4.1)
 hipError_t launch_propagate(const Dag &d, hipStream_t s);
+// the same for G graphs of one launch shape in one launch; staging: device memory of propagate_batch_staging_bytes(G)
+size_t propagate_batch_staging_bytes(int G);
+hipError_t launch_propagate_batch(Dag *const *ds, int G, void *staging, hipStream_t s);
 
 // TIC (Sec. 4.2): prio always; order / rank when not NULL
 hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank, int32_t *scratch_prio,

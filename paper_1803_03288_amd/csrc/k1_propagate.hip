@@ -46,11 +46,8 @@ constexpr int LVL_CHUNK = 512;
 // different XCDs (eight of them, each with an L2 of its own); when the number of slices is a
 // multiple of eight, the slices are dealt so that every XCD gets a run of adjacent slices
 // and the narrow stores of one row meet in one L2 before they are written back.
-__device__ __forceinline__ int slice_of_block()
-{
-    const int b = blockIdx.x, n = gridDim.x;
-    return (n & 7) == 0 ? (b & 7) * (n >> 3) + (b >> 3) : b;
-}
+__device__ __forceinline__ int slice_of(int b, int n) { return (n & 7) == 0 ? (b & 7) * (n >> 3) + (b >> 3) : b; }
+__device__ __forceinline__ int slice_of_block() { return slice_of(blockIdx.x, gridDim.x); }
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void drain_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -463,14 +460,14 @@ struct LevelParams {
 
 #define KL_EACH(F) F(0) F(1) F(2) F(3) F(4) F(5) F(6) F(7)
 
+// `block` of `n_blocks`: which slice of the graph this workgroup takes (its index in a launch for one graph;
+// in a launch for several graphs, its index among the workgroups of its graph)
 template <int WC>
-__global__ void __launch_bounds__(1024)
-propagate_levels(const LevelParams p)
+__device__ __forceinline__ void propagate_levels_body(const LevelParams &p, uint64_t *ring, int block, int n_blocks)
 {
-    extern __shared__ uint64_t ring[];          // rows [ring + 2][WC] (the last two all zero), then the input lists
     const int W = p.W, L = p.n_levels, P = p.P;
     const int w = threadIdx.x % WC, sub = threadIdx.x / WC;
-    const int gw = slice_of_block() * WC + w;
+    const int gw = slice_of(block, n_blocks) * WC + w;
     const uint32_t rmask = (uint32_t)p.ring - 1u;
     int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * WC);
     if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
@@ -487,7 +484,7 @@ propagate_levels(const LevelParams p)
 #define KL_DECL(i) int4 a##i, b##i; KL_LOAD(a##i, b##i, i)
     KL_EACH(KL_DECL)
 
-    uint64_t *const sink = p.sink + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t *const sink = p.sink + (size_t)block * blockDim.x + threadIdx.x;
     // (the next record of a set is requested after the last use of the set, into the same registers)
 #define KL_STEP(i)                                                                        \
     {                                                                                     \
@@ -528,6 +525,26 @@ propagate_levels(const LevelParams p)
 #undef KL_LOAD
 }
 
+template <int WC>
+__global__ void __launch_bounds__(1024)
+propagate_levels(const LevelParams p)
+{
+    extern __shared__ uint64_t ring[];          // rows [ring + 2][WC] (the last two all zero), then the input lists
+    propagate_levels_body<WC>(p, ring, blockIdx.x, gridDim.x);
+}
+
+// Several graphs of one launch shape in one launch: workgroup b takes slice b % blocks_per of graph b / blocks_per.
+// (One graph is a chain of dependent levels and cannot fill the chip; independent graphs side by side can.)
+template <int WC>
+__global__ void __launch_bounds__(1024)
+propagate_levels_batch(const LevelParams *__restrict__ ps, int blocks_per)
+{
+    extern __shared__ uint64_t ring[];
+    const int g = blockIdx.x / blocks_per;
+    const LevelParams p = ps[g];
+    propagate_levels_body<WC>(p, ring, blockIdx.x - g * blocks_per, blocks_per);
+}
+
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto
 __global__ void __launch_bounds__(256)
 expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep)
@@ -542,6 +559,85 @@ expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep
     } else if (s != v) {
         dep[idx] = dep[(size_t)s * W + w];
     }
+}
+
+// the same for several graphs: blockIdx.y = graph
+struct ExpandParams {
+    int32_t n, W;
+    const int32_t *src;
+    uint64_t *dep;
+};
+__global__ void __launch_bounds__(256)
+expand_rows_batch(const ExpandParams *__restrict__ ps)
+{
+    const ExpandParams p = ps[blockIdx.y];
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)p.n * p.W) return;
+    const int v = (int)(idx / p.W), w = (int)(idx % p.W);
+    const int s = p.src[v];
+    if (s < 0) {
+        const int i = ~s;
+        p.dep[idx] = (i >> 6) == w ? 1ull << (i & 63) : 0ull;
+    } else if (s != v) {
+        p.dep[idx] = p.dep[(size_t)s * p.W + w];
+    }
+}
+
+static bool level_params(const Dag &d, int WC, LevelParams *q, size_t *lds)
+{
+    if (!d.d_lrecs || !d.d_k1_sink || d.k1_wc != WC) return false;
+    q->n_levels = d.n_node_levels; q->W = d.W; q->P = d.k1_threads / WC; q->ring = d.k1_lring;
+    q->lrecs = d.d_lrecs; q->lfovf = d.d_lfovf; q->dep = d.d_dep; q->sink = d.d_k1_sink;
+    q->lfovf_lds = d.lfovf_len <= 4096 ? d.lfovf_len : 0;
+    *lds = (size_t)(d.k1_lring + 2) * WC * 8 + (size_t)q->lfovf_lds * 4;
+    return *lds <= 150 * 1024;
+}
+
+// Propagation for G graphs that all take the level-major kernel with one launch shape (as G handles of one
+// graph do): one launch of the node kernel, one of the copies.  `staging`: device memory for G parameter records
+// of each kind (filled here, stream-ordered).  hipErrorNotSupported when the graphs do not fit that description.
+template <int WC>
+static hipError_t launch_levels_batch(Dag *const *ds, int G, void *staging, hipStream_t s)
+{
+    std::vector<LevelParams> lp(G);
+    std::vector<ExpandParams> ep(G);
+    size_t lds0 = 0;
+    for (int g = 0; g < G; ++g) {
+        size_t lds = 0;
+        if (!level_params(*ds[g], WC, &lp[g], &lds)) return hipErrorNotSupported;
+        if (g == 0) lds0 = lds;
+        if (lds != lds0 || ds[g]->k1_threads != ds[0]->k1_threads || ds[g]->W != ds[0]->W || ds[g]->n != ds[0]->n)
+            return hipErrorNotSupported;
+        ep[g] = ExpandParams{ds[g]->n, ds[g]->W, ds[g]->d_src, ds[g]->d_dep};
+    }
+    LevelParams *d_lp = static_cast<LevelParams *>(staging);
+    ExpandParams *d_ep = reinterpret_cast<ExpandParams *>(d_lp + G);
+    hipError_t e = hipMemcpyAsync(d_lp, lp.data(), sizeof(LevelParams) * G, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    e = hipMemcpyAsync(d_ep, ep.data(), sizeof(ExpandParams) * G, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    if (lds0 > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_levels_batch<WC>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds0);
+        if (e != hipSuccess) return e;
+    }
+    const Dag &d0 = *ds[0];
+    const int blocks_per = (d0.W + WC - 1) / WC;
+    hipLaunchKernelGGL(propagate_levels_batch<WC>, dim3(blocks_per * G), dim3(d0.k1_threads), lds0, s, d_lp, blocks_per);
+    const size_t total = (size_t)d0.n * d0.W;
+    hipLaunchKernelGGL(expand_rows_batch, dim3((unsigned)((total + 255) / 256), G), dim3(256), 0, s, d_ep);
+    return hipGetLastError();
+}
+
+size_t propagate_batch_staging_bytes(int G) { return (sizeof(LevelParams) + sizeof(ExpandParams)) * (size_t)G; }
+
+hipError_t launch_propagate_batch(Dag *const *ds, int G, void *staging, hipStream_t s)
+{
+    if (G <= 0) return hipSuccess;
+    if (ds[0]->n == 0 || ds[0]->W == 0 || ds[0]->M == 0) return hipErrorNotSupported;
+    if (ds[0]->k1_wc == 1) return launch_levels_batch<1>(ds, G, staging, s);
+    if (ds[0]->k1_wc == 2) return launch_levels_batch<2>(ds, G, staging, s);
+    return launch_levels_batch<4>(ds, G, staging, s);
 }
 
 template <int WC>

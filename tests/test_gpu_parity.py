@@ -104,6 +104,28 @@ def test_deps_and_tic_bit_exact(tt, name):
     assert h.n_classes == np.unique(rows, axis=0).shape[0]
 
 
+@pytest.mark.parametrize("name", ["stress", "deep_w1", "deep_w2", "resnet50", "tiny"])
+def test_deps_of_several_handles_in_one_launch(tt, name):
+    """tictac_dag_recompute_deps_batch: the bitsets of several handles, cleared first, are propagated again by
+    one call (one launch where the graphs take the level-major kernel, one after the other elsewhere) and
+    equal the oracle's; so do those of the single-handle call."""
+    d, h, dep = get(tt, name, SMALL.get(name))
+    hs = [tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids) for _ in range(3)]
+    for x in hs:
+        x.deps_view().zero_()
+    tt.recompute_deps_batch(hs)
+    for x in hs:
+        assert np.array_equal(x.deps().cpu().numpy().view(np.uint64), dep)
+    hs[1].deps_view().fill_(-1)
+    hs[1].recompute_deps()
+    assert np.array_equal(hs[1].deps().cpu().numpy().view(np.uint64), dep)
+    tt.recompute_deps_batch(hs[:1])
+    tt.recompute_deps_batch([])
+    assert np.array_equal(hs[0].deps().cpu().numpy().view(np.uint64), dep)
+    for x in hs:
+        x.close()
+
+
 def test_no_recvs_and_empty_graph(tt):
     d = wl.no_recv_dag(17)
     h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
