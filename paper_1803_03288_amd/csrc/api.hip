@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <mutex>
 #include <numeric>
+#include <unordered_map>
 
 #include "internal.h"
 
@@ -121,6 +122,28 @@ int device_cu_count(int device)
     known_device = device;
     known_count = n;
     return n;
+}
+
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes)
+{
+    // (one table for the process: the attribute belongs to the kernel on a device, not to a thread)
+    struct Entry { int device; const void *kernel; size_t bytes; };
+    static std::vector<Entry> known;
+    static std::mutex mutex;
+    int device = 0;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) return err;
+    std::lock_guard<std::mutex> lock(mutex);
+    for (Entry &e : known)
+        if (e.kernel == kernel && e.device == device) {
+            if (bytes <= e.bytes) return hipSuccess;
+            err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (err == hipSuccess) e.bytes = bytes;
+            return err;
+        }
+    err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (err == hipSuccess) known.push_back({device, kernel, bytes});
+    return err;
 }
 
 hipError_t cached_blocks_per_cu(int *per_cu, const void *kernel, int threads, size_t lds)
@@ -409,47 +432,133 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             if (lring < 16 * per_pass && lring < n_node_levels * per_pass) lring = 0;
         }
         d->k1_lring = lring;
-        if (lring > 0) {
-            const int32_t P = per_pass, row_bytes = d->k1_wc * 8, zero_row = lring * row_bytes;
+        // Rows of a multiple of eight words, levels of at most 256 nodes: also the records of the kernel with
+        // 64-byte slices (four lanes per slot; P slots per level, a multiple of 16 so that the slots of a wave are
+        // whole; 2048 slots in the ring), which the propagation of several graphs by one launch takes.
+        int32_t q_slots = (max_width + 15) / 16 * 16, q_ring = 0;
+        if (q_slots < 16) q_slots = 16;
+        if (d->k1_wc == 1 && d->W % 8 == 0 && d->W <= 1016 && max_width <= 256 && M > 0 &&
+            (int64_t)n_node_levels * q_slots <= (int64_t)4 * M + 8192) {
+            q_ring = 2048;
+            while (q_ring > 64 && q_ring / 2 >= n_node_levels * q_slots) q_ring /= 2;
+            if (q_ring < 4 * q_slots && q_ring < n_node_levels * q_slots) q_ring = 0;
+        }
+        d->k1_q_ring = q_ring;
+        d->k1_q_threads = q_ring > 0 ? 4 * q_slots : 0;
+        // Level-major records, of either kind.  While level l is computed the ring holds the slots from
+        // (l + 1) * P - ring on.  With 64-byte slices that is few levels, and a row that a later level needs is
+        // handed on by copy nodes (op = -2: one input, the row goes to the ring only) in free slots of the levels
+        // between, each within reach of the one before; the copies of a row form one chain, which the consumers,
+        // taken level by level, extend.
+        auto level_major = [&](bool quad, int32_t P, int32_t lring, std::vector<Dag::FastRec> &lrecs,
+                               std::vector<Dag::QuadRec> &qrecs, std::vector<int32_t> &lfovf) {
+            const int32_t row_bytes = d->k1_wc * 8, zero_row = lring * row_bytes;
             std::vector<int32_t> slot_of(M);            // position -> slot
             for (int32_t l = 0; l < n_node_levels; ++l)
                 for (int32_t q = nlvl_ptr[l]; q < nlvl_ptr[l + 1]; ++q) slot_of[q] = l * P + (q - nlvl_ptr[l]);
-            Dag::FastRec none;
-            for (int j = 0; j < 4; ++j) none.in[j] = zero_row;
-            none.rcv[0] = none.rcv[1] = -1;
-            none.op = -1;
-            none.ovf = -1;
-            std::vector<Dag::FastRec> lrecs((size_t)n_node_levels * P, none);
-            std::vector<int32_t> lfovf;
+            if (quad) {
+                const uint32_t zero2 = (uint32_t)lring | (uint32_t)lring << 16;
+                qrecs.assign((size_t)n_node_levels * P, Dag::QuadRec{zero2, zero2, 0xffffffffu, -1});
+            } else {
+                Dag::FastRec none;
+                for (int j = 0; j < 4; ++j) none.in[j] = zero_row;
+                none.rcv[0] = none.rcv[1] = -1;
+                none.op = -1;
+                none.ovf = -1;
+                lrecs.assign((size_t)n_node_levels * P, none);
+            }
+            const int32_t reach = lring / P - 1;        // a row of level x is in the ring up to level x + reach
+            std::vector<int32_t> used(n_node_levels);
+            for (int32_t l = 0; l < n_node_levels; ++l) used[l] = nlvl_ptr[l + 1] - nlvl_ptr[l];
+            std::unordered_map<int32_t, std::vector<int32_t>> chain;       // slot of a row -> slots of its copies
+            auto within_reach = [&](int32_t slot, int32_t l) -> int32_t {   // the slot to read at level l, or -1
+                if ((int64_t)slot >= (int64_t)(l + 1) * P - lring) return slot;
+                if (!quad || reach < 1 || l - slot / P > 8 * reach) return -1;
+                std::vector<int32_t> &ch = chain[slot];
+                int32_t cur = ch.empty() ? slot : ch.back();
+                while (l - cur / P > reach) {
+                    int32_t t = cur / P + reach;
+                    while (t > cur / P && used[t] >= P) --t;
+                    if (t == cur / P) return -1;
+                    const int32_t c = t * P + used[t]++;
+                    qrecs[c].in01 = (uint32_t)(cur & (lring - 1)) | (uint32_t)lring << 16;
+                    qrecs[c].op = -2;
+                    ch.push_back(c);
+                    cur = c;
+                }
+                return cur;
+            };
+            std::vector<int32_t> src_slot;
             for (int32_t l = 0; l < n_node_levels; ++l)
                 for (int32_t q = nlvl_ptr[l]; q < nlvl_ptr[l + 1]; ++q) {
                     const Dag::NodeRec &r = nodes[q];
-                    Dag::FastRec &f = lrecs[slot_of[q]];
                     tmp.clear();
                     for (int j = 0; j < 6; ++j) if (r.in[j] != INT32_MIN) tmp.push_back(r.in[j]);
                     if (r.ovf_beg >= 0)
                         for (int32_t e = 1; e <= ovf_idx[r.ovf_beg]; ++e) tmp.push_back(ovf_idx[r.ovf_beg + e]);
                     int nn = 0, nr = 0;
-                    bool resident = true;       // every node input is still in the ring while level l is computed
                     for (int32_t &x : tmp) {
                         if (x < 0) { ++nr; continue; }
                         ++nn;
                         x = slot_of[x];
-                        resident = resident && (int64_t)x >= (int64_t)(l + 1) * P - lring;
                     }
-                    f.op = r.op;
-                    if (nn <= 4 && nr <= 2 && resident) {
-                        int a = 0, b = 0;
+                    // (copies are made only for a node that then fits a record)
+                    bool resident = nn <= 4 && nr <= 2;
+                    src_slot.clear();
+                    if (resident)
                         for (int32_t x : tmp) {
-                            if (x < 0) f.rcv[b++] = ~x;
-                            else f.in[a++] = (x & (lring - 1)) * row_bytes;
+                            if (x < 0) continue;
+                            const int32_t c = within_reach(x, l);
+                            if (c < 0) { resident = false; break; }
+                            src_slot.push_back(c);
+                        }
+                    if (quad) {
+                        Dag::QuadRec &f = qrecs[slot_of[q]];
+                        f.op = r.op;
+                        if (resident) {
+                            uint32_t in[4] = {(uint32_t)lring, (uint32_t)lring, (uint32_t)lring, (uint32_t)lring};
+                            uint32_t rc[2] = {0xffffu, 0xffffu};
+                            int a = 0, b = 0;
+                            for (int32_t x : tmp) if (x < 0) rc[b++] = (uint32_t)~x;
+                            for (int32_t c : src_slot) in[a++] = (uint32_t)(c & (lring - 1));
+                            f.in01 = in[0] | in[1] << 16;
+                            f.in23 = in[2] | in[3] << 16;
+                            f.rcv01 = rc[0] | rc[1] << 16;
+                        } else {
+                            f.in01 = 0xffffffffu;
+                            f.in23 = (uint32_t)lfovf.size();
                         }
                     } else {
-                        f.ovf = (int32_t)lfovf.size();
+                        Dag::FastRec &f = lrecs[slot_of[q]];
+                        f.op = r.op;
+                        if (resident) {
+                            int a = 0, b = 0;
+                            for (int32_t x : tmp) if (x < 0) f.rcv[b++] = ~x;
+                            for (int32_t c : src_slot) f.in[a++] = (c & (lring - 1)) * row_bytes;
+                        } else {
+                            f.ovf = (int32_t)lfovf.size();
+                        }
+                    }
+                    if (!resident) {
                         lfovf.push_back((int32_t)tmp.size());
                         lfovf.insert(lfovf.end(), tmp.begin(), tmp.end());
                     }
                 }
+        };
+        if (q_ring > 0) {
+            std::vector<Dag::FastRec> unused;
+            std::vector<Dag::QuadRec> qrecs;
+            std::vector<int32_t> qfovf;
+            level_major(true, q_slots, q_ring, unused, qrecs, qfovf);
+            graph.add(&d->d_qrecs, qrecs);
+            graph.add(&d->d_qfovf, qfovf);
+            d->qfovf_len = (int32_t)qfovf.size();
+        }
+        if (lring > 0) {
+            std::vector<Dag::FastRec> lrecs;
+            std::vector<Dag::QuadRec> unused;
+            std::vector<int32_t> lfovf;
+            level_major(false, per_pass, lring, lrecs, unused, lfovf);
             graph.add(&d->d_lrecs, lrecs);
             graph.add(&d->d_lfovf, lfovf);
             d->lfovf_len = (int32_t)lfovf.size();
@@ -493,11 +602,16 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             d->fovf_len = (int32_t)fovf.size();
         }
     }
-    graph.add(&d->d_src, src);
+    std::vector<int32_t> copied;
+    for (int32_t v = 0; v < n; ++v)
+        if (src[v] != v) { copied.push_back(v); copied.push_back(src[v]); }
+    d->n_copied = (int32_t)(copied.size() / 2);
+    graph.add(&d->d_copied, copied);
     const size_t dep_words = (size_t)n * d->W;
     graph.reserve(&d->d_dep, dep_words * 8);
     if (d->k1_lring > 0)
         graph.reserve(&d->d_k1_sink, (size_t)((d->W + d->k1_wc - 1) / d->k1_wc) * d->k1_threads * 8);
+    if (d->k1_q_ring > 0) graph.reserve(&d->d_k1_q_sink, (size_t)(d->W / 8) * d->k1_q_threads * 16);
     // (sized for the copy back of the rows as well, so that the block is not replaced while a copy is under way)
     (void)stage(std::max(graph.host.size(), dep_words * 8));
     HIP_TRY(graph.commit(&d->d_graph_block, s));

@@ -68,8 +68,23 @@ struct Dag {
     int32_t *d_lfovf = nullptr;
     int32_t lfovf_len = 0;
     int32_t k1_lring = 0;           // slots held in LDS (a power of two, at least 16 levels)
+    // The level-major records of the kernel with 64-byte slices (four lanes per slot, P = k1_threads / 4):
+    // ring slots of up to four input rows in 16-bit halves (unused: the zero row, slot k1_lring), two recv indices
+    // likewise (0xffff none), the op id (-1: no node in the slot; -2: a copy node, which hands a row on inside the
+    // ring and stores nothing).  Any other node: in01 = 0xffffffff and in23 = the start of its list in lfovf.
+    struct QuadRec {                // 16 bytes, one per slot
+        uint32_t in01, in23, rcv01;
+        int32_t op;
+    };
+    int32_t k1_q_ring = 0, k1_q_threads = 0;   // slots held in LDS (0: no such records), threads of a workgroup
+    QuadRec *d_qrecs = nullptr;     // [n_node_levels * P]
+    int32_t *d_qfovf = nullptr;     // the lists of the other nodes, as lfovf
+    int32_t qfovf_len = 0;
+    uint64_t *d_k1_q_sink = nullptr;    // [slices * k1_q_threads][2]
     uint64_t *d_k1_sink = nullptr;  // [slices * k1_threads] one word per thread: where a thread without a node stores
-    int32_t *d_src = nullptr;       // [n] per op: ~i for recv i, else the op id of the node whose row it has
+    // the ops whose rows are copies, as pairs (op, ~i for recv i or the op id of the node whose row it has)
+    int32_t *d_copied = nullptr;    // [n_copied][2]
+    int32_t n_copied = 0;
     // op.dep
     uint64_t *d_dep = nullptr;      // [n][W]
 
@@ -124,6 +139,9 @@ hipError_t ensure_workspace(Dag *d, size_t bytes);
 // asked of the runtime once and remembered (the queries cost microseconds on every launch
 // otherwise).  The occupancy is remembered per (kernel, threads, dynamic LDS bytes).
 int device_cu_count(int device);
+// hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes), asked of the runtime only when
+// `bytes` exceeds what has already been set for the kernel on the current device
+hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes);
 hipError_t cached_blocks_per_cu(int *per_cu, const void *kernel, int threads, size_t lds);
 
 // ---- kernel launchers (each returns the HIP status of its launches) ----

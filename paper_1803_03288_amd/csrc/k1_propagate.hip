@@ -14,6 +14,8 @@
 // ring, so that inputs from recent levels cost an LDS read and only long edges go to
 // memory.
 #include "device_utils.h"
+#include <algorithm>
+
 #include "internal.h"
 
 namespace tictac {
@@ -48,6 +50,19 @@ constexpr int LVL_CHUNK = 512;
 // and the narrow stores of one row meet in one L2 before they are written back.
 __device__ __forceinline__ int slice_of(int b, int n) { return (n & 7) == 0 ? (b & 7) * (n >> 3) + (b >> 3) : b; }
 __device__ __forceinline__ int slice_of_block() { return slice_of(blockIdx.x, gridDim.x); }
+
+// Accesses that are stated to be to device memory.  A pointer that a kernel reads from a record in memory (not from
+// its own arguments) could point anywhere as far as the compiler knows, and an access through it becomes a generic one,
+// which counts as an LDS operation too: the LDS-only waits before the barriers would then wait for memory.
+typedef int tt_i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int4 load_device_16(const void *q)
+{
+    const tt_i32x4 v = *(const __attribute__((address_space(1))) tt_i32x4 *)q;
+    return make_int4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_device_8(void *q, uint64_t v) { *(__attribute__((address_space(1))) uint64_t *)q = v; }
+__device__ __forceinline__ uint64_t load_device_8(const void *q) { return *(const __attribute__((address_space(1))) uint64_t *)q; }
+__device__ __forceinline__ int32_t load_device_4(const void *q) { return *(const __attribute__((address_space(1))) int32_t *)q; }
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void drain_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -471,7 +486,7 @@ __device__ __forceinline__ void propagate_levels_body(const LevelParams &p, uint
     const uint32_t rmask = (uint32_t)p.ring - 1u;
     int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * WC);
     if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
-    for (int i = threadIdx.x; i < p.lfovf_lds; i += blockDim.x) fov[i] = p.lfovf[i];
+    for (int i = threadIdx.x; i < p.lfovf_lds; i += blockDim.x) fov[i] = load_device_4(p.lfovf + i);
     __syncthreads();
     if (L == 0) return;
 
@@ -479,12 +494,14 @@ __device__ __forceinline__ void propagate_levels_body(const LevelParams &p, uint
 #define KL_LOAD(a, b, l)                                                                  \
     {                                                                                     \
         const int4 *q_ = reinterpret_cast<const int4 *>(p.lrecs + (size_t)min((l), L - 1) * P + sub); \
-        a = q_[0]; b = q_[1];                                                             \
+        a = load_device_16(q_); b = load_device_16(q_ + 1);                               \
     }
 #define KL_DECL(i) int4 a##i, b##i; KL_LOAD(a##i, b##i, i)
     KL_EACH(KL_DECL)
 
     uint64_t *const sink = p.sink + (size_t)block * blockDim.x + threadIdx.x;
+    const char *const rbase = reinterpret_cast<const char *>(ring) + w * 8;
+    uint32_t slot = (uint32_t)sub;              // the slot of this thread group at the level being computed
     // (the next record of a set is requested after the last use of the set, into the same registers)
 #define KL_STEP(i)                                                                        \
     {                                                                                     \
@@ -492,7 +509,6 @@ __device__ __forceinline__ void propagate_levels_body(const LevelParams &p, uint
         uint64_t val = 0;                                                                 \
         uint64_t *dst = sink;               /* past the last level and without a node: a zero to the sink */ \
         if (l < L && b##i.z >= 0) {                                                       \
-            const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;             \
             const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + a##i.x);      \
             const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + a##i.y);      \
             const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + a##i.z);      \
@@ -504,10 +520,12 @@ __device__ __forceinline__ void propagate_levels_body(const LevelParams &p, uint
                 val |= other_inputs(p.lfovf, p.lfovf_lds > 0 ? fov : nullptr, ring, p.lrecs, p.dep, W, b##i.w, \
                                     (l + 1) * P - p.ring, rmask, WC, w, gw);              \
             if (gw >= W) val = 0;                                                         \
-            ring[(((uint32_t)(l * P + sub)) & rmask) * WC + w] = val;                     \
+            ring[(slot & rmask) * WC + w] = val;                                          \
             if (gw < W) dst = &p.dep[(size_t)b##i.z * W + gw];                            \
         }                                                                                 \
-        *dst = val;                                                                       \
+        store_device_8(dst, val);                                                         \
+        slot += (uint32_t)P;                                                              \
+        asm volatile("" : "+v"(slot));   /* (else one register per unrolled level holds its slot) */ \
         KL_LOAD(a##i, b##i, l + 8)                                                        \
         asm volatile("s_waitcnt vmcnt(21)" ::: "memory");                                 \
         lds_barrier();                                                                    \
@@ -545,42 +563,161 @@ propagate_levels_batch(const LevelParams *__restrict__ ps, int blocks_per)
     propagate_levels_body<WC>(p, ring, blockIdx.x - g * blocks_per, blocks_per);
 }
 
-// rows that are copies: a recv's single bit, or the row of the node an op collapses onto
-__global__ void __launch_bounds__(256)
-expand_rows(int32_t n, int32_t W, const int32_t *__restrict__ src, uint64_t *dep)
+// ---- the level-major kernel with 64-byte slices ----
+// For wide rows (a multiple of eight words).  A workgroup takes a slice of eight consecutive words (64 bytes) of
+// every row, and four adjacent lanes take one slot of a level, 16 bytes each: the four lanes' store of a row is one
+// 64-byte piece, their reads of an input row one 64-byte stretch of LDS, and they share the slot's record.  An
+// eighth of the workgroups, of the record traffic and of the store requests of one-word slices for the same bytes.
+// The ring then holds fewer levels (2048 slots in 128 KB); the host gives a row that is needed after it has left
+// the ring a copy node some levels later (see the build of the records), so a level still reads LDS only.
+// The records are 16 bytes (see internal.h): a level issues exactly one 16-byte load and one 16-byte store per thread.
+typedef unsigned long long tt_u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_device_16(void *q, tt_u64x2 v) { *(__attribute__((address_space(1))) tt_u64x2 *)q = v; }
+
+// words gw, gw + 1 of all inputs of a node that does not fit a record (see other_inputs)
+__device__ __noinline__ tt_u64x2 other_inputs_q(const int32_t *lfovf, const int32_t *fov, const uint64_t *ring,
+                                                const Dag::QuadRec *qrecs, uint64_t *dep, int W, int beg, int safe_from,
+                                                uint32_t rmask, int word_in_slice, int gw)
 {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)n * W) return;
-    const int v = (int)(idx / W), w = (int)(idx % W);
-    const int s = src[v];
+    const int32_t *list = fov ? fov : lfovf;
+    const int cnt = list[beg];
+    tt_u64x2 val = {0ull, 0ull};
+    for (int e = 1; e <= cnt; ++e) {
+        const int x = list[beg + e];
+        if (x < 0) {
+            const int i = ~x;
+            if ((i >> 6) == gw) val.x |= 1ull << (i & 63);
+            if ((i >> 6) == gw + 1) val.y |= 1ull << (i & 63);
+        } else if (x >= safe_from) {
+            val |= *reinterpret_cast<const tt_u64x2 *>(ring + ((uint32_t)x & rmask) * 8 + word_in_slice);
+        } else {
+            const uint64_t *q = &dep[(size_t)qrecs[x].op * W + gw];
+            val.x |= __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            val.y |= __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    return val;
+}
+
+struct QuadParams {
+    int32_t n_levels, W, P, ring;       // P slots per level; ring: slots held in LDS (power of two)
+    const Dag::QuadRec *qrecs;          // [n_levels * P]
+    const int32_t *lfovf;
+    int32_t lfovf_lds;                  // > 0: that many entries of lfovf (all of them) are copied to LDS
+    uint64_t *dep;
+    uint64_t *sink;                     // [gridDim.x * blockDim.x][2]
+};
+
+__device__ __forceinline__ void propagate_levels_q_body(const QuadParams &p, uint64_t *ring, int block, int n_blocks)
+{
+    const int W = p.W, L = p.n_levels, P = p.P;
+    const int sub = threadIdx.x >> 2, qd = threadIdx.x & 3;
+    const int gw = slice_of(block, n_blocks) * 8 + qd * 2;      // first of this thread's two words of the row
+    const uint32_t rmask = (uint32_t)p.ring - 1u;
+    int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * 8);
+    if (threadIdx.x < 16) ring[(size_t)p.ring * 8 + threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < p.lfovf_lds; i += blockDim.x) fov[i] = load_device_4(p.lfovf + i);
+    __syncthreads();
+    if (L == 0) return;
+
+#define KQ_LOAD(a, l) a = load_device_16(p.qrecs + (size_t)min((l), L - 1) * P + sub);
+#define KQ_DECL(i) int4 a##i; KQ_LOAD(a##i, i)
+    KL_EACH(KQ_DECL)
+
+    uint64_t *const sink = p.sink + ((size_t)block * blockDim.x + threadIdx.x) * 2;
+    const char *const rb = reinterpret_cast<const char *>(ring) + qd * 16;
+    uint32_t slot = (uint32_t)sub;              // the slot of these four lanes at the level being computed
+#define KQ_BIT(r)                                                                         \
+    {                                                                                     \
+        const int wi_ = (int)((r) >> 6) - gw;          /* no recv: r = 0xffff, word 1023, which no row here has */ \
+        const uint64_t bit_ = 1ull << ((r) & 63);                                         \
+        val.x |= wi_ == 0 ? bit_ : 0ull;                                                  \
+        val.y |= wi_ == 1 ? bit_ : 0ull;                                                  \
+    }
+    // (a level issues exactly one 16-byte load and one 16-byte store per thread: "at most fourteen outstanding")
+#define KQ_STEP(i)                                                                        \
+    {                                                                                     \
+        const int l = lbase + i;                                                          \
+        tt_u64x2 val = {0ull, 0ull};                                                      \
+        uint64_t *dst = sink;               /* past the last level, no node, a copy: to the sink */ \
+        if (l < L && a##i.w != -1) {                                                      \
+            const uint32_t i01 = (uint32_t)a##i.x, i23 = (uint32_t)a##i.y, r01 = (uint32_t)a##i.z; \
+            if (i01 != 0xffffffffu) {                                                     \
+                val = *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 & 0xffffu) << 6)) |  \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 >> 16) << 6)) |      \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 & 0xffffu) << 6)) |  \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 >> 16) << 6));       \
+                KQ_BIT(r01 & 0xffffu)                                                     \
+                KQ_BIT(r01 >> 16)                                                         \
+            } else {                                                                      \
+                val = other_inputs_q(p.lfovf, p.lfovf_lds > 0 ? fov : nullptr, ring, p.qrecs, p.dep, W, (int)i23, \
+                                     (l + 1) * P - p.ring, rmask, qd * 2, gw);            \
+            }                                                                             \
+            *reinterpret_cast<tt_u64x2 *>(ring + (slot & rmask) * 8 + qd * 2) = val;      \
+            if (a##i.w >= 0) dst = &p.dep[(size_t)a##i.w * W + gw];                       \
+        }                                                                                 \
+        store_device_16(dst, val);                                                        \
+        slot += (uint32_t)P;                                                              \
+        asm volatile("" : "+v"(slot));   /* (else one register per unrolled level holds its slot) */ \
+        KQ_LOAD(a##i, l + 8)                                                              \
+        asm volatile("s_waitcnt vmcnt(14)" ::: "memory");                                 \
+        lds_barrier();                                                                    \
+    }
+    for (int l0 = 0; l0 < L; l0 += 32) {
+        { const int lbase = l0;      KL_EACH(KQ_STEP) }
+        { const int lbase = l0 + 8;  KL_EACH(KQ_STEP) }
+        { const int lbase = l0 + 16; KL_EACH(KQ_STEP) }
+        { const int lbase = l0 + 24; KL_EACH(KQ_STEP) }
+    }
+#undef KQ_STEP
+#undef KQ_BIT
+#undef KQ_DECL
+#undef KQ_LOAD
+}
+
+__global__ void __launch_bounds__(1024)
+propagate_levels_q_batch(const QuadParams *__restrict__ ps, int blocks_per)
+{
+    extern __shared__ uint64_t ring[];          // rows [ring + 2][8] (the last two all zero), then the input lists
+    const int g = blockIdx.x / blocks_per;
+    const QuadParams p = ps[g];
+    propagate_levels_q_body(p, ring, blockIdx.x - g * blocks_per, blocks_per);
+}
+
+// rows that are copies: a recv's single bit, or the row of the node an op collapses onto.  `copied`: the ops
+// with such rows, as pairs (op, ~i for recv i or the op id of the node whose row it has).
+__device__ __forceinline__ void expand_word(int32_t n_copied, int32_t W, const int32_t *copied, uint64_t *dep, size_t idx)
+{
+    if (idx >= (size_t)n_copied * W) return;
+    const int e = (int)(idx / W), w = (int)(idx % W);
+    const int v = load_device_4(copied + 2 * e), s = load_device_4(copied + 2 * e + 1);
+    uint64_t val;
     if (s < 0) {
         const int i = ~s;
-        dep[idx] = (i >> 6) == w ? 1ull << (i & 63) : 0ull;
-    } else if (s != v) {
-        dep[idx] = dep[(size_t)s * W + w];
+        val = (i >> 6) == w ? 1ull << (i & 63) : 0ull;
+    } else {
+        val = load_device_8(dep + (size_t)s * W + w);
     }
+    store_device_8(dep + (size_t)v * W + w, val);
+}
+
+__global__ void __launch_bounds__(256)
+expand_rows(int32_t n_copied, int32_t W, const int32_t *__restrict__ copied, uint64_t *dep)
+{
+    expand_word(n_copied, W, copied, dep, (size_t)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 // the same for several graphs: blockIdx.y = graph
 struct ExpandParams {
-    int32_t n, W;
-    const int32_t *src;
+    int32_t n_copied, W;
+    const int32_t *copied;
     uint64_t *dep;
 };
 __global__ void __launch_bounds__(256)
 expand_rows_batch(const ExpandParams *__restrict__ ps)
 {
     const ExpandParams p = ps[blockIdx.y];
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (size_t)p.n * p.W) return;
-    const int v = (int)(idx / p.W), w = (int)(idx % p.W);
-    const int s = p.src[v];
-    if (s < 0) {
-        const int i = ~s;
-        p.dep[idx] = (i >> 6) == w ? 1ull << (i & 63) : 0ull;
-    } else if (s != v) {
-        p.dep[idx] = p.dep[(size_t)s * p.W + w];
-    }
+    expand_word(p.n_copied, p.W, p.copied, p.dep, (size_t)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 static bool level_params(const Dag &d, int WC, LevelParams *q, size_t *lds)
@@ -593,6 +730,17 @@ static bool level_params(const Dag &d, int WC, LevelParams *q, size_t *lds)
     return *lds <= 150 * 1024;
 }
 
+static bool quad_params(const Dag &d, QuadParams *q, size_t *lds)
+{
+    if (d.k1_q_ring <= 0 || !d.d_qrecs || !d.d_k1_q_sink || d.W % 8 != 0 || d.k1_q_threads % 64 != 0 || d.k1_q_threads > 1024)
+        return false;
+    q->n_levels = d.n_node_levels; q->W = d.W; q->P = d.k1_q_threads / 4; q->ring = d.k1_q_ring;
+    q->qrecs = d.d_qrecs; q->lfovf = d.d_qfovf; q->dep = d.d_dep; q->sink = d.d_k1_q_sink;
+    q->lfovf_lds = d.qfovf_len <= 4096 ? d.qfovf_len : 0;
+    *lds = (size_t)(d.k1_q_ring + 2) * 64 + (size_t)q->lfovf_lds * 4;
+    return *lds <= 150 * 1024;
+}
+
 // Propagation for G graphs that all take the level-major kernel with one launch shape (as G handles of one
 // graph do): one launch of the node kernel, one of the copies.  `staging`: device memory for G parameter records
 // of each kind (filled here, stream-ordered).  hipErrorNotSupported when the graphs do not fit that description.
@@ -602,13 +750,15 @@ static hipError_t launch_levels_batch(Dag *const *ds, int G, void *staging, hipS
     std::vector<LevelParams> lp(G);
     std::vector<ExpandParams> ep(G);
     size_t lds0 = 0;
+    int32_t most_copied = 0;
     for (int g = 0; g < G; ++g) {
         size_t lds = 0;
         if (!level_params(*ds[g], WC, &lp[g], &lds)) return hipErrorNotSupported;
         if (g == 0) lds0 = lds;
         if (lds != lds0 || ds[g]->k1_threads != ds[0]->k1_threads || ds[g]->W != ds[0]->W || ds[g]->n != ds[0]->n)
             return hipErrorNotSupported;
-        ep[g] = ExpandParams{ds[g]->n, ds[g]->W, ds[g]->d_src, ds[g]->d_dep};
+        ep[g] = ExpandParams{ds[g]->n_copied, ds[g]->W, ds[g]->d_copied, ds[g]->d_dep};
+        most_copied = std::max(most_copied, ds[g]->n_copied);
     }
     LevelParams *d_lp = static_cast<LevelParams *>(staging);
     ExpandParams *d_ep = reinterpret_cast<ExpandParams *>(d_lp + G);
@@ -617,24 +767,61 @@ static hipError_t launch_levels_batch(Dag *const *ds, int G, void *staging, hipS
     e = hipMemcpyAsync(d_ep, ep.data(), sizeof(ExpandParams) * G, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return e;
     if (lds0 > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_levels_batch<WC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds0);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_levels_batch<WC>), lds0);
         if (e != hipSuccess) return e;
     }
     const Dag &d0 = *ds[0];
     const int blocks_per = (d0.W + WC - 1) / WC;
     hipLaunchKernelGGL(propagate_levels_batch<WC>, dim3(blocks_per * G), dim3(d0.k1_threads), lds0, s, d_lp, blocks_per);
-    const size_t total = (size_t)d0.n * d0.W;
-    hipLaunchKernelGGL(expand_rows_batch, dim3((unsigned)((total + 255) / 256), G), dim3(256), 0, s, d_ep);
+    const size_t total = (size_t)most_copied * d0.W;
+    if (total) hipLaunchKernelGGL(expand_rows_batch, dim3((unsigned)((total + 255) / 256), G), dim3(256), 0, s, d_ep);
     return hipGetLastError();
 }
 
-size_t propagate_batch_staging_bytes(int G) { return (sizeof(LevelParams) + sizeof(ExpandParams)) * (size_t)G; }
+// the same for graphs that take the kernel with 64-byte slices
+static hipError_t launch_quad_batch(Dag *const *ds, int G, void *staging, hipStream_t s)
+{
+    std::vector<QuadParams> lp(G);
+    std::vector<ExpandParams> ep(G);
+    size_t lds0 = 0;
+    int32_t most_copied = 0;
+    for (int g = 0; g < G; ++g) {
+        size_t lds = 0;
+        if (!quad_params(*ds[g], &lp[g], &lds)) return hipErrorNotSupported;
+        if (g == 0) lds0 = lds;
+        if (lds != lds0 || ds[g]->k1_q_threads != ds[0]->k1_q_threads || ds[g]->W != ds[0]->W || ds[g]->n != ds[0]->n)
+            return hipErrorNotSupported;
+        ep[g] = ExpandParams{ds[g]->n_copied, ds[g]->W, ds[g]->d_copied, ds[g]->d_dep};
+        most_copied = std::max(most_copied, ds[g]->n_copied);
+    }
+    QuadParams *d_lp = static_cast<QuadParams *>(staging);
+    ExpandParams *d_ep = reinterpret_cast<ExpandParams *>(d_lp + G);
+    hipError_t e = hipMemcpyAsync(d_lp, lp.data(), sizeof(QuadParams) * G, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    e = hipMemcpyAsync(d_ep, ep.data(), sizeof(ExpandParams) * G, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    if (lds0 > 48 * 1024) {
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_levels_q_batch), lds0);
+        if (e != hipSuccess) return e;
+    }
+    const Dag &d0 = *ds[0];
+    const int blocks_per = d0.W / 8;
+    hipLaunchKernelGGL(propagate_levels_q_batch, dim3(blocks_per * G), dim3(d0.k1_q_threads), lds0, s, d_lp, blocks_per);
+    const size_t total = (size_t)most_copied * d0.W;
+    if (total) hipLaunchKernelGGL(expand_rows_batch, dim3((unsigned)((total + 255) / 256), G), dim3(256), 0, s, d_ep);
+    return hipGetLastError();
+}
+
+size_t propagate_batch_staging_bytes(int G)
+{
+    return (std::max(sizeof(LevelParams), sizeof(QuadParams)) + sizeof(ExpandParams)) * (size_t)G;
+}
 
 hipError_t launch_propagate_batch(Dag *const *ds, int G, void *staging, hipStream_t s)
 {
     if (G <= 0) return hipSuccess;
     if (ds[0]->n == 0 || ds[0]->W == 0 || ds[0]->M == 0) return hipErrorNotSupported;
+    if (G >= 2 && ds[0]->k1_q_ring > 0) return launch_quad_batch(ds, G, staging, s);
     if (ds[0]->k1_wc == 1) return launch_levels_batch<1>(ds, G, staging, s);
     if (ds[0]->k1_wc == 2) return launch_levels_batch<2>(ds, G, staging, s);
     return launch_levels_batch<4>(ds, G, staging, s);
@@ -656,15 +843,10 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     if (d.d_lrecs) {
         // level-major records: no staging, no chunks
         LevelParams q;
-        q.n_levels = d.n_node_levels; q.W = d.W; q.P = per_pass; q.ring = d.k1_lring;
-        q.lrecs = d.d_lrecs; q.lfovf = d.d_lfovf; q.dep = d.d_dep; q.sink = d.d_k1_sink;
-        if (!q.sink) return hipErrorInvalidValue;
-        q.lfovf_lds = d.lfovf_len <= 4096 ? d.lfovf_len : 0;
-        const size_t lds_l = (size_t)(d.k1_lring + 2) * WC * 8 + (size_t)q.lfovf_lds * 4;
-        if (lds_l > 150 * 1024) return hipErrorInvalidValue;
+        size_t lds_l = 0;
+        if (!level_params(d, WC, &q, &lds_l)) return hipErrorInvalidValue;
         if (lds_l > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_levels<WC>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_l);
+            hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_levels<WC>), lds_l);
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(propagate_levels<WC>, dim3(blocks), dim3(threads), lds_l, s, q);
@@ -678,8 +860,7 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
                              (size_t)p.fovf_lds * 4;
         if (lds_w <= 150 * 1024) {
             if (lds_w > 48 * 1024) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(propagate_nodes_wave<WC>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+                hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_nodes_wave<WC>), lds_w);
                 if (e != hipSuccess) return e;
             }
             hipLaunchKernelGGL(propagate_nodes_wave<WC>, dim3(blocks), dim3(64), lds_w, s, p);
@@ -694,7 +875,7 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     const void *kern = wide ? reinterpret_cast<const void *>(propagate_nodes_wide<WC>)
                             : reinterpret_cast<const void *>(propagate_nodes<WC>);
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds(kern, lds);
         if (e != hipSuccess) return e;
     }
     if (wide)
@@ -714,8 +895,9 @@ hipError_t launch_propagate(const Dag &d, hipStream_t s)
         else e = launch_nodes<4>(d, s);
         if (e != hipSuccess) return e;
     }
-    const size_t total = (size_t)d.n * d.W;
-    hipLaunchKernelGGL(expand_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, d.n, d.W, d.d_src, d.d_dep);
+    const size_t total = (size_t)d.n_copied * d.W;
+    if (total)
+        hipLaunchKernelGGL(expand_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, d.n_copied, d.W, d.d_copied, d.d_dep);
     return hipGetLastError();
 }
 

@@ -378,8 +378,7 @@ static hipError_t launch_tac_t(Dag &d, TacKernelParams &p, int grid, size_t lds,
 {
     auto kern = tac_kernel<BS, GSTATE>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(BS), lds, s, p);

@@ -537,8 +537,7 @@ static hipError_t launch_reg_k(TacRegParams &p, const Dag &d, hipStream_t s)
     int per_cu = 0;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(tac_reg_kernel<KT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(tac_reg_kernel<KT>), lds);
         if (e != hipSuccess) return e;
     }
     e = cached_blocks_per_cu(&per_cu, reinterpret_cast<const void *>(tac_reg_kernel<KT>), 64 * waves, lds);

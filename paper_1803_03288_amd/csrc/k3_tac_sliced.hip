@@ -784,8 +784,7 @@ static hipError_t launch_sliced_k(SlicedParams &p, Dag &d, const TacArgs &a, siz
     if (lds > 150 * 1024) return hipErrorNotSupported;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(tac_sliced_kernel<KW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(tac_sliced_kernel<KW>), lds);
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;

@@ -313,8 +313,7 @@ static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
     p.wave_bytes = (int32_t)wave_bytes;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(simulate_wave_kernel<KT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(simulate_wave_kernel<KT>), lds);
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;
@@ -357,8 +356,7 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
 {
     auto kern = simulate_kernel<BS>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(BS), lds, s, p);
@@ -545,8 +543,7 @@ static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
     p.chan_bytes = (int32_t)chan_bytes;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(simulate_channels_kernel<KT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(simulate_channels_kernel<KT>), lds);
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;

@@ -318,8 +318,7 @@ static hipError_t launch_search_t(SearchParams &p, const Dag &d, hipStream_t s)
     p.rows_bytes = (int32_t)rows_bytes;
     hipError_t e;
     if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(order_search_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(order_search_kernel<T>), lds);
         if (e != hipSuccess) return e;
     }
     int per_cu = 0;
