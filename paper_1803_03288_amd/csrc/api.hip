@@ -395,6 +395,11 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     HIP_TRY(hipGetDevice(&d->device));
 
     // ---- upload and propagate ----
+    // the ops whose rows are copies (of a recv's single bit, or of the row of the node the op collapses onto)
+    std::vector<int32_t> copied;
+    for (int32_t v = 0; v < n; ++v)
+        if (src[v] != v) { copied.push_back(v); copied.push_back(src[v]); }
+    d->n_copied = (int32_t)(copied.size() / 2);
     Packer graph;
     graph.add(&d->d_recv_of_op, recv_of_op);
     graph.add(&d->d_nodes, nodes);
@@ -451,7 +456,7 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         // between, each within reach of the one before; the copies of a row form one chain, which the consumers,
         // taken level by level, extend.
         auto level_major = [&](bool quad, int32_t P, int32_t lring, std::vector<Dag::FastRec> &lrecs,
-                               std::vector<Dag::QuadRec> &qrecs, std::vector<int32_t> &lfovf) {
+                               std::vector<Dag::QuadRec> &qrecs, std::vector<int32_t> &lfovf, std::vector<int32_t> &left) {
             const int32_t row_bytes = d->k1_wc * 8, zero_row = lring * row_bytes;
             std::vector<int32_t> slot_of(M);            // position -> slot
             for (int32_t l = 0; l < n_node_levels; ++l)
@@ -544,21 +549,59 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
                         lfovf.insert(lfovf.end(), tmp.begin(), tmp.end());
                     }
                 }
+            if (!quad) return;
+            // The copied rows ride along in slots that are still free: a recv's row anywhere (no input, one recv
+            // bit), the copy of a node's row at a level within reach of the node or of one of its copy nodes, as
+            // a node with that one input and the op's own id.  What finds no slot stays on the list `left`.
+            std::vector<int32_t> slot_of_op(n, -1);
+            for (int32_t q = 0; q < M; ++q) slot_of_op[nodes[q].op] = slot_of[q];
+            const uint32_t zero2 = (uint32_t)lring | (uint32_t)lring << 16;
+            int32_t cursor = 0;
+            for (size_t e = 0; e + 1 < copied.size(); e += 2) {
+                const int32_t v = copied[e], sv = copied[e + 1];
+                int32_t c = -1;
+                if (sv < 0) {
+                    while (cursor < n_node_levels && used[cursor] >= P) ++cursor;
+                    if (cursor < n_node_levels) {
+                        c = cursor * P + used[cursor]++;
+                        qrecs[c] = Dag::QuadRec{zero2, zero2, (uint32_t)~sv | 0xffff0000u, v};
+                    }
+                } else if (slot_of_op[sv] >= 0 && reach >= 1) {
+                    const int32_t base = slot_of_op[sv];
+                    auto it = chain.find(base);
+                    const size_t n_cand = 1 + (it == chain.end() ? 0 : it->second.size());
+                    for (size_t k = 0; k < n_cand && c < 0; ++k) {
+                        const int32_t from = k == 0 ? base : it->second[k - 1];
+                        for (int32_t t = from / P + 1; t <= from / P + reach && t < n_node_levels; ++t)
+                            if (used[t] < P) {
+                                c = t * P + used[t]++;
+                                qrecs[c] = Dag::QuadRec{(uint32_t)(from & (lring - 1)) | (uint32_t)lring << 16, zero2,
+                                                        0xffffffffu, v};
+                                break;
+                            }
+                    }
+                }
+                if (c < 0) { left.push_back(v); left.push_back(sv); }
+            }
         };
         if (q_ring > 0) {
             std::vector<Dag::FastRec> unused;
             std::vector<Dag::QuadRec> qrecs;
             std::vector<int32_t> qfovf;
-            level_major(true, q_slots, q_ring, unused, qrecs, qfovf);
+            std::vector<int32_t> left;
+            level_major(true, q_slots, q_ring, unused, qrecs, qfovf, left);
             graph.add(&d->d_qrecs, qrecs);
             graph.add(&d->d_qfovf, qfovf);
+            graph.add(&d->d_q_copied, left);
             d->qfovf_len = (int32_t)qfovf.size();
+            d->n_q_copied = (int32_t)(left.size() / 2);
         }
         if (lring > 0) {
             std::vector<Dag::FastRec> lrecs;
             std::vector<Dag::QuadRec> unused;
             std::vector<int32_t> lfovf;
-            level_major(false, per_pass, lring, lrecs, unused, lfovf);
+            std::vector<int32_t> none_left;
+            level_major(false, per_pass, lring, lrecs, unused, lfovf, none_left);
             graph.add(&d->d_lrecs, lrecs);
             graph.add(&d->d_lfovf, lfovf);
             d->lfovf_len = (int32_t)lfovf.size();
@@ -602,10 +645,6 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
             d->fovf_len = (int32_t)fovf.size();
         }
     }
-    std::vector<int32_t> copied;
-    for (int32_t v = 0; v < n; ++v)
-        if (src[v] != v) { copied.push_back(v); copied.push_back(src[v]); }
-    d->n_copied = (int32_t)(copied.size() / 2);
     graph.add(&d->d_copied, copied);
     const size_t dep_words = (size_t)n * d->W;
     graph.reserve(&d->d_dep, dep_words * 8);

@@ -81,6 +81,8 @@ struct Dag {
     int32_t *d_qfovf = nullptr;     // the lists of the other nodes, as lfovf
     int32_t qfovf_len = 0;
     uint64_t *d_k1_q_sink = nullptr;    // [slices * k1_q_threads][2]
+    int32_t *d_q_copied = nullptr;  // [n_q_copied][2] the copied rows (see d_copied) that found no free slot of these records
+    int32_t n_q_copied = 0;
     uint64_t *d_k1_sink = nullptr;  // [slices * k1_threads] one word per thread: where a thread without a node stores
     // the ops whose rows are copies, as pairs (op, ~i for recv i or the op id of the node whose row it has)
     int32_t *d_copied = nullptr;    // [n_copied][2]

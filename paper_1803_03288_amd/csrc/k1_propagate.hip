@@ -679,9 +679,14 @@ __global__ void __launch_bounds__(1024)
 propagate_levels_q_batch(const QuadParams *__restrict__ ps, int blocks_per)
 {
     extern __shared__ uint64_t ring[];          // rows [ring + 2][8] (the last two all zero), then the input lists
-    const int g = blockIdx.x / blocks_per;
+    // Workgroup b runs on XCD b % 8.  The workgroups are renumbered so that every XCD gets a run of consecutive
+    // numbers, hence whole graphs where it can: the slices of a row then meet in one L2 and leave it as whole
+    // lines, and the eight slices of a graph read its records through one L2.
+    const int n = gridDim.x;
+    const int v = (n & 7) == 0 ? (blockIdx.x & 7) * (n >> 3) + (blockIdx.x >> 3) : (int)blockIdx.x;
+    const int g = v / blocks_per;
     const QuadParams p = ps[g];
-    propagate_levels_q_body(p, ring, blockIdx.x - g * blocks_per, blocks_per);
+    propagate_levels_q_body(p, ring, v - g * blocks_per, 1);
 }
 
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto.  `copied`: the ops
@@ -791,8 +796,8 @@ static hipError_t launch_quad_batch(Dag *const *ds, int G, void *staging, hipStr
         if (g == 0) lds0 = lds;
         if (lds != lds0 || ds[g]->k1_q_threads != ds[0]->k1_q_threads || ds[g]->W != ds[0]->W || ds[g]->n != ds[0]->n)
             return hipErrorNotSupported;
-        ep[g] = ExpandParams{ds[g]->n_copied, ds[g]->W, ds[g]->d_copied, ds[g]->d_dep};
-        most_copied = std::max(most_copied, ds[g]->n_copied);
+        ep[g] = ExpandParams{ds[g]->n_q_copied, ds[g]->W, ds[g]->d_q_copied, ds[g]->d_dep};
+        most_copied = std::max(most_copied, ds[g]->n_q_copied);
     }
     QuadParams *d_lp = static_cast<QuadParams *>(staging);
     ExpandParams *d_ep = reinterpret_cast<ExpandParams *>(d_lp + G);
