@@ -54,7 +54,7 @@ def parse() -> argparse.Namespace:
     ap.add_argument("--no-per-config", action="store_true", help="skip the records of the other presets")
     ap.add_argument("--no-deps-bench", action="store_true", help="skip the propagation timing on the stress preset")
     ap.add_argument("--no-compare", action="store_true", help="skip the side legs on the headline samples")
-    ap.add_argument("--deps-batch", type=int, default=16,
+    ap.add_argument("--deps-batch", type=int, default=32,
                     help="independent instances of the stress graph propagated by one launch (a run beyond the "
                          "configuration: one graph alone is bound by the latency of its level chain); 0 = skip")
     ap.add_argument("--copy-probe", action="store_true",
@@ -343,6 +343,7 @@ def main() -> int:
                 dep_bitset.setdefault("batched", []).append(
                     {"instances": G, "us_per_launch": b_ms * 1e3, "GB/s": G * alg_bytes / (b_ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": G * alg_bytes / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "target_met": bool(G * alg_bytes / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS >= 0.5),
                      "note": "G independent graphs in one launch, HIP events; beyond the configuration"})
                 for hh in hb[1:]:
                     hh.close()

@@ -54,7 +54,7 @@ typedef enum tictac_status {
     TICTAC_ERR_CYCLE = -3,         /* the graph is not acyclic */
     TICTAC_ERR_RECV_NOT_ROOT = -4, /* a recv op has predecessors (Sec. 2.2: recvs are roots) */
     TICTAC_ERR_DUP_RECV = -5,      /* recv_ids holds an op twice */
-    TICTAC_ERR_BAD_ORDER = -6,     /* order_stride is neither 0 nor n_recv, or a channel index is out of range */
+    TICTAC_ERR_BAD_ORDER = -6,     /* order_stride is neither 0 nor n_recv, a channel index is out of range, or an order is no permutation */
     TICTAC_ERR_HIP = -7,           /* a HIP runtime call failed */
     TICTAC_ERR_NO_MEM = -8,        /* host or device allocation failed */
     TICTAC_ERR_UNSUPPORTED = -9    /* size beyond what the kernels are built for */
@@ -106,6 +106,15 @@ int tictac_dag_recompute_deps(tictac_dag *dag, tictac_stream stream);
  * handles must not be used by other calls meanwhile. */
 int tictac_dag_recompute_deps_batch(tictac_dag *const *dags, int32_t n_dags, tictac_stream stream);
 
+/* Sec. 3.2 takes the transfer order as a permutation of the recvs.  tictac_simulate, tictac_simulate_f32,
+ * tictac_simulate_channels and tictac_order_search are asynchronous and cannot return what only the device
+ * sees, so each of them first checks, on the device, every order it is given (each entry in 0 .. n_recv-1,
+ * none twice) and raises a flag of the handle when one fails; the outputs of such a sample are unspecified
+ * (entries out of range are skipped, nothing is read or written out of bounds).  This call waits for the
+ * stream, returns TICTAC_ERR_BAD_ORDER when the flag was raised since the last such call, TICTAC_OK otherwise,
+ * and lowers the flag. */
+int tictac_dag_check_orders(tictac_dag *dag, tictac_stream stream);
+
 int tictac_dag_free(tictac_dag *dag);
 
 /*
@@ -145,7 +154,7 @@ int tictac_tac_priority(const tictac_dag *dag, int32_t B, const double *op_time,
  * device runs one op at a time and never idles while an op is ready.
  *   order: device, recv indices.  order_stride = 0: one order [n_recv] for every
  *          sample; order_stride = n_recv: order [B][n_recv].  Must be a
- *          permutation of 0..n_recv-1 (not checked on the device).
+ *          permutation of 0..n_recv-1 (checked on the device: tictac_dag_check_orders).
  *   makespan [B] device: finish time of the last op
  *   eff      [B] device: E = (U - m) / (U - L) (Eq. 3); 1 when U == L
  *   U, L, S  [B] device, each may be NULL: U = sum of all times (Eq. 1),
@@ -251,7 +260,7 @@ int tictac_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double
  *     makespan m of that order; keep the exchange when m < m_cur (then m_cur = m), else undo it.
  * A move with a == b or with a position outside 0 .. n_recv-1 is skipped.
  *   order  device, start orders: order_stride = 0: one order [n_recv] for every sample;
- *          order_stride = n_recv: [B][n_recv].  Must be permutations (not checked on the device).
+ *          order_stride = n_recv: [B][n_recv].  Must be permutations (checked on the device: tictac_dag_check_orders).
  *   moves  device, int32 [n_moves][2]; n_moves >= 0
  *   best_order     [B][n_recv] device: the order every sample ends with
  *   best_makespan  [B] device: its makespan, equal to what tictac_simulate gives for it

@@ -28,7 +28,7 @@ STATUS = {
 
 EXPORTS = (
     "tictac_build_deps", "tictac_dag_info", "tictac_dag_deps", "tictac_dag_copy_deps", "tictac_dag_recompute_deps",
-    "tictac_dag_recompute_deps_batch",
+    "tictac_dag_recompute_deps_batch", "tictac_dag_check_orders",
     "tictac_dag_free",
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
     "tictac_tac_simulate_noalloc",
@@ -115,6 +115,11 @@ class Dag:
     def recompute_deps(self) -> None:
         """``tictac_dag_recompute_deps``: run the propagation kernel again (for timing)."""
         _check(lib().tictac_dag_recompute_deps(self._h, _stream()))
+
+    def check_orders(self) -> None:
+        """``tictac_dag_check_orders``: waits for the stream; raises ``TicTacError`` (TICTAC_ERR_BAD_ORDER) when an order
+        given to a simulation or a search since the last call was no permutation of the recvs."""
+        _check(lib().tictac_dag_check_orders(self._h, _stream()))
 
     def close(self) -> None:
         if self._h is not None:

@@ -651,9 +651,11 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     if (d->k1_lring > 0)
         graph.reserve(&d->d_k1_sink, (size_t)((d->W + d->k1_wc - 1) / d->k1_wc) * d->k1_threads * 8);
     if (d->k1_q_ring > 0) graph.reserve(&d->d_k1_q_sink, (size_t)(d->W / 8) * d->k1_q_threads * 16);
+    graph.reserve(&d->d_bad_order, 256);
     // (sized for the copy back of the rows as well, so that the block is not replaced while a copy is under way)
     (void)stage(std::max(graph.host.size(), dep_words * 8));
     HIP_TRY(graph.commit(&d->d_graph_block, s));
+    HIP_TRY(hipMemsetAsync(d->d_bad_order, 0, 256, s));
     if (dep_words) HIP_TRY(launch_propagate(*d, s));
 
     // ---- classes of identical rows among the compute ops ----
@@ -1062,6 +1064,7 @@ static int simulate_any(const tictac_dag *dag, int32_t B, const int32_t *order, 
     if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
     SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
     a.f32 = f32;
+    HIP_TRY(launch_check_orders(*d, B, order, order_stride, (hipStream_t)stream));
     HIP_TRY(launch_simulate(*d, a, (hipStream_t)stream));
     return TICTAC_OK;
 }
@@ -1108,6 +1111,7 @@ int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channel
     if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
     SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
     hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(launch_check_orders(*d, B, order, order_stride, s));
     if (d->R == 0) {                      // no transfers: the channels play no role
         HIP_TRY(launch_simulate(*d, a, s));
         return TICTAC_OK;
@@ -1125,6 +1129,21 @@ int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channel
     }
     HIP_TRY(e);
     return TICTAC_OK;
+}
+
+int tictac_dag_check_orders(tictac_dag *dag, tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = reinterpret_cast<Dag *>(dag);
+    if (!d->d_bad_order) return TICTAC_OK;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t raised = 0;
+    HIP_TRY(hipMemcpyAsync(&raised, d->d_bad_order, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (raised == 0) return TICTAC_OK;
+    HIP_TRY(hipMemsetAsync(d->d_bad_order, 0, sizeof(int32_t), s));
+    set_error("an order given since the last check was no permutation of 0 .. n_recv-1");
+    return TICTAC_ERR_BAD_ORDER;
 }
 
 int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double *straggler, tictac_stream stream)
@@ -1172,6 +1191,7 @@ int tictac_order_search(const tictac_dag *dag, int32_t B, const int32_t *order, 
     if (!best_order || !best_makespan) { set_error("best_order or best_makespan is NULL"); return TICTAC_ERR_NULL; }
     SearchArgs a{B, order, order_stride, n_moves, moves, op_time, recv_time, best_order, best_makespan,
                  start_makespan, n_accepted};
+    HIP_TRY(launch_check_orders(*d, B, order, order_stride, (hipStream_t)stream));
     const hipError_t e = launch_order_search(*d, a, (hipStream_t)stream);
     if (e == hipErrorNotSupported) {
         set_error("graph outside what the order search handles");

@@ -84,6 +84,7 @@ struct Dag {
     int32_t *d_q_copied = nullptr;  // [n_q_copied][2] the copied rows (see d_copied) that found no free slot of these records
     int32_t n_q_copied = 0;
     uint64_t *d_k1_sink = nullptr;  // [slices * k1_threads] one word per thread: where a thread without a node stores
+    int32_t *d_bad_order = nullptr; // one flag: an order handed to a simulation or a search was no permutation
     // the ops whose rows are copies, as pairs (op, ~i for recv i or the op id of the node whose row it has)
     int32_t *d_copied = nullptr;    // [n_copied][2]
     int32_t n_copied = 0;
@@ -198,6 +199,8 @@ struct SimArgs {
     double *makespan, *eff, *U, *L, *S;
     bool f32 = false;
 };
+// raises *d.d_bad_order when a row of `order` (B rows, or one when order_stride = 0) is no permutation of 0 .. R-1
+hipError_t launch_check_orders(Dag &d, int32_t B, const int32_t *order, int32_t order_stride, hipStream_t s);
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
 hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s);
 hipError_t launch_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, hipStream_t s);

@@ -30,12 +30,15 @@ struct SimKernelParams {
     double *makespan, *eff, *U, *L, *S;
 };
 
-// 1-based position of every recv in an order shared by all samples
+// 1-based position of every recv in an order shared by all samples (one workgroup; 0 for a recv that an
+// invalid order leaves out, so that every position read later is in 0 .. R)
 __global__ void __launch_bounds__(256)
 position_kernel(int32_t R, const int32_t *__restrict__ order, int32_t *pos /*[R]*/)
 {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < R && (unsigned)order[k] < (unsigned)R) pos[order[k]] = k + 1;
+    for (int k = threadIdx.x; k < R; k += 256) pos[k] = 0;
+    __syncthreads();
+    for (int k = threadIdx.x; k < R; k += 256)
+        if ((unsigned)order[k] < (unsigned)R) pos[order[k]] = k + 1;
 }
 
 // kappa of every class under that order
@@ -73,6 +76,8 @@ simulate_kernel(const SimKernelParams p)
         const TimeRow rt = time_row(p.recv_time, (size_t)b * R, p.f32 != 0);
         const TimeRow ot = time_row(p.op_time, (size_t)b * N, p.f32 != 0);
         const int32_t *ord = p.order + (size_t)b * p.order_stride;
+        __syncthreads();
+        for (int k = tid; k < R; k += BS) pos[k] = 0;   // (a recv that an invalid order leaves out: position 0)
         __syncthreads();
         for (int k = tid; k < R; k += BS) {
             const int r = ord[k];
@@ -675,7 +680,7 @@ hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
         int32_t *pos = static_cast<int32_t *>(d.d_work);
         int32_t *kappa = pos + d.R;
-        hipLaunchKernelGGL(position_kernel, dim3((d.R + 255) / 256), dim3(256), 0, s, d.R, a.order, pos);
+        hipLaunchKernelGGL(position_kernel, dim3(1), dim3(256), 0, s, d.R, a.order, pos);
         hipLaunchKernelGGL(kappa_kernel, dim3((d.C + 255) / 256), dim3(256), 0, s, d.W, d.C, d.d_cls_dep, pos, kappa);
         p.kappa = kappa;
     }
@@ -691,6 +696,43 @@ hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s)
     }
     const int grid = a.B < 256 * 2 ? a.B : 256 * 2;
     return launch_sim_t<1024>(p, grid, lds, s);
+}
+
+// ---- orders given by the caller ----
+// One wave per order: every entry in 0 .. R-1 and none twice (a bit per recv in LDS), else the flag is raised.
+// The simulations and the search skip entries out of range themselves; what they return for such a row is unspecified.
+__global__ void __launch_bounds__(256)
+check_orders_kernel(int32_t R, int32_t rows, const int32_t *__restrict__ order, int32_t stride, int32_t *flag)
+{
+    extern __shared__ uint32_t seen_all[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, words = (R + 31) >> 5;
+    uint32_t *seen = seen_all + (size_t)wave * words;
+    bool bad = false;
+    for (int b = blockIdx.x * 4 + wave; b < rows; b += gridDim.x * 4) {
+        const int32_t *ord = order + (size_t)b * stride;
+        for (int i = lane; i < words; i += 64) seen[i] = 0;
+        wave_sync();
+        for (int k = lane; k < R; k += 64) {
+            const int r = ord[k];
+            if ((unsigned)r >= (unsigned)R) { bad = true; continue; }
+            const uint32_t bit = 1u << (r & 31);
+            if (atomicOr(&seen[r >> 5], bit) & bit) bad = true;
+        }
+        wave_sync();
+    }
+    if (bad) atomicOr(flag, 1);
+}
+
+hipError_t launch_check_orders(Dag &d, int32_t B, const int32_t *order, int32_t order_stride, hipStream_t s)
+{
+    if (d.R <= 0 || B <= 0 || !order) return hipSuccess;
+    if (!d.d_bad_order) return hipErrorInvalidValue;
+    const int rows = order_stride == 0 ? 1 : B;
+    const size_t lds = (size_t)4 * ((d.R + 31) / 32) * 4;
+    if (lds > 48 * 1024) return hipErrorInvalidValue;
+    const int blocks = std::min((rows + 3) / 4, 8 * device_cu_count(d.device));
+    hipLaunchKernelGGL(check_orders_kernel, dim3(blocks), dim3(256), lds, s, d.R, rows, order, order_stride, d.d_bad_order);
+    return hipGetLastError();
 }
 
 }  // namespace tictac

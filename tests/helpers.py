@@ -145,3 +145,48 @@ def oracle_rounds_after_prefix(dep, recv_ids, op_row, rv_row, order_row, ks, thr
     sel = o[:, 0]
     rows = np.arange(len(ks))
     return sel, sP[rows, sel], sM[rows, sel]
+
+
+def tac_order_up_to_near_ties(oracle, dag, dep, op_row, rv_row, got, tol=1e-9, max_restarts=64):
+    """Checks one TAC order computed in floating point on times that are not quantised.
+
+    Where `got` equals the oracle's order nothing is to show.  At the first step where they differ the
+    oracle's round (Algorithm 1 on the recvs still outstanding) must call it a near tie: no outstanding
+    recv precedes the one `got` chose by more than `tol` relative in the comparator's min-terms
+    (Sec. 4.3, Case 1), nor, where those are equal bit for bit, in M+ (Case 2), nor, where M+ is equal bit
+    for bit too, by its smaller index.  The oracle is then
+    continued from the prefix of `got` (its start-set argument) and the rest compared the same way.
+    Returns the number of near ties met; raises AssertionError on any other difference."""
+    R = dag.n_recv
+    got = np.asarray(got)
+    assert np.array_equal(np.sort(got), np.arange(R)), "not a permutation"
+    t = full_time_row(dag, op_row, rv_row)
+    alive = np.ones(R, dtype=np.uint8)
+    k, near = 0, 0
+    while k < R:
+        exp = oracle.tac(dep, dag.recv_ids, op_row[None], rv_row[None], alive0=alive[None])[0][0][: R - k]
+        diff = np.nonzero(exp != got[k:])[0]
+        if diff.size == 0:
+            break
+        j = k + int(diff[0])
+        alive[got[k:j]] = 0
+        M, P, Mp = oracle.update_properties(dep, dag.recv_ids, t, alive)
+        Mr = M[dag.recv_ids]
+        g = int(got[j])
+        for c in np.nonzero(alive)[0]:
+            if c == g:
+                continue
+            x, y = min(P[g], Mr[c]), min(P[c], Mr[g])       # c before g iff x < y
+            scale = max(abs(x), abs(y))
+            assert not (x < y - tol * scale), (
+                f"step {j}: recv {c} precedes the chosen recv {g} outright: {x!r} < {y!r}")
+            if x == y:
+                assert not (Mp[c] < Mp[g] - tol * max(abs(Mp[c]), abs(Mp[g]))), (
+                    f"step {j}: equal min-terms and recv {c} has the smaller M+: {Mp[c]!r} < {Mp[g]!r}")
+                assert not (Mp[c] == Mp[g] and c < g), (
+                    f"step {j}: recvs {c} and {g} tie in every term and the smaller index goes first")
+        near += 1
+        assert near <= max_restarts, "too many near ties for one sample"
+        alive[g] = 0
+        k = j + 1
+    return near

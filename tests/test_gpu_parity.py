@@ -15,7 +15,7 @@ torch = pytest.importorskip("torch")
 import oracle
 from paper_1803_03288_amd import workloads as wl
 
-from helpers import dep_bool, oracle_rounds_after_prefix, oracle_tac_rows
+from helpers import dep_bool, oracle_rounds_after_prefix, oracle_tac_rows, tac_order_up_to_near_ties
 
 RTOL = 1e-5
 
@@ -562,8 +562,9 @@ def test_times_that_are_not_quantised(tt, name):
     within 1e-5 relative of the oracle's.  The simulation, the several-channel simulation and the
     search take no decision that rounding could turn (the search is compared through the makespan of
     the order it returns); TAC can, where two sums that are equal in exact arithmetic are formed in
-    different ways, so its orders are compared sample by sample, and an order that differs must
-    still be a permutation whose makespan the oracle confirms."""
+    different ways, so its orders are compared sample by sample: an order that differs may differ
+    only where the oracle's own round calls the choice a near tie (see tac_order_up_to_near_ties), and its
+    makespan must be the one the oracle computes for it.  Two runs on the same inputs are equal byte for byte."""
     makers = dict(SMALL)
     makers.update(EXTRA)
     d, h, dep = get(tt, name, makers.get(name))
@@ -584,13 +585,17 @@ def test_times_that_are_not_quantised(tt, name):
     chan = rng.integers(0, 3, size=R).astype(np.int32)
     close(tt.simulate_channels(h, 3, chan, cuda(orders), gop, grv),
           oracle.simulate_channels(*args, 3, chan, orders, op, rv), "three channels")
-    got = tt.tac_simulate(h, gop, grv, want_rank=True)
+    got = tt.tac_simulate(h, gop, grv, want_rank=True, want_sel=True)
+    again = tt.tac_simulate(h, gop, grv, want_rank=True, want_sel=True)
+    for x, y in zip(got, again):
+        assert torch.equal(x, y), f"{name}: two runs on the same unquantised inputs differ"
     go = got[0].cpu().numpy()
     assert np.array_equal(np.sort(go, axis=1), np.tile(np.arange(R, dtype=np.int32), (B, 1)))
     eo = oracle.tac(dep, d.recv_ids, op, rv)[0]
     same = (go == eo).all(axis=1)
-    print(f"[unquantised] {name}: {int(same.sum())} of {B} TAC orders equal to the oracle's", flush=True)
-    assert same.mean() >= 0.9
+    near = [tac_order_up_to_near_ties(oracle, d, dep, op[b], rv[b], go[b]) for b in np.nonzero(~same)[0]]
+    print(f"[unquantised] {name}: {int(same.sum())} of {B} TAC orders equal to the oracle's; the others differ "
+          f"at near ties only ({near} per sample)", flush=True)
     close(got[4:], oracle.simulate(*args, go, op, rv), "fused, under the order the GPU chose")
     moves = rng.integers(0, R, size=(40, 2)).astype(np.int32)
     best, mb, ms, acc = tt.order_search(h, cuda(orders), cuda(moves), gop, grv)

@@ -654,3 +654,25 @@ def test_order_search_shared_start_order():
     b = search(d, np.repeat(start[None, :], 4, axis=0), moves, op, rv)
     for x, y in zip(a, b):
         np.testing.assert_array_equal(x, y)
+
+
+def test_near_tie_checker_accepts_the_oracle_and_rejects_a_swap():
+    """The checker that the GPU tests use on unquantised times: the oracle's own order passes with no near
+    tie; the same order with two steps exchanged is refused unless the round really is a tie."""
+    from helpers import tac_order_up_to_near_ties
+    d = wl.layered_dag(11, levels=9, width=7, fan_in=(1, 3), back=3, n_recv=70, attach=(1, 3))
+    dep = oracle.find_dependencies(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    rng = np.random.default_rng(5)
+    op = rng.lognormal(np.log(1e-3), 0.5, size=(4, d.n_compute))
+    rv = rng.lognormal(np.log(2e-3), 0.7, size=(4, d.n_recv))
+    eo = oracle.tac(dep, d.recv_ids, op, rv)[0]
+    refused = 0
+    for b in range(4):
+        assert tac_order_up_to_near_ties(oracle, d, dep, op[b], rv[b], eo[b]) == 0
+        bad = eo[b].copy()
+        bad[[3, 4]] = bad[[4, 3]]
+        try:
+            tac_order_up_to_near_ties(oracle, d, dep, op[b], rv[b], bad)
+        except AssertionError:
+            refused += 1
+    assert refused == 4
