@@ -571,7 +571,9 @@ hipError_t launch_tac_reg(Dag &d, const TacArgs &a, int32_t *flags, hipStream_t 
     if (K <= 2) return launch_reg_k<2>(p, d, s);
     if (K <= 3) return launch_reg_k<3>(p, d, s);
     if (K <= 4) return launch_reg_k<4>(p, d, s);
+    if (K <= 5) return launch_reg_k<5>(p, d, s);
     if (K <= 6) return launch_reg_k<6>(p, d, s);
+    if (K <= 7) return launch_reg_k<7>(p, d, s);
     return launch_reg_k<8>(p, d, s);
 }
 

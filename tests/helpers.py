@@ -147,7 +147,7 @@ def oracle_rounds_after_prefix(dep, recv_ids, op_row, rv_row, order_row, ks, thr
     return sel, sP[rows, sel], sM[rows, sel]
 
 
-def tac_order_up_to_near_ties(oracle, dag, dep, op_row, rv_row, got, tol=1e-9, max_restarts=64):
+def tac_order_up_to_near_ties(oracle, dag, dep, op_row, rv_row, got, tol=1e-12, max_restarts=64):
     """Checks one TAC order computed in floating point on times that are not quantised.
 
     Where `got` equals the oracle's order nothing is to show.  At the first step where they differ the
