@@ -178,6 +178,32 @@ def simulate_channels(n_ops: int, row_ptr, col_idx, recv_ids, n_channels: int, c
     return tuple(out)
 
 
+def simulate_sends(n_ops: int, row_ptr, col_idx, recv_ids, send_ids, order, op_time, recv_time, pick_key=None):
+    """Sec. 2.2: the iteration of ``simulate`` with send ops (leaves of the graph) on an uplink that carries one
+    transfer at a time, first come first served; the compute device picks the ready op of lowest ``pick_key``
+    (default: lowest op id).  ``op_time`` holds a send's transfer time in its column.
+    Returns ``(makespan, E, U, L, S)``, each ``[B]``."""
+    row_ptr, col_idx, recv_ids, send_ids = _i32(row_ptr), _i32(col_idx), _i32(recv_ids), _i32(send_ids)
+    op_time, recv_time, order = _f64(op_time), _f64(recv_time), _i32(order)
+    R = recv_ids.size
+    B = recv_time.shape[0]
+    assert op_time.shape == (B, n_ops - R) and recv_time.shape == (B, R)
+    if order.ndim == 1:
+        assert order.shape == (R,)
+        stride = 0
+    else:
+        assert order.shape == (B, R)
+        stride = R
+    key = None if pick_key is None else _i32(pick_key)
+    out = [np.zeros(B) for _ in range(5)]
+    rc = _load().oracle_simulate_sends(ctypes.c_int(n_ops), _p(row_ptr), _p(col_idx), ctypes.c_int(R), _p(recv_ids),
+                                       ctypes.c_int(send_ids.size), _p(send_ids), ctypes.c_int(B), _p(order),
+                                       ctypes.c_int(stride), _p(op_time), _p(recv_time), _p(key),
+                                       *(_p(o) for o in out))
+    _check(rc, "oracle_simulate_sends")
+    return tuple(out)
+
+
 def straggler(makespan, w: int) -> np.ndarray:
     """Sec. 6, Straggler Effect: per group of ``w`` consecutive samples, the longest wait of any
     worker over the iteration time, ``(max - min) / max`` of the group's makespans.

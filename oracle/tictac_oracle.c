@@ -20,6 +20,7 @@
  *                              channel, transfers released in priority order)
  *   oracle_simulate_channels   the same with one channel per parameter server
  *                              (Sec. 4.1, 5.1)
+ *   oracle_simulate_sends      the same with send ops on an uplink (Sec. 2.2)
  *   oracle_straggler           Sec. 6 "Straggler Effect"
  *   oracle_time_oracle_min     Sec. 5 "Time Oracle"
  *   oracle_order_search        Sec. 3.1 (the best order is NP-hard to find) and
@@ -444,6 +445,159 @@ int oracle_simulate(int n, const int32_t *row_ptr, const int32_t *col_idx, int R
         if (S_out) S_out[b] = (U == L || L == 0.0) ? 0.0 : (U - L) / L;
     }
     free(ri); free(sptr); free(sidx); free(fill); free(waiting); free(time); free(h.key); free(h.op);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * The iteration with send ops (Sec. 2.2: in the worker's graph the recv ops are roots and the
+ * send ops are leaves; they carry results back to the parameter servers).  The paper orders
+ * the recvs only and gives the sends no model of their own; the reading taken here:
+ *   - a send is a leaf of the graph whose time is a transfer time on the uplink, a third
+ *     resource beside the compute device and the (downlink) channel of oracle_simulate,
+ *     with one active transfer at a time (Sec. 5.1's rule for a channel);
+ *   - a send is requested at the instant its last predecessor finishes, and the uplink
+ *     serves requests first come first served (requests of one instant by op id);
+ *   - the compute device runs the other compute ops as in oracle_simulate, and since the
+ *     finish times of single ops now matter, so does its pick among several ready ops:
+ *     the lowest op id (pick_key NULL) or the lowest pick_key;
+ *   - makespan = finish of the last op, sends included; U = sum of all times;
+ *     L = max(sum of compute times without the sends, sum of recv times, sum of send times)
+ *     (Eq. 2: one term per resource); E and S from them as in oracle_simulate.
+ *   send_ids [n_send]: op ids; every one must be a compute op without successors.
+ *   op_time holds a send's transfer time in the send's column.
+ * ---------------------------------------------------------------------- */
+int oracle_simulate_sends(int n, const int32_t *row_ptr, const int32_t *col_idx, int R, const int32_t *recv_ids,
+                          int n_send, const int32_t *send_ids, int B, const int32_t *order, int order_stride,
+                          const double *op_time, const double *recv_time, const int32_t *pick_key,
+                          double *makespan, double *eff, double *U_out, double *L_out, double *S_out)
+{
+    const int N = n - R;
+    const size_t n1 = (size_t)(n > 0 ? n : 1);
+    int32_t *ri = recv_index_of_op(n, R, recv_ids);
+    int32_t *sptr = (int32_t *)calloc(n1 + 1, sizeof(int32_t));
+    int32_t *sidx = (int32_t *)malloc((size_t)(row_ptr[n] > 0 ? row_ptr[n] : 1) * sizeof(int32_t));
+    int32_t *fill = (int32_t *)malloc(n1 * sizeof(int32_t));
+    int32_t *waiting = (int32_t *)malloc(n1 * sizeof(int32_t));
+    uint8_t *is_send = (uint8_t *)calloc(n1, 1);
+    int32_t *queue = (int32_t *)malloc(n1 * sizeof(int32_t));       /* requests to the uplink, in service order */
+    int32_t *fresh = (int32_t *)malloc(n1 * sizeof(int32_t));       /* sends requested at the current instant */
+    double *time = (double *)malloc(n1 * sizeof(double));
+    heap_t h = { (int32_t *)malloc(n1 * sizeof(int32_t)), (int32_t *)malloc(n1 * sizeof(int32_t)), 0 };
+    if (!ri || !sptr || !sidx || !fill || !waiting || !is_send || !queue || !fresh || !time || !h.key || !h.op)
+        return ORACLE_ERR_MEM;
+    for (int v = 0; v < n; ++v)
+        for (int e = row_ptr[v]; e < row_ptr[v + 1]; ++e) sptr[col_idx[e] + 1]++;
+    for (int v = 0; v < n; ++v) sptr[v + 1] += sptr[v];
+    for (int v = 0; v < n; ++v) fill[v] = sptr[v];
+    for (int v = 0; v < n; ++v)
+        for (int e = row_ptr[v]; e < row_ptr[v + 1]; ++e) sidx[fill[col_idx[e]]++] = v;
+    for (int i = 0; i < n_send; ++i) {
+        const int v = send_ids[i];
+        if (v < 0 || v >= n || ri[v] >= 0 || is_send[v] || sptr[v + 1] != sptr[v]) return ORACLE_ERR_ARG;
+        is_send[v] = 1;
+    }
+
+    int rc = ORACLE_OK;
+    for (int b = 0; b < B && rc == ORACLE_OK; ++b) {
+        const double *ot = op_time + (size_t)b * N, *rt = recv_time + (size_t)b * R;
+        const int32_t *ord = order + (size_t)b * order_stride;
+        int j = 0;
+        double sum_c = 0.0, sum_r = 0.0, sum_s = 0.0;
+        for (int v = 0; v < n; ++v) {
+            if (ri[v] >= 0) { time[v] = rt[ri[v]]; sum_r += time[v]; }
+            else {
+                time[v] = ot[j++];
+                if (is_send[v]) sum_s += time[v]; else sum_c += time[v];
+            }
+            waiting[v] = row_ptr[v + 1] - row_ptr[v];
+        }
+        h.len = 0;
+        int q_head = 0, q_tail = 0, n_fresh = 0;
+        for (int v = 0; v < n; ++v) {
+            if (ri[v] >= 0 || waiting[v] != 0) continue;
+            if (is_send[v]) fresh[n_fresh++] = v;                   /* a send without predecessors: requested at 0 */
+            else heap_push(&h, pick_key ? pick_key[v] : v, v);
+        }
+
+        double now = 0.0, m = 0.0;
+        int k = 0;
+        double net_end = (R > 0) ? rt[ord[0]] : 0.0;
+        int running = -1, sending = -1;
+        double run_end = 0.0, send_end = 0.0;
+        int finished = 0;
+        while (finished < n) {
+            int acted = 0;
+            /* completions at the current time: their successors become ready, sends among them are requested */
+            while (k < R && net_end <= now) {
+                int v = recv_ids[ord[k]];
+                if (net_end > m) m = net_end;
+                for (int e = sptr[v]; e < sptr[v + 1]; ++e) {
+                    const int s2 = sidx[e];
+                    if (--waiting[s2] == 0) {
+                        if (is_send[s2]) fresh[n_fresh++] = s2;
+                        else heap_push(&h, pick_key ? pick_key[s2] : s2, s2);
+                    }
+                }
+                ++finished; ++k; acted = 1;
+                if (k < R) net_end = net_end + rt[ord[k]];
+            }
+            if (running >= 0 && run_end <= now) {
+                int v = running;
+                if (run_end > m) m = run_end;
+                for (int e = sptr[v]; e < sptr[v + 1]; ++e) {
+                    const int s2 = sidx[e];
+                    if (--waiting[s2] == 0) {
+                        if (is_send[s2]) fresh[n_fresh++] = s2;
+                        else heap_push(&h, pick_key ? pick_key[s2] : s2, s2);
+                    }
+                }
+                running = -1; ++finished; acted = 1;
+            }
+            if (sending >= 0 && send_end <= now) {
+                if (send_end > m) m = send_end;
+                sending = -1; ++finished; acted = 1;
+            }
+            if (running < 0 && h.len > 0) {
+                running = heap_pop(&h);
+                run_end = now + time[running];
+                acted = 1;
+            }
+            if (acted) continue;     /* something may complete or start at this same instant */
+            /* the instant is over: its requests join the queue by op id, and an idle uplink starts the next one */
+            if (n_fresh > 0) {
+                for (int a = 1; a < n_fresh; ++a) {                 /* insertion sort by op id */
+                    const int v = fresh[a];
+                    int c = a;
+                    while (c > 0 && fresh[c - 1] > v) { fresh[c] = fresh[c - 1]; --c; }
+                    fresh[c] = v;
+                }
+                for (int a = 0; a < n_fresh; ++a) queue[q_tail++] = fresh[a];
+                n_fresh = 0;
+            }
+            if (sending < 0 && q_head < q_tail) {
+                sending = queue[q_head++];
+                send_end = now + time[sending];
+                continue;            /* a send of zero time completes at this instant */
+            }
+            /* advance to the next completion */
+            double nxt = HUGE_VAL;
+            if (k < R) nxt = net_end;
+            if (running >= 0 && run_end < nxt) nxt = run_end;
+            if (sending >= 0 && send_end < nxt) nxt = send_end;
+            if (nxt == HUGE_VAL) { rc = ORACLE_ERR_CYCLE; break; }   /* ops left that can never start */
+            now = nxt;
+        }
+        double U = sum_c + sum_r + sum_s;
+        double L = sum_c > sum_r ? sum_c : sum_r;
+        if (sum_s > L) L = sum_s;
+        makespan[b] = m;
+        eff[b] = (U == L) ? 1.0 : (U - m) / (U - L);
+        if (U_out) U_out[b] = U;
+        if (L_out) L_out[b] = L;
+        if (S_out) S_out[b] = (U == L || L == 0.0) ? 0.0 : (U - L) / L;
+    }
+    free(ri); free(sptr); free(sidx); free(fill); free(waiting); free(is_send); free(queue); free(fresh);
+    free(time); free(h.key); free(h.op);
     return rc;
 }
 

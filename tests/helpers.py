@@ -190,3 +190,67 @@ def tac_order_up_to_near_ties(oracle, dag, dep, op_row, rv_row, got, tol=1e-12, 
         alive[g] = 0
         k = j + 1
     return near
+
+
+def tick_simulate_sends(dag, send_ids, order, op_row, recv_row):
+    """The iteration with send ops, simulated tick by tick for whole-number durations (a second
+    implementation for small cases; nothing in it is event-driven).  At every tick t: transfers and ops
+    whose remaining time is zero complete, which may make ops ready; the compute device, when idle, starts
+    the ready compute op of lowest id; the uplink, when idle, starts the send that was requested first
+    (lowest id among those of one tick); the downlink serves the recvs back to back in `order`.  All of
+    that is repeated within the tick until nothing changes (durations of zero), then one tick passes.
+    Returns the makespan."""
+    n = dag.n_ops
+    t_of = full_time_row(dag, op_row, recv_row).astype(np.int64)
+    assert np.array_equal(t_of, full_time_row(dag, op_row, recv_row)), "whole numbers only"
+    is_recv = np.zeros(n, dtype=bool)
+    is_recv[dag.recv_ids] = True
+    is_send = np.zeros(n, dtype=bool)
+    is_send[np.asarray(send_ids, dtype=np.int64)] = True
+    preds = [list(map(int, dag.col_idx[dag.row_ptr[v]:dag.row_ptr[v + 1]])) for v in range(n)]
+    done = np.zeros(n, dtype=bool)
+    started = np.zeros(n, dtype=bool)
+    requested_at = {}
+    down = [int(dag.recv_ids[i]) for i in order]
+    down_k, down_left = 0, (int(t_of[down[0]]) if down else 0)
+    running, run_left = -1, 0
+    sending, send_left = -1, 0
+    t, last = 0, 0
+    while not done.all():
+        changed = True
+        while changed:
+            changed = False
+            if down_k < len(down) and down_left == 0:
+                done[down[down_k]] = True
+                down_k += 1
+                down_left = int(t_of[down[down_k]]) if down_k < len(down) else 0
+                last, changed = t, True
+            if running >= 0 and run_left == 0:
+                done[running], running, last, changed = True, -1, t, True
+            if sending >= 0 and send_left == 0:
+                done[sending], sending, last, changed = True, -1, t, True
+            ready = [v for v in range(n) if not is_recv[v] and not started[v] and all(done[u] for u in preds[v])]
+            for v in ready:
+                if is_send[v] and v not in requested_at:
+                    requested_at[v] = t
+            if running < 0:
+                cand = [v for v in ready if not is_send[v]]
+                if cand:
+                    running = min(cand)
+                    started[running], run_left, changed = True, int(t_of[running]), True
+            if sending < 0:
+                cand = [v for v in requested_at if not started[v]]
+                if cand:
+                    sending = min(cand, key=lambda v: (requested_at[v], v))
+                    started[sending], send_left, changed = True, int(t_of[sending]), True
+        if done.all():
+            break
+        t += 1
+        if down_k < len(down):
+            down_left -= 1
+        if running >= 0:
+            run_left -= 1
+        if sending >= 0:
+            send_left -= 1
+        assert t < 10**6, "stuck"
+    return last

@@ -676,3 +676,114 @@ def test_near_tie_checker_accepts_the_oracle_and_rejects_a_swap():
         except AssertionError:
             refused += 1
     assert refused == 4
+
+
+# --------------------------------------------------------------------------
+# send ops on an uplink (Sec. 2.2)
+# --------------------------------------------------------------------------
+def toy_with_sends():
+    """recv1 -> op1; op2 <- {op1, recv2}; send1 <- op1; send2 <- op2 (ids 0..5 in that order of kinds)."""
+    row_ptr = np.array([0, 0, 0, 1, 3, 4, 5], dtype=np.int32)
+    col_idx = np.array([0, 2, 1, 2, 3], dtype=np.int32)
+    return (wl.Dag("toy_sends", 6, row_ptr, col_idx, np.array([0, 1], dtype=np.int32), np.ones(4), np.ones(2)),
+            np.array([4, 5], dtype=np.int32))
+
+
+def test_sends_toy_graph_by_hand():
+    g = read_golden("toy_sends.txt")
+    d, sends = toy_with_sends()
+    op, rv = g["op_time"][None], g["recv_time"][None]
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, sends)
+    for order, tag in (([0, 1], "order_0_1"), ([1, 0], "order_1_0")):
+        m, E, U, L, S = oracle.simulate_sends(*args, np.array(order, dtype=np.int32), op, rv)
+        assert m[0] == g["makespan_" + tag][0] and U[0] == g["U"][0] and L[0] == g["L"][0]
+        assert E[0] == pytest.approx(g["E_" + tag][0], abs=1e-15) and S[0] == pytest.approx(g["S"][0], abs=1e-15)
+
+
+def test_sends_without_sends_or_with_sends_of_no_duration_are_the_plain_iteration():
+    d = wl.layered_dag(21, levels=6, width=5, fan_in=(1, 3), back=2, n_recv=12, attach=(1, 2))
+    rng = np.random.default_rng(8)
+    B = 16
+    op = rng.integers(1, 50, size=(B, d.n_compute)).astype(np.float64) * wl.QUANTUM
+    rv = rng.integers(1, 80, size=(B, d.n_recv)).astype(np.float64) * wl.QUANTUM
+    orders = np.stack([rng.permutation(d.n_recv) for _ in range(B)]).astype(np.int32)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    plain = oracle.simulate(*args, orders, op, rv)
+    none = oracle.simulate_sends(*args, np.zeros(0, dtype=np.int32), orders, op, rv)
+    for a, b in zip(plain, none):
+        assert np.array_equal(a, b)
+    # leaves turned into sends that take no time: nothing else moves, and U, L lose nothing
+    succ = np.bincount(d.col_idx, minlength=d.n_ops)
+    leaves = np.array([v for v in d.compute_ids() if succ[v] == 0], dtype=np.int32)
+    assert leaves.size >= 2
+    cols = np.searchsorted(d.compute_ids(), leaves)
+    op0 = op.copy()
+    op0[:, cols] = 0.0
+    a = oracle.simulate(*args, orders, op0, rv)
+    b = oracle.simulate_sends(*args, leaves, orders, op0, rv)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_sends_chain_is_the_two_machine_flow_shop():
+    """recv -> c_1 -> c_2 -> ... -> c_k with a send after every c_i: the compute device and the uplink form
+    the textbook two-machine flow shop in the order of the chain, C1_i = C1_{i-1} + a_i (after the recv),
+    C2_i = max(C2_{i-1}, C1_i) + s_i."""
+    k = 9
+    n = 1 + 2 * k
+    pred = {}
+    for i in range(k):
+        pred[1 + i] = [0] if i == 0 else [i]              # c_i = op 1 + i
+        pred[1 + k + i] = [1 + i]                          # send_i = op 1 + k + i
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col = []
+    for v in range(n):
+        col += pred.get(v, [])
+        row_ptr[v + 1] = len(col)
+    d = wl.Dag("chain_sends", n, row_ptr, np.array(col, dtype=np.int32), np.array([0], dtype=np.int32),
+               np.ones(2 * k), np.ones(1))
+    sends = np.arange(1 + k, n, dtype=np.int32)
+    rng = np.random.default_rng(9)
+    B = 32
+    op = rng.lognormal(0.0, 0.8, size=(B, 2 * k))
+    rv = rng.lognormal(0.0, 0.5, size=(B, 1))
+    m = oracle.simulate_sends(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, sends, np.zeros(1, dtype=np.int32), op, rv)[0]
+    for b in range(B):
+        c1, c2 = rv[b, 0], 0.0
+        for i in range(k):
+            c1 = c1 + op[b, i]
+            c2 = max(c2, c1) + op[b, k + i]
+        assert m[b] == pytest.approx(max(c1, c2), rel=1e-14)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_sends_equal_a_tick_by_tick_simulation(seed):
+    from helpers import tick_simulate_sends
+    rng = np.random.default_rng(100 + seed)
+    d = wl.layered_dag(300 + seed, levels=int(rng.integers(2, 5)), width=int(rng.integers(2, 5)), fan_in=(1, 3),
+                       back=2, n_recv=int(rng.integers(1, 6)), attach=(1, 2))
+    succ = np.bincount(d.col_idx, minlength=d.n_ops)
+    leaves = [int(v) for v in d.compute_ids() if succ[v] == 0]
+    sends = np.array([v for v in leaves if rng.random() < 0.7] or leaves[:1], dtype=np.int32)
+    B = 6
+    op = rng.integers(0, 6, size=(B, d.n_compute)).astype(np.float64)       # zeros included
+    rv = rng.integers(0, 7, size=(B, d.n_recv)).astype(np.float64)
+    orders = np.stack([rng.permutation(d.n_recv) for _ in range(B)]).astype(np.int32)
+    m = oracle.simulate_sends(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, sends, orders, op, rv)[0]
+    for b in range(B):
+        assert m[b] == tick_simulate_sends(d, sends, orders[b], op[b], rv[b]), (seed, b)
+
+
+def test_sends_the_pick_of_the_compute_device_matters():
+    """Without sends the makespan does not depend on which ready op the device takes; with sends it does,
+    which is why the pick is part of the reading: two ready ops, the one with the long send behind it should
+    go first."""
+    # recv0 -> a (op 1), recv0 -> b (op 2); send after a (op 3, long), send after b (op 4, short)
+    row_ptr = np.array([0, 0, 1, 2, 3, 4], dtype=np.int32)
+    col_idx = np.array([0, 0, 1, 2], dtype=np.int32)
+    args = (5, row_ptr, col_idx, np.array([0], dtype=np.int32), np.array([3, 4], dtype=np.int32), np.zeros(1, dtype=np.int32))
+    op = np.array([[2.0, 2.0, 10.0, 1.0]])
+    rv = np.array([[1.0]])
+    low = oracle.simulate_sends(*args, op, rv)[0][0]                                      # a first: 1..3, send 3..13; b 3..5, send 13..14
+    high = oracle.simulate_sends(*args, op, rv, pick_key=np.array([0, 2, 1, 0, 0]))[0][0]   # b first: 1..3, send 3..4; a 3..5, send 5..15
+    assert low == 14.0 and high == 15.0
