@@ -228,6 +228,28 @@ int tictac_simulate_channels(const tictac_dag *dag, int32_t B, int32_t n_channel
                              double *S, tictac_stream stream);
 
 /*
+ * Sec. 2.2: in the worker's graph the recv ops are the roots and the send ops the leaves (they carry results
+ * back to the parameter servers).  One iteration under a transfer order as in tictac_simulate, with the ops
+ * send_ids as sends: a send's time (its column of op_time) is a transfer time on the uplink, a third
+ * resource beside the compute device and the channel of the recvs, which carries one transfer at a time
+ * (Sec. 5.1) and serves the sends first come first served, a send being requested at the instant its last
+ * predecessor finishes.  The finish times of single compute ops matter here, so the pick of the compute
+ * device is part of the definition: whenever it is idle it starts the ready compute op of lowest op id.
+ *   send_ids  HOST, [n_send] op ids: compute ops without successors, each once (TICTAC_ERR_BAD_CSR
+ *             otherwise).  n_send = 0 gives the results of tictac_simulate.  The tables for a send set are
+ *             built at the first call with it (the call then waits for the stream once).
+ *   makespan  finish of the last op, sends included;  U = sum of all times (Eq. 1);
+ *   L = max(compute times without the sends, transfer times of the recvs, transfer times of the sends)
+ *   (Eq. 2: one term per resource);  E, S from them (Eq. 3, 4).  U, L, S may be NULL.
+ * Orders are checked as for tictac_simulate (tictac_dag_check_orders).  Graphs whose per-sample state
+ * (2 bytes per op, 12 per recv) exceeds the LDS of a compute unit: TICTAC_ERR_UNSUPPORTED.  B = 0 is valid.
+ */
+int tictac_simulate_sends(const tictac_dag *dag, int32_t B, int32_t n_send, const int32_t *send_ids,
+                          const int32_t *order, int32_t order_stride, const double *op_time,
+                          const double *recv_time, double *makespan, double *eff, double *U, double *L, double *S,
+                          tictac_stream stream);
+
+/*
  * Sec. 6, "Straggler Effect": workers that run one synchronous iteration together wait
  * for the slowest one; the effect is the longest wait of any worker as a fraction of the
  * iteration time.  The workers of group g are the w consecutive samples g*w .. g*w+w-1:

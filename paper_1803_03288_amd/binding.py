@@ -33,7 +33,7 @@ EXPORTS = (
     "tictac_tic_priority", "tictac_tac_priority", "tictac_simulate", "tictac_tac_simulate",
     "tictac_tac_simulate_noalloc",
     "tictac_simulate_f32", "tictac_tac_simulate_f32",
-    "tictac_simulate_channels", "tictac_straggler_effect", "tictac_time_oracle_min", "tictac_order_search",
+    "tictac_simulate_channels", "tictac_simulate_sends", "tictac_straggler_effect", "tictac_time_oracle_min", "tictac_order_search",
     "tictac_last_error", "tictac_version",
 )
 
@@ -229,6 +229,27 @@ def time_oracle_min(runs: torch.Tensor) -> torch.Tensor:
     out = torch.empty(runs.shape[1:], dtype=torch.float64, device="cuda")
     _check(lib().tictac_time_oracle_min(ctypes.c_int32(K), ctypes.c_int64(out.numel()), _dev(runs), _dev(out), _stream()))
     return out
+
+
+def simulate_sends(dag: Dag, send_ids, order: torch.Tensor, op_time: torch.Tensor, recv_time: torch.Tensor):
+    """``tictac_simulate_sends``: ``(makespan, eff, U, L, S)``, float64 CUDA tensors ``[B]``.  ``send_ids`` is a host
+    int32 array of op ids (leaves of the graph); ``order`` is int32 ``[R]`` or ``[B][R]``."""
+    B = _check_times(dag, op_time, recv_time)
+    R = dag.n_recv
+    sends = np.ascontiguousarray(send_ids, dtype=np.int32)
+    assert sends.ndim == 1
+    assert order.is_cuda and order.dtype == torch.int32 and order.is_contiguous()
+    if order.dim() == 1:
+        assert order.shape[0] == R
+        stride = 0
+    else:
+        assert tuple(order.shape) == (B, R)
+        stride = R
+    out = [torch.empty(B, dtype=torch.float64, device=recv_time.device) for _ in range(5)]
+    _check(lib().tictac_simulate_sends(dag._h, ctypes.c_int32(B), ctypes.c_int32(sends.size),
+                                       sends.ctypes.data_as(ctypes.c_void_p), _dev(order), ctypes.c_int32(stride),
+                                       _dev(op_time), _dev(recv_time), *(_dev(o) for o in out), _stream()))
+    return tuple(out)
 
 
 def order_search(dag: Dag, order: torch.Tensor, moves: torch.Tensor, op_time: torch.Tensor, recv_time: torch.Tensor):

@@ -202,7 +202,7 @@ static hipError_t ensure_chan_table(Dag *d, const int32_t *chan, hipStream_t s)
 static void free_dag(Dag *d)
 {
     if (!d) return;
-    void *ptrs[] = {d->d_graph_block, d->d_class_block, d->d_work, d->d_chan};
+    void *ptrs[] = {d->d_graph_block, d->d_class_block, d->d_work, d->d_chan, d->d_send_block};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete d;
@@ -390,6 +390,9 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     for (int32_t v = 0; v < n; ++v) src[v] = recv_of_op[v] >= 0 ? ~recv_of_op[v] : rep[v];
 
     d->n = n; d->R = R; d->W = (R + 63) / 64; d->N = n - R; d->E = E;
+    d->h_row_ptr.assign(row_ptr, row_ptr + n + 1);
+    d->h_col_idx.assign(col_idx, col_idx + E);
+    d->h_recv_ids.assign(recv_ids, recv_ids + R);
     d->n_levels = n_levels;
     d->M = M; d->n_node_levels = n_node_levels; d->max_node_level_width = max_width;
     HIP_TRY(hipGetDevice(&d->device));
@@ -1144,6 +1147,109 @@ int tictac_dag_check_orders(tictac_dag *dag, tictac_stream stream)
     HIP_TRY(hipMemsetAsync(d->d_bad_order, 0, sizeof(int32_t), s));
     set_error("an order given since the last check was no permutation of 0 .. n_recv-1");
     return TICTAC_ERR_BAD_ORDER;
+}
+
+// Tables of the iteration with send ops for the given send set (kept until another set is given).
+// TICTAC_OK, or the status to return (the error text is set).
+static int ensure_send_tables(Dag *d, int32_t n_send, const int32_t *send_ids, hipStream_t s)
+{
+    if (d->send_tables_built && d->h_send_ids.size() == (size_t)n_send &&
+        (n_send == 0 || memcmp(d->h_send_ids.data(), send_ids, (size_t)n_send * sizeof(int32_t)) == 0))
+        return TICTAC_OK;
+    const int32_t n = d->n, E = d->E;
+    std::vector<int32_t> recv_of_op(n, -1), col_of_op(n, -1), n_succ(n, 0);
+    for (int32_t i = 0; i < d->R; ++i) recv_of_op[d->h_recv_ids[i]] = i;
+    for (int32_t v = 0, j = 0; v < n; ++v)
+        if (recv_of_op[v] < 0) col_of_op[v] = j++;
+    for (int32_t e = 0; e < E; ++e) n_succ[d->h_col_idx[e]]++;
+    std::vector<uint8_t> is_send(n, 0);
+    for (int32_t i = 0; i < n_send; ++i) {
+        const int32_t v = send_ids[i];
+        if (v < 0 || v >= n) { set_error("send_ids[%d] = %d is no op id", i, v); return TICTAC_ERR_BAD_CSR; }
+        if (recv_of_op[v] >= 0) { set_error("send_ids[%d] = %d is a recv op", i, v); return TICTAC_ERR_BAD_CSR; }
+        if (is_send[v]) { set_error("send_ids holds op %d twice", v); return TICTAC_ERR_BAD_CSR; }
+        if (n_succ[v] != 0) {
+            set_error("send op %d has successors (Sec. 2.2: the send ops are leaves)", v);
+            return TICTAC_ERR_BAD_CSR;
+        }
+        is_send[v] = 1;
+    }
+    std::vector<int4> rec(n);
+    std::vector<int32_t> succ(E > 0 ? E : 1), fill(n), send_free;
+    std::vector<uint16_t> indeg(n);
+    std::vector<uint32_t> ready0(((size_t)n + 31) / 32, 0u);
+    std::vector<uint8_t> col_kind(d->N > 0 ? d->N : 1, 0);
+    int32_t at = 0;
+    for (int32_t v = 0; v < n; ++v) {
+        rec[v] = make_int4(at, n_succ[v], col_of_op[v], is_send[v]);
+        fill[v] = at;
+        at += n_succ[v];
+        const int32_t deg = d->h_row_ptr[v + 1] - d->h_row_ptr[v];
+        if (deg > 65535) { set_error("op %d has %d predecessors, more than 65535", v, deg); return TICTAC_ERR_UNSUPPORTED; }
+        indeg[v] = (uint16_t)deg;
+        if (recv_of_op[v] < 0 && deg == 0) {
+            if (is_send[v]) send_free.push_back(col_of_op[v]);
+            else ready0[v >> 5] |= 1u << (v & 31);
+        }
+        if (is_send[v]) col_kind[col_of_op[v]] = 1;
+    }
+    for (int32_t v = 0; v < n; ++v)
+        for (int32_t e = d->h_row_ptr[v]; e < d->h_row_ptr[v + 1]; ++e) succ[fill[d->h_col_idx[e]]++] = v;
+
+    Packer tables;
+    tables.add(&d->d_send_rec, rec);
+    tables.add(&d->d_send_succ, succ);
+    tables.add(&d->d_send_indeg, indeg);
+    tables.add(&d->d_send_ready0, ready0);
+    tables.add(&d->d_send_free, send_free);
+    tables.add(&d->d_send_col_kind, col_kind);
+    tables.add(&d->d_send_recv_ids, d->h_recv_ids);
+    d->n_send_free = (int32_t)send_free.size();
+    d->send_tables_built = false;
+    HIP_TRY(hipStreamSynchronize(s));               // no kernel reads the old tables any more
+    if (d->d_send_block) { (void)hipFree(d->d_send_block); d->d_send_block = nullptr; }
+    HIP_TRY(tables.commit(&d->d_send_block, s));
+    HIP_TRY(hipStreamSynchronize(s));               // the copy came out of `tables`, which ends here
+    d->h_send_ids.assign(send_ids, send_ids + n_send);
+    d->send_tables_built = true;
+    return TICTAC_OK;
+}
+
+int tictac_simulate_sends(const tictac_dag *dag, int32_t B, int32_t n_send, const int32_t *send_ids,
+                          const int32_t *order, int32_t order_stride, const double *op_time,
+                          const double *recv_time, double *makespan, double *eff, double *U, double *L, double *S,
+                          tictac_stream stream)
+{
+    if (!dag) { set_error("dag is NULL"); return TICTAC_ERR_NULL; }
+    Dag *d = const_cast<Dag *>(reinterpret_cast<const Dag *>(dag));
+    int rc = check_batch(d, B, op_time, recv_time);
+    if (rc != TICTAC_OK) return rc;
+    if (n_send < 0) { set_error("n_send = %d is negative", n_send); return TICTAC_ERR_BAD_CSR; }
+    if (n_send > 0 && !send_ids) { set_error("send_ids is NULL"); return TICTAC_ERR_NULL; }
+    if (order_stride != 0 && order_stride != d->R) {
+        set_error("order_stride = %d, expected 0 or n_recv = %d", order_stride, d->R);
+        return TICTAC_ERR_BAD_ORDER;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    rc = ensure_send_tables(d, n_send, send_ids, s);
+    if (rc != TICTAC_OK) return rc;
+    if (B == 0) return TICTAC_OK;
+    if (d->R > 0 && !order) { set_error("order is NULL"); return TICTAC_ERR_NULL; }
+    if (!makespan || !eff) { set_error("makespan or eff is NULL"); return TICTAC_ERR_NULL; }
+    if (d->n == 0) {
+        SimArgs a0{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
+        HIP_TRY(launch_simulate(*d, a0, s));        // the empty graph: nothing to send
+        return TICTAC_OK;
+    }
+    SimArgs a{B, order, order_stride, op_time, recv_time, makespan, eff, U, L, S};
+    HIP_TRY(launch_check_orders(*d, B, order, order_stride, s));
+    const hipError_t e = launch_simulate_sends(*d, a, s);
+    if (e == hipErrorNotSupported) {
+        set_error("%d ops and %d recvs: the per-sample state of the iteration with send ops does not fit LDS", d->n, d->R);
+        return TICTAC_ERR_UNSUPPORTED;
+    }
+    HIP_TRY(e);
+    return TICTAC_OK;
 }
 
 int tictac_straggler_effect(int32_t B, int32_t w, const double *makespan, double *straggler, tictac_stream stream)

@@ -133,6 +133,17 @@ struct Dag {
     void *d_work = nullptr;
     int32_t *d_chan = nullptr;      // [R] channel table of the last several-channel simulation
     std::vector<int32_t> h_chan;    // its host copy
+    // The graph as given (predecessor lists), kept for the tables of the iteration with send ops, which are
+    // built for the send set of the last such call (one device block; see k6_sends.hip for the arrays).
+    std::vector<int32_t> h_row_ptr, h_col_idx, h_recv_ids, h_send_ids;
+    bool send_tables_built = false;
+    void *d_send_block = nullptr;
+    int4 *d_send_rec = nullptr;
+    int32_t *d_send_succ = nullptr, *d_send_free = nullptr, *d_send_recv_ids = nullptr;
+    uint16_t *d_send_indeg = nullptr;
+    uint32_t *d_send_ready0 = nullptr;
+    uint8_t *d_send_col_kind = nullptr;
+    int32_t n_send_free = 0;
     size_t work_bytes = 0;
 };
 
@@ -202,6 +213,8 @@ struct SimArgs {
 // raises *d.d_bad_order when a row of `order` (B rows, or one when order_stride = 0) is no permutation of 0 .. R-1
 hipError_t launch_check_orders(Dag &d, int32_t B, const int32_t *order, int32_t order_stride, hipStream_t s);
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
+// (needs the tables d_send_*; hipErrorNotSupported when the per-sample state does not fit LDS)
+hipError_t launch_simulate_sends(Dag &d, const SimArgs &a, hipStream_t s);
 hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels, const int32_t *chan, hipStream_t s);
 hipError_t launch_time_oracle_min(int32_t n_runs, int64_t n, const double *runs, double *time, hipStream_t s);
 hipError_t launch_straggler(int32_t B, int32_t w, const double *makespan, double *out, hipStream_t s);
