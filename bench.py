@@ -170,7 +170,7 @@ def main() -> int:
             h, res = step(True)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        tac_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+        tac_ms = float(np.median([a.elapsed_time(b) for a, b in events]))
         build_ms = timed(lambda: tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids), 3)
         tic_ms = timed(lambda: tt.tic_priority(h), 3)
         k1_ms = timed(h.recompute_deps, 5, skip=2)
@@ -201,7 +201,7 @@ def main() -> int:
                 continue
             dd = wl.preset(name)
             k = 3 if name in ("stress",) else 5
-            out = measure(name, dd.batch, k, 1)
+            out = measure(name, dd.batch, k, 2)
             per_config[name] = out[-1]
             log(f"{name}: {out[-1]['schedules_per_s']:.4g} schedules/s, fused call {out[-1]['tac_simulate_ms']:.3f} ms")
             del out
@@ -270,6 +270,32 @@ def main() -> int:
         channels = {"n_channels": 4, "ms_per_launch": c_ms, "hbm_GBs": c_bytes / (c_ms * 1e-3) / 1e9,
                     "frac_of_hbm_peak": c_bytes / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "mean_makespan_s": float(rc_[0].mean()), "mean_efficiency": float(rc_[1].mean())}
+
+    # ---- send ops: the same graph with a send behind R compute ops drawn at random, on an uplink ----
+    sends_leg = None
+    if not args.no_compare and small:
+        rng_s = np.random.default_rng(d.seed + 99)
+        k_s = d.n_recv
+        behind = np.sort(rng_s.choice(d.compute_ids(), size=k_s, replace=False)).astype(np.int32)
+        row2 = np.concatenate([d.row_ptr, d.row_ptr[-1] + 1 + np.arange(k_s, dtype=np.int32)]).astype(np.int32)
+        col2 = np.concatenate([d.col_idx, behind]).astype(np.int32)
+        send_ids = np.arange(d.n_ops, d.n_ops + k_s, dtype=np.int32)
+        h2 = tt.build_deps(d.n_ops + k_s, row2, col2, d.recv_ids)
+        Bs = min(B, 16384)
+        # a send moves what a recv moves (the gradient of a parameter has the parameter's size)
+        send_t = grv[:Bs].index_select(1, torch.from_numpy(rng_s.permutation(d.n_recv)).cuda())
+        op2 = torch.cat([gop[:Bs], send_t], dim=1).contiguous()
+        rv2 = grv[:Bs].contiguous()
+        ord2 = order_tac[:Bs].contiguous()
+        q_ms = timed(lambda: tt.simulate_sends(h2, send_ids, ord2, op2, rv2), 2)
+        rs_ = tt.simulate_sends(h2, send_ids, ord2, op2, rv2)
+        sends_leg = {"n_send": int(k_s), "samples": int(Bs), "ms_per_launch": q_ms, "samples_per_s": Bs / (q_ms * 1e-3),
+                     "ns_per_op_and_sample": q_ms * 1e6 / Bs / (d.n_compute + k_s),
+                     "mean_makespan_s": float(rs_[0].mean()), "mean_efficiency": float(rs_[1].mean()),
+                     "mean_makespan_without_sends_s": float(out[0][:Bs].mean()),
+                     "note": "compute device followed op by op (lowest ready op id first), TAC orders"}
+        h2.close()
+        del op2, rv2, ord2, send_t
 
     # ---- order search: every sample climbs from its random order through proposed exchanges ----
     search = None
@@ -429,7 +455,7 @@ def main() -> int:
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": head["workload"] + "; step = build_deps + TIC + fused TAC/simulate"},
         "roofline": roofline, "cpu_baseline": cpu, "per_config": per_config,
-        "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels,
+        "simulate": simulate, "dep_bitset": dep_bitset, "order_comparison": comparison, "simulate_channels": channels, "simulate_sends": sends_leg,
         "time_oracle_min": time_oracle, "order_search": search, "float32_storage": f32,
         "mean_scheduling_efficiency": head["mean_scheduling_efficiency"],
     }
