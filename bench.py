@@ -344,6 +344,9 @@ def main() -> int:
     cy = torch.empty_like(cx)
     copy_ms = timed(lambda: torch.add(cx, 1.0, out=cy), 4, skip=2)
     copy_GBs = 2.0 * cx.numel() * 8 / (copy_ms * 1e-3) / 1e9
+    # (the propagation only writes: the rate of a plain fill on the same box stands beside it)
+    fill_ms = timed(lambda: cy.fill_(1.0), 4, skip=2)
+    fill_GBs = cy.numel() * 8 / (fill_ms * 1e-3) / 1e9
     del cx, cy
     simulate["frac_of_device_copy"] = simulate["hbm_GBs"] / copy_GBs
 
@@ -360,7 +363,8 @@ def main() -> int:
                       "target_frac_of_hbm_peak": 0.5, "target_met": bool(gbs / HBM_PEAK_GBS >= 0.5),
                       "us_per_level": k1_ms * 1e3 / max(hs.n_levels, 1),
                       "note": "one graph is a chain of dependent levels: its time is levels x per-level latency, not bytes",
-                      "frac_of_device_copy": gbs / copy_GBs, "device_copy_GB/s": copy_GBs}
+                      "frac_of_device_copy": gbs / copy_GBs, "device_copy_GB/s": copy_GBs,
+                      "device_fill_GB/s": fill_GBs}
         if args.deps_batch > 1 and hasattr(tt, "recompute_deps_batch"):
             # beyond the configuration: G instances of the graph, propagated by one launch
             for G in sorted({max(2, args.deps_batch // 2), args.deps_batch, args.deps_batch * 2}):
@@ -370,6 +374,7 @@ def main() -> int:
                     {"instances": G, "us_per_launch": b_ms * 1e3, "GB/s": G * alg_bytes / (b_ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": G * alg_bytes / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "target_met": bool(G * alg_bytes / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS >= 0.5),
+                     "frac_of_device_fill": G * alg_bytes / (b_ms * 1e-3) / 1e9 / fill_GBs,
                      "note": "G independent graphs in one launch, HIP events; beyond the configuration"})
                 for hh in hb[1:]:
                     hh.close()

@@ -376,8 +376,9 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
 // device that never idles while an op is ready finishes at
 //     max( latest arrival,  max over classes c of  rho_c + sum of the times of the classes with rho >= rho_c ).
 // One wave per sample: arrivals by one wave scan per channel, rho by range maxima over the
-// arrival array (runs of the class rows), the last step by comparing every class with every
-// class (lane l owns classes l, l + 64, ...; the pairs (rho, time) are broadcast from LDS).
+// arrival array (runs of the class rows), the last step by comparing every class with every class
+// (lane l owns classes l, l + 64, ...; the pairs (rho, time) are broadcast from LDS) or, with more than 256
+// classes, by sorting the classes by rho in registers and one suffix sum over the sorted order.
 struct SimChanParams {
     int32_t B, R, C, N, n_waves, wave_bytes, levels, n_channels, chan_bytes;
     const int32_t *col_cls, *run_ptr, *run_lo, *run_hi;
@@ -388,6 +389,50 @@ struct SimChanParams {
     int32_t f32;
     double *makespan, *eff, *U, *L, *S;
 };
+
+// Sorts the 64 KP pairs (key, val) of a wave by key, ascending; element e = k * 64 + lane sits in register k of
+// its lane.  A bitonic network: partners at a distance below 64 exchange through the cross-lane permute, larger
+// distances are between registers of one lane.  A pair moves as a whole and only when the keys differ, so pairs
+// with equal keys are never mixed up.
+template <int KP>
+__device__ __forceinline__ void wave_sort_pairs(double (&key)[KP], double (&val)[KP], int lane)
+{
+#pragma unroll
+    for (int size = 2; size <= 64 * KP; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            if (stride < 64) {
+#pragma unroll
+                for (int k = 0; k < KP; ++k) {
+                    const int e = k * 64 + lane;
+                    const bool keep_min = ((e & stride) == 0) == ((e & size) == 0);
+                    const double pk = __hiloint2double(__shfl_xor(__double2hiint(key[k]), stride),
+                                                       __shfl_xor(__double2loint(key[k]), stride));
+                    const double pv = __hiloint2double(__shfl_xor(__double2hiint(val[k]), stride),
+                                                       __shfl_xor(__double2loint(val[k]), stride));
+                    const bool take = keep_min ? pk < key[k] : pk > key[k];
+                    key[k] = take ? pk : key[k];
+                    val[k] = take ? pv : val[k];
+                }
+            } else {
+                const int dk = stride >> 6;
+#pragma unroll
+                for (int k = 0; k < KP; ++k) {
+                    if ((k & dk) == 0) {
+                        const int k2 = k | dk;
+                        const bool ascending = ((k * 64) & size) == 0;
+                        const bool swap = ascending ? key[k2] < key[k] : key[k2] > key[k];
+                        const double tk = key[k], tv = val[k];
+                        key[k] = swap ? key[k2] : tk;
+                        val[k] = swap ? val[k2] : tv;
+                        key[k2] = swap ? tk : key[k2];
+                        val[k2] = swap ? tv : val[k2];
+                    }
+                }
+            }
+        }
+    }
+}
 
 template <int KT>
 __global__ void __launch_bounds__(256)
@@ -501,23 +546,48 @@ simulate_channels_kernel(const SimChanParams p)
                 }                                                                         \
                 rho_##k = m;                                                              \
             }                                                                             \
-            pairs[2 * (k * 64 + lane)] = rho_##k;                                         \
-            pairs[2 * (k * 64 + lane) + 1] = ct_##k;                                      \
+            if constexpr (KT < 5) {                                                       \
+                pairs[2 * (k * 64 + lane)] = rho_##k;                                     \
+                pairs[2 * (k * 64 + lane) + 1] = ct_##k;                                  \
+            }                                                                             \
         }
         SW_EACH_K(SC_RHO)
         wave_sync();
 
-        // ---- every class against every class ----
-#define SC_ACC_DECL(k) double w_##k = 0.0;
-        SW_EACH_K(SC_ACC_DECL)
-        for (int c = 0; c < C; ++c) {
-            const double2 pr = *reinterpret_cast<const double2 *>(pairs + 2 * c);   // the same for every lane
-#define SC_ACC(k) if constexpr (k < KT) { w_##k += pr.x >= rho_##k ? pr.y : 0.0; }
-            SW_EACH_K(SC_ACC)
-        }
+        // ---- the compute device: makespan = max over classes of (release date + time of the classes released
+        // then or later) ----
         double mloc = last_arrival, ct_sum = 0.0;
+        if constexpr (KT < 5) {
+            // few classes: every class against every class (pairs broadcast from LDS)
+#define SC_ACC_DECL(k) double w_##k = 0.0;
+            SW_EACH_K(SC_ACC_DECL)
+            for (int c = 0; c < C; ++c) {
+                const double2 pr = *reinterpret_cast<const double2 *>(pairs + 2 * c);   // the same for every lane
+#define SC_ACC(k) if constexpr (k < KT) { w_##k += pr.x >= rho_##k ? pr.y : 0.0; }
+                SW_EACH_K(SC_ACC)
+            }
 #define SC_MAX(k) if constexpr (k < KT) { if (k * 64 + lane < C) mloc = fmax(mloc, rho_##k + w_##k); ct_sum += ct_##k; }
-        SW_EACH_K(SC_MAX)
+            SW_EACH_K(SC_MAX)
+        } else {
+            // many classes: sorted by release date in registers, a suffix sum gives the second term (classes
+            // released at the same instant: the first of them in the sorted order carries the whole group)
+            constexpr int KP = 8;
+            double key[KP], val[KP];
+#pragma unroll
+            for (int k = 0; k < KP; ++k) { key[k] = -1.0; val[k] = 0.0; }     // (release dates are >= 0)
+#define SC_KEYS(k) if constexpr (k < KT) { if (k * 64 + lane < C) { key[k] = rho_##k; val[k] = ct_##k; } ct_sum += ct_##k; }
+            SW_EACH_K(SC_KEYS)
+            wave_sort_pairs<KP>(key, val, lane);
+            double sfx = 0.0;
+#pragma unroll
+            for (int k = KP - 1; k >= 0; --k) {
+                const double inc = wave_incl_scan_f64_dpp(val[k]);
+                const double tot = lane63_f64(inc);
+                const double w = sfx + (tot - inc + val[k]);        // this element and everything after it
+                if (key[k] >= 0.0) mloc = fmax(mloc, key[k] + w);
+                sfx += tot;
+            }
+        }
         const double m = wave_max_f64_dpp(mloc);
         const double sum_c = wave_sum_f64_dpp(ct_sum);
         if (lane == 0) {
