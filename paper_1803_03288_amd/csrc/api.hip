@@ -264,6 +264,50 @@ static void group_classes(const std::vector<uint64_t> &rows, int32_t N, int32_t 
         }
 }
 
+// The same grouping from per-op digests (int32[8] per op: a 128-bit hash of the row in the first four words, the
+// number of set bits in the fifth): ops with equal digests form a class.  first_col: the first member of every
+// class (piece), whose row is the row of the class.
+static void group_digests(const int32_t *digest, int32_t N, int32_t max_members, std::vector<int32_t> &cls_ptr,
+                          std::vector<int32_t> &cls_cols, std::vector<int32_t> &first_col, int32_t &n_distinct)
+{
+    size_t cap = 16;
+    while (cap < (size_t)N * 2) cap <<= 1;
+    std::vector<int32_t> slot(cap, -1), first, cls_of(N), count;
+    for (int32_t j = 0; j < N; ++j) {
+        const int32_t *g = digest + (size_t)j * 8;
+        size_t q = ((uint32_t)g[0] ^ ((size_t)(uint32_t)g[1] << 17) ^ ((size_t)(uint32_t)g[3] << 33)) & (cap - 1);
+        for (;;) {
+            const int32_t c = slot[q];
+            if (c < 0) {
+                slot[q] = (int32_t)first.size();
+                cls_of[j] = (int32_t)first.size();
+                first.push_back(j);
+                count.push_back(1);
+                break;
+            }
+            if (memcmp(digest + (size_t)first[c] * 8, g, 5 * sizeof(int32_t)) == 0) {
+                cls_of[j] = c;
+                ++count[c];
+                break;
+            }
+            q = (q + 1) & (cap - 1);
+        }
+    }
+    n_distinct = (int32_t)first.size();
+    std::vector<int32_t> start(n_distinct + 1, 0);
+    for (int32_t c = 0; c < n_distinct; ++c) start[c + 1] = start[c] + count[c];
+    std::vector<int32_t> members(N), fill(start.begin(), start.end() - 1);
+    for (int32_t j = 0; j < N; ++j) members[fill[cls_of[j]]++] = j;
+    cls_ptr.assign(1, 0); cls_cols.clear(); first_col.clear();
+    for (int32_t c = 0; c < n_distinct; ++c)
+        for (int32_t k = start[c]; k < start[c + 1]; k += max_members) {
+            const int32_t e = std::min(start[c + 1], k + max_members);
+            for (int32_t m = k; m < e; ++m) cls_cols.push_back(members[m]);
+            cls_ptr.push_back((int32_t)cls_cols.size());
+            first_col.push_back(first[c]);
+        }
+}
+
 static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int32_t R, const int32_t *recv_ids,
                  hipStream_t s, Dag *d)
 {
@@ -649,6 +693,10 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         }
     }
     graph.add(&d->d_copied, copied);
+    std::vector<int32_t> op_of_col(d->N);
+    for (int32_t v = 0; v < n; ++v)
+        if (comp_col[v] >= 0) op_of_col[comp_col[v]] = v;
+    graph.add(&d->d_op_of_col, op_of_col);
     const size_t dep_words = (size_t)n * d->W;
     graph.reserve(&d->d_dep, dep_words * 8);
     if (d->k1_lring > 0)
@@ -661,48 +709,79 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     HIP_TRY(hipMemsetAsync(d->d_bad_order, 0, 256, s));
     if (dep_words) HIP_TRY(launch_propagate(*d, s));
 
-    // ---- classes of identical rows among the compute ops ----
-    std::vector<uint64_t> rows((size_t)d->N * d->W);
-    if (!rows.empty()) {
-        std::vector<uint64_t> pageable;
-        uint64_t *all = static_cast<uint64_t *>(stage(dep_words * 8));   // stream order: after the copy of the graph block out of it
-        if (!all) {
-            pageable.resize(dep_words);
-            all = pageable.data();
-        }
-        HIP_TRY(hipMemcpyAsync(all, d->d_dep, dep_words * 8, hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        for (int32_t v = 0; v < n; ++v)
-            if (comp_col[v] >= 0)
-                memcpy(&rows[(size_t)comp_col[v] * d->W], &all[(size_t)v * d->W], (size_t)d->W * 8);
-    }
-    std::vector<uint64_t> cls_dep;
-    std::vector<int32_t> cls_ptr, cls_cols;
+    // ---- classes of identical rows among the compute ops (a lambda: done again on the host when the device's
+    // grouping cannot be used; returns a status, or 1 for "again, from the rows") ----
+    auto classes = [&](const bool on_device) -> int {
+    // Large graphs (8 MB of rows or more) are grouped without bringing the rows to the host: the device hashes
+    // every row (128 bits, with the number of set bits and the lowest one), the host groups the hashes, and the
+    // device forms the class rows and checks every op's row against its class (on a mismatch, which two
+    // different rows with one hash would cause, everything below is done again from the rows themselves).
+    std::vector<uint64_t> rows, cls_dep, depT;
+    std::vector<int32_t> cls_ptr, cls_cols, cnt0, first_op, lowest;
     // only classes far larger than a lane's fair share of the ops are split
     const int32_t max_members = std::min(256, std::max(16, (d->N + 63) / 64));
-    group_classes(rows, d->N, d->W, max_members, cls_dep, cls_ptr, cls_cols, d->C_distinct);
-    d->C = (int32_t)cls_ptr.size() - 1;
-    d->Cpad = (d->C + 63) / 64 * 64;
-    std::vector<int32_t> cnt0(d->C, 0);
-    std::vector<uint64_t> depT((size_t)d->W * d->Cpad, 0);
-    d->cls_nnz = 0;
-    // (the transpose in blocks of 16 classes: the block of rows stays in cache and every word row
-    // of depT receives 128 consecutive bytes at a time)
-    for (int32_t c0 = 0; c0 < d->C; c0 += 16) {
-        const int32_t c1 = std::min(d->C, c0 + 16);
-        for (int32_t w = 0; w < d->W; ++w) {
-            uint64_t *dst = &depT[(size_t)w * d->Cpad];
-            for (int32_t c = c0; c < c1; ++c) {
-                const uint64_t x = cls_dep[(size_t)c * d->W + w];
-                cnt0[c] += __builtin_popcountll(x);
-                dst[c] = x;
+    if (on_device) {
+        HIP_TRY(ensure_workspace(d, (size_t)d->N * 32));
+        int32_t *d_digest = static_cast<int32_t *>(d->d_work);
+        HIP_TRY(launch_row_digests(*d, d->d_op_of_col, d_digest, s));
+        std::vector<int32_t> pageable;
+        int32_t *dg = static_cast<int32_t *>(stage((size_t)d->N * 32));
+        if (!dg) {
+            pageable.resize((size_t)d->N * 8);
+            dg = pageable.data();
+        }
+        HIP_TRY(hipMemcpyAsync(dg, d_digest, (size_t)d->N * 32, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        std::vector<int32_t> first_col;
+        group_digests(dg, d->N, max_members, cls_ptr, cls_cols, first_col, d->C_distinct);
+        d->C = (int32_t)cls_ptr.size() - 1;
+        d->Cpad = (d->C + 63) / 64 * 64;
+        if (d->R <= 1024 && d->C <= 512) return 1;      // the small-graph kernels want tables made from the rows
+        cnt0.resize(d->C); first_op.resize(d->C); lowest.resize(d->C);
+        for (int32_t c = 0; c < d->C; ++c) {
+            cnt0[c] = dg[(size_t)first_col[c] * 8 + 4];
+            lowest[c] = dg[(size_t)first_col[c] * 8 + 5];
+            first_op[c] = op_of_col[first_col[c]];
+        }
+    } else {
+        rows.resize((size_t)d->N * d->W);
+        if (!rows.empty()) {
+            std::vector<uint64_t> pageable;
+            uint64_t *all = static_cast<uint64_t *>(stage(dep_words * 8));   // stream order: after the copy of the graph block out of it
+            if (!all) {
+                pageable.resize(dep_words);
+                all = pageable.data();
+            }
+            HIP_TRY(hipMemcpyAsync(all, d->d_dep, dep_words * 8, hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            for (int32_t v = 0; v < n; ++v)
+                if (comp_col[v] >= 0)
+                    memcpy(&rows[(size_t)comp_col[v] * d->W], &all[(size_t)v * d->W], (size_t)d->W * 8);
+        }
+        group_classes(rows, d->N, d->W, max_members, cls_dep, cls_ptr, cls_cols, d->C_distinct);
+        d->C = (int32_t)cls_ptr.size() - 1;
+        d->Cpad = (d->C + 63) / 64 * 64;
+        cnt0.assign(d->C, 0);
+        depT.assign((size_t)d->W * d->Cpad, 0);
+        // (the transpose in blocks of 16 classes: the block of rows stays in cache and every word row
+        // of depT receives 128 consecutive bytes at a time)
+        for (int32_t c0 = 0; c0 < d->C; c0 += 16) {
+            const int32_t c1 = std::min(d->C, c0 + 16);
+            for (int32_t w = 0; w < d->W; ++w) {
+                uint64_t *dst = &depT[(size_t)w * d->Cpad];
+                for (int32_t c = c0; c < c1; ++c) {
+                    const uint64_t x = cls_dep[(size_t)c * d->W + w];
+                    cnt0[c] += __builtin_popcountll(x);
+                    dst[c] = x;
+                }
             }
         }
     }
+    d->cls_nnz = 0;
     for (int32_t c = 0; c < d->C; ++c) d->cls_nnz += cnt0[c];
     // runs [lo, hi) of consecutive recv indices of every class row, and the sum of its indices
     // (only the kernels for graphs with at most 1 024 recvs and 512 classes use them)
-    const bool want_runs = d->R <= 1024 && d->C <= 512;
+    const bool want_runs = !on_device && d->R <= 1024 && d->C <= 512;
     std::vector<int32_t> run_ptr, run_lo, run_hi, isum;
     if (want_runs) {
         run_ptr.assign(1, 0);
@@ -742,8 +821,12 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     cls.add(&d->d_run_ptr, run_ptr);
     cls.add(&d->d_run_lo, run_lo);
     cls.add(&d->d_run_hi, run_hi);
-    cls.add(&d->d_cls_dep, cls_dep);
-    cls.add(&d->d_cls_depT, depT);
+    if (!on_device) {
+        cls.add(&d->d_cls_dep, cls_dep);
+        cls.add(&d->d_cls_depT, depT);
+    } else {
+        cls.add(&d->d_cls_first_op, first_op);
+    }
     cls.add(&d->d_cls_cnt0, cnt0);
     cls.add(&d->d_cls_ptr, cls_ptr);
     cls.add(&d->d_cls_cols, cls_cols);
@@ -812,7 +895,8 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         for (int32_t c = 0; c < d->C; ++c) {
             if (cnt0[c] == 0) empty_cls.push_back(c);
             if (cnt0[c] != 1) continue;
-            for (int32_t w = 0; w < d->W; ++w)
+            if (on_device) first_recv[c] = lowest[c];
+            for (int32_t w = 0; !on_device && w < d->W; ++w)
                 if (const uint64_t x = cls_dep[(size_t)c * d->W + w]) { first_recv[c] = w * 64 + __builtin_ctzll(x); break; }
             single_ptr[first_recv[c] + 1]++;
         }
@@ -835,10 +919,29 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         cls.reserve(&d->d_planes0, (size_t)13 * d->CWpad * 8);
         cls.reserve(&d->d_live0, (size_t)d->CWpad * 8);
     }
+    if (on_device) {
+        cls.reserve(&d->d_cls_dep, (size_t)d->C * d->W * 8);
+        cls.reserve(&d->d_cls_depT, (size_t)d->W * d->Cpad * 8);
+    }
     HIP_TRY(cls.commit(&d->d_class_block, s));
+    int32_t *mismatch = d->d_bad_order + 1;         // (a second word of the zeroed flag block)
+    if (on_device) HIP_TRY(launch_class_rows(*d, d->d_op_of_col, d->d_cls_first_op, mismatch, s));
     if (want_sliced) HIP_TRY(launch_sliced_tables(*d, s));
+    int32_t differs = 0;
+    if (on_device) HIP_TRY(hipMemcpyAsync(&differs, mismatch, sizeof(int32_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));   // host vectors go out of scope; the handle is complete
+    if (differs) {
+        HIP_TRY(hipMemsetAsync(mismatch, 0, sizeof(int32_t), s));
+        return 1;
+    }
     return TICTAC_OK;
+    };
+    int rc = classes(dep_words * 8 >= ((size_t)8 << 20) && d->N > 0 && !getenv("TICTAC_GROUP_ON_HOST"));
+    if (rc == 1) {
+        if (d->d_class_block) { HIP_TRY(hipStreamSynchronize(s)); (void)hipFree(d->d_class_block); d->d_class_block = nullptr; }
+        rc = classes(false);
+    }
+    return rc;
 }
 
 }  // namespace tictac

@@ -84,6 +84,8 @@ struct Dag {
     int32_t *d_q_copied = nullptr;  // [n_q_copied][2] the copied rows (see d_copied) that found no free slot of these records
     int32_t n_q_copied = 0;
     uint64_t *d_k1_sink = nullptr;  // [slices * k1_threads] one word per thread: where a thread without a node stores
+    int32_t *d_op_of_col = nullptr; // [N] op id of every op_time column
+    int32_t *d_cls_first_op = nullptr;  // [C] (graphs grouped on the device) the op whose row is the class's
     int32_t *d_bad_order = nullptr; // one flag: an order handed to a simulation or a search was no permutation
     // the ops whose rows are copies, as pairs (op, ~i for recv i or the op id of the node whose row it has)
     int32_t *d_copied = nullptr;    // [n_copied][2]
@@ -211,6 +213,15 @@ struct SimArgs {
     bool f32 = false;
 };
 // raises *d.d_bad_order when a row of `order` (B rows, or one when order_stride = 0) is no permutation of 0 .. R-1
+// Class grouping on the device, for graphs whose rows are too many to bring back to the host:
+//   launch_row_digests: per compute op (op_of_col[j]) a 128-bit hash of its row, its number of set bits and its
+//   lowest set bit (-1 none), as int32[8] per op: h0 lo, h0 hi, h1 lo, h1 hi, count, lowest, 0, 0;
+//   launch_class_rows: cls_dep[c] = dep[first_op[c]] for every class, its transpose cls_depT (columns C..Cpad-1
+//   zero), and *mismatch is raised when the row of a compute op differs from the row of its class (two different
+//   rows with one hash: the caller then groups on the host)
+hipError_t launch_row_digests(const Dag &d, const int32_t *op_of_col, int32_t *digest, hipStream_t s);
+hipError_t launch_class_rows(const Dag &d, const int32_t *op_of_col, const int32_t *first_op, int32_t *mismatch,
+                             hipStream_t s);
 hipError_t launch_check_orders(Dag &d, int32_t B, const int32_t *order, int32_t order_stride, hipStream_t s);
 hipError_t launch_simulate(Dag &d, const SimArgs &a, hipStream_t s);
 // (needs the tables d_send_*; hipErrorNotSupported when the per-sample state does not fit LDS)

@@ -160,4 +160,98 @@ hipError_t launch_tic(const Dag &d, int32_t *prio, int32_t *order, int32_t *rank
     return hipGetLastError();
 }
 
+// ---- class grouping on the device (see internal.h) ----
+__device__ __forceinline__ uint64_t mix64(uint64_t h, uint64_t x, uint64_t k)
+{
+    h ^= x + k + (h << 6) + (h >> 2);
+    return h * 0xFF51AFD7ED558CCDull;
+}
+
+// one wave per compute op: lanes take words lane, lane + 64, ...; the two hashes mix the words in index order, so
+// they are formed by lane 0 from the words gathered through LDS-free cross-lane reads, 64 words at a time
+__global__ void __launch_bounds__(256)
+row_digest_kernel(int32_t N, int32_t W, const int32_t *__restrict__ op_of_col, const uint64_t *__restrict__ dep,
+                  int32_t *__restrict__ digest)
+{
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= N) return;
+    const uint64_t *row = dep + (size_t)op_of_col[j] * W;
+    uint64_t h0 = 0x9E3779B97F4A7C15ull, h1 = 0xC2B2AE3D27D4EB4Full;
+    int cnt = 0, lowest = -1;
+    for (int w0 = 0; w0 < W; w0 += 64) {
+        const uint64_t x = w0 + lane < W ? row[w0 + lane] : 0ull;
+        cnt += __builtin_popcountll(x);
+        const uint64_t has = __ballot(x != 0ull);
+        if (lowest < 0 && has != 0ull) {
+            const int l = __builtin_ctzll(has);
+            const uint64_t xl = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(x >> 32), l) << 32) |
+                                (uint32_t)__builtin_amdgcn_readlane((int)x, l);
+            lowest = (w0 + l) * 64 + __builtin_ctzll(xl);
+        }
+        // position-dependent contribution of every word, combined by a sum: independent of the order of the lanes
+        const uint64_t k = (uint64_t)(w0 + lane) * 0x9E3779B97F4A7C15ull;
+        uint64_t a = mix64(0x243F6A8885A308D3ull ^ k, x, 0x9E3779B97F4A7C15ull);
+        uint64_t b = mix64(0x13198A2E03707344ull + k, x ^ (x >> 29), 0xA4093822299F31D0ull);
+        a ^= a >> 32; b ^= b >> 31;
+        if (x == 0ull) { a = 0; b = 0; }            // (rows are sparse; an absent word adds nothing)
+        for (int off = 32; off > 0; off >>= 1) {
+            a += ((uint64_t)(uint32_t)__shfl_xor((int)(a >> 32), off) << 32) | (uint32_t)__shfl_xor((int)a, off);
+            b += ((uint64_t)(uint32_t)__shfl_xor((int)(b >> 32), off) << 32) | (uint32_t)__shfl_xor((int)b, off);
+        }
+        h0 = mix64(h0, a, 0x9E3779B97F4A7C15ull);
+        h1 = mix64(h1, b, 0x452821E638D01377ull);
+    }
+    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if (lane == 0) {
+        int32_t *o = digest + (size_t)j * 8;
+        o[0] = (int32_t)h0; o[1] = (int32_t)(h0 >> 32); o[2] = (int32_t)h1; o[3] = (int32_t)(h1 >> 32);
+        o[4] = cnt; o[5] = lowest; o[6] = 0; o[7] = 0;
+    }
+}
+
+hipError_t launch_row_digests(const Dag &d, const int32_t *op_of_col, int32_t *digest, hipStream_t s)
+{
+    if (d.N == 0) return hipSuccess;
+    hipLaunchKernelGGL(row_digest_kernel, dim3((d.N + 3) / 4), dim3(256), 0, s, d.N, d.W, op_of_col, d.d_dep, digest);
+    return hipGetLastError();
+}
+
+// thread per (class, word): the class's row from its first op, into cls_dep and cls_depT
+__global__ void __launch_bounds__(256)
+class_rows_kernel(int32_t C, int32_t Cpad, int32_t W, const int32_t *__restrict__ first_op,
+                  const uint64_t *__restrict__ dep, uint64_t *__restrict__ cls_dep, uint64_t *__restrict__ cls_depT)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)Cpad * W) return;
+    const int c = (int)(idx / W), w = (int)(idx % W);
+    const uint64_t x = c < C ? dep[(size_t)first_op[c] * W + w] : 0ull;
+    if (c < C) cls_dep[idx] = x;
+    cls_depT[(size_t)w * Cpad + c] = x;
+}
+
+// thread per (compute op, word): the op's row against the row of its class
+__global__ void __launch_bounds__(256)
+class_check_kernel(int32_t N, int32_t W, const int32_t *__restrict__ op_of_col, const int32_t *__restrict__ col_cls,
+                   const uint64_t *__restrict__ dep, const uint64_t *__restrict__ cls_dep, int32_t *mismatch)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)N * W) return;
+    const int j = (int)(idx / W), w = (int)(idx % W);
+    if (dep[(size_t)op_of_col[j] * W + w] != cls_dep[(size_t)col_cls[j] * W + w]) atomicOr(mismatch, 1);
+}
+
+hipError_t launch_class_rows(const Dag &d, const int32_t *op_of_col, const int32_t *first_op, int32_t *mismatch,
+                             hipStream_t s)
+{
+    if (d.C == 0 || d.W == 0) return hipSuccess;
+    const size_t total = (size_t)d.Cpad * d.W;
+    hipLaunchKernelGGL(class_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, d.C, d.Cpad, d.W,
+                       first_op, d.d_dep, d.d_cls_dep, d.d_cls_depT);
+    const size_t all = (size_t)d.N * d.W;
+    hipLaunchKernelGGL(class_check_kernel, dim3((unsigned)((all + 255) / 256)), dim3(256), 0, s, d.N, d.W, op_of_col,
+                       d.d_col_cls, d.d_dep, d.d_cls_dep, mismatch);
+    return hipGetLastError();
+}
+
 }  // namespace tictac

@@ -833,3 +833,29 @@ def test_zero_transfer_times_that_are_not_quantised(tt, name):
         exp = oracle.simulate(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids, eo, op, rv)
         for a, b, nm in zip(got[4:], exp, "m E U L S".split()):
             np.testing.assert_allclose(a.cpu().numpy(), b, rtol=RTOL, atol=1e-9 if nm in "ES" else 0.0)
+
+
+def test_class_grouping_on_the_device_equals_the_host_grouping(tt):
+    """Large graphs are grouped into classes of equal dependency rows from hashes formed on the device (the rows
+    stay there); the same graph grouped on the host from the rows themselves must give the same classes and,
+    through them, the same TAC orders and iteration metrics."""
+    d = wl.preset("stress")
+    assert d.n_ops * d.words * 8 >= 8 << 20
+    h_dev = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    os.environ["TICTAC_GROUP_ON_HOST"] = "1"
+    try:
+        h_host = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    finally:
+        del os.environ["TICTAC_GROUP_ON_HOST"]
+    assert h_dev.n_classes == h_host.n_classes == 60567
+    op, rv = wl.timing_samples(d, 0, 2)
+    a = tt.tac_simulate(h_dev, cuda(op), cuda(rv), want_rank=True)
+    b = tt.tac_simulate(h_host, cuda(op), cuda(rv), want_rank=True)
+    for x, y in zip(a, b):
+        if x is not None:
+            assert torch.equal(x, y)
+    pa, pb = tt.tic_priority(h_dev), tt.tic_priority(h_host)
+    for x, y in zip(pa, pb):
+        assert torch.equal(x, y)
+    h_dev.close()
+    h_host.close()
