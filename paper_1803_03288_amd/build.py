@@ -43,7 +43,7 @@ def is_stale() -> bool:
 COUNTED_WAITS = {
     "16propagate_levelsILi": {"n": 21, "kind": "level", "loads": 2, "stores": 1},
     "22propagate_levels_batchILi": {"n": 21, "kind": "level", "loads": 2, "stores": 1},
-    "24propagate_levels_q_batch": {"n": 14, "kind": "level", "loads": 1, "stores": 1},
+    "24propagate_levels_q_batchILi": {"n": 14, "kind": "level", "loads": 1, "stores": 1},
     "15propagate_nodesILi": {"n": 8, "kind": "request", "loads": 8},
 }
 _VM_PREFIXES = ("global_", "flat_", "scratch_", "buffer_")

@@ -485,10 +485,10 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         }
         d->k1_lring = lring;
         // Rows of a multiple of eight words, levels of at most 256 nodes: also the records of the kernel with
-        // 64-byte slices (four lanes per slot; P slots per level, a multiple of 16 so that the slots of a wave are
-        // whole; 2048 slots in the ring), which the propagation of several graphs by one launch takes.
-        int32_t q_slots = (max_width + 15) / 16 * 16, q_ring = 0;
-        if (q_slots < 16) q_slots = 16;
+        // 64-byte slices (four lanes per slot, or two with 32-byte slices; P slots per level, a multiple of 32 so that the
+        // slots of a wave are whole; 2048 slots in the ring), which the propagation of several graphs by one launch takes.
+        int32_t q_slots = (max_width + 31) / 32 * 32, q_ring = 0;
+        if (q_slots < 32) q_slots = 32;
         if (d->k1_wc == 1 && d->W % 8 == 0 && d->W <= 1016 && max_width <= 256 && M > 0 &&
             (int64_t)n_node_levels * q_slots <= (int64_t)4 * M + 8192) {
             q_ring = 2048;

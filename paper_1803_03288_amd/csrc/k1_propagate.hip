@@ -577,7 +577,7 @@ __device__ __forceinline__ void store_device_16(void *q, tt_u64x2 v) { *(__attri
 // words gw, gw + 1 of all inputs of a node that does not fit a record (see other_inputs)
 __device__ __noinline__ tt_u64x2 other_inputs_q(const int32_t *lfovf, const int32_t *fov, const uint64_t *ring,
                                                 const Dag::QuadRec *qrecs, uint64_t *dep, int W, int beg, int safe_from,
-                                                uint32_t rmask, int word_in_slice, int gw)
+                                                uint32_t rmask, int row_words, int word_in_slice, int gw)
 {
     const int32_t *list = fov ? fov : lfovf;
     const int cnt = list[beg];
@@ -589,7 +589,7 @@ __device__ __noinline__ tt_u64x2 other_inputs_q(const int32_t *lfovf, const int3
             if ((i >> 6) == gw) val.x |= 1ull << (i & 63);
             if ((i >> 6) == gw + 1) val.y |= 1ull << (i & 63);
         } else if (x >= safe_from) {
-            val |= *reinterpret_cast<const tt_u64x2 *>(ring + ((uint32_t)x & rmask) * 8 + word_in_slice);
+            val |= *reinterpret_cast<const tt_u64x2 *>(ring + ((uint32_t)x & rmask) * row_words + word_in_slice);
         } else {
             const uint64_t *q = &dep[(size_t)qrecs[x].op * W + gw];
             val.x |= __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -608,14 +608,18 @@ struct QuadParams {
     uint64_t *sink;                     // [gridDim.x * blockDim.x][2]
 };
 
+// QC lanes per slot (4: 64-byte slices, 2: 32-byte slices)
+template <int QC>
 __device__ __forceinline__ void propagate_levels_q_body(const QuadParams &p, uint64_t *ring, int block, int n_blocks)
 {
+    constexpr int RW = 2 * QC;                  // words of a row in the ring
+    constexpr int SH = QC == 4 ? 6 : 5;         // log2 of the bytes of a row in the ring
     const int W = p.W, L = p.n_levels, P = p.P;
-    const int sub = threadIdx.x >> 2, qd = threadIdx.x & 3;
-    const int gw = slice_of(block, n_blocks) * 8 + qd * 2;      // first of this thread's two words of the row
+    const int sub = threadIdx.x / QC, qd = threadIdx.x % QC;
+    const int gw = slice_of(block, n_blocks) * RW + qd * 2;      // first of this thread's two words of the row
     const uint32_t rmask = (uint32_t)p.ring - 1u;
-    int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * 8);
-    if (threadIdx.x < 16) ring[(size_t)p.ring * 8 + threadIdx.x] = 0;
+    int32_t *fov = reinterpret_cast<int32_t *>(ring + (size_t)(p.ring + 2) * RW);
+    if (threadIdx.x < 2 * RW) ring[(size_t)p.ring * RW + threadIdx.x] = 0;
     for (int i = threadIdx.x; i < p.lfovf_lds; i += blockDim.x) fov[i] = load_device_4(p.lfovf + i);
     __syncthreads();
     if (L == 0) return;
@@ -643,17 +647,17 @@ __device__ __forceinline__ void propagate_levels_q_body(const QuadParams &p, uin
         if (l < L && a##i.w != -1) {                                                      \
             const uint32_t i01 = (uint32_t)a##i.x, i23 = (uint32_t)a##i.y, r01 = (uint32_t)a##i.z; \
             if (i01 != 0xffffffffu) {                                                     \
-                val = *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 & 0xffffu) << 6)) |  \
-                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 >> 16) << 6)) |      \
-                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 & 0xffffu) << 6)) |  \
-                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 >> 16) << 6));       \
+                val = *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 & 0xffffu) << SH)) | \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i01 >> 16) << SH)) |     \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 & 0xffffu) << SH)) | \
+                      *reinterpret_cast<const tt_u64x2 *>(rb + ((i23 >> 16) << SH));      \
                 KQ_BIT(r01 & 0xffffu)                                                     \
                 KQ_BIT(r01 >> 16)                                                         \
             } else {                                                                      \
                 val = other_inputs_q(p.lfovf, p.lfovf_lds > 0 ? fov : nullptr, ring, p.qrecs, p.dep, W, (int)i23, \
-                                     (l + 1) * P - p.ring, rmask, qd * 2, gw);            \
+                                     (l + 1) * P - p.ring, rmask, RW, qd * 2, gw);        \
             }                                                                             \
-            *reinterpret_cast<tt_u64x2 *>(ring + (slot & rmask) * 8 + qd * 2) = val;      \
+            *reinterpret_cast<tt_u64x2 *>(ring + (slot & rmask) * RW + qd * 2) = val;     \
             if (a##i.w >= 0) dst = &p.dep[(size_t)a##i.w * W + gw];                       \
         }                                                                                 \
         store_device_16(dst, val);                                                        \
@@ -675,10 +679,11 @@ __device__ __forceinline__ void propagate_levels_q_body(const QuadParams &p, uin
 #undef KQ_LOAD
 }
 
-__global__ void __launch_bounds__(1024)
+template <int QC>
+__global__ void __launch_bounds__(256 * QC)
 propagate_levels_q_batch(const QuadParams *__restrict__ ps, int blocks_per)
 {
-    extern __shared__ uint64_t ring[];          // rows [ring + 2][8] (the last two all zero), then the input lists
+    extern __shared__ uint64_t ring[];          // rows [ring + 2][2 QC] (the last two all zero), then the input lists
     // Workgroup b runs on XCD b % 8.  The workgroups are renumbered so that every XCD gets a run of consecutive
     // numbers, hence whole graphs where it can: the slices of a row then meet in one L2 and leave it as whole
     // lines, and the eight slices of a graph read its records through one L2.
@@ -686,7 +691,7 @@ propagate_levels_q_batch(const QuadParams *__restrict__ ps, int blocks_per)
     const int v = (n & 7) == 0 ? (blockIdx.x & 7) * (n >> 3) + (blockIdx.x >> 3) : (int)blockIdx.x;
     const int g = v / blocks_per;
     const QuadParams p = ps[g];
-    propagate_levels_q_body(p, ring, v - g * blocks_per, 1);
+    propagate_levels_q_body<QC>(p, ring, v - g * blocks_per, 1);
 }
 
 // rows that are copies: a recv's single bit, or the row of the node an op collapses onto.  `copied`: the ops
@@ -735,14 +740,16 @@ static bool level_params(const Dag &d, int WC, LevelParams *q, size_t *lds)
     return *lds <= 150 * 1024;
 }
 
-static bool quad_params(const Dag &d, QuadParams *q, size_t *lds)
+static bool quad_params(const Dag &d, int QC, QuadParams *q, size_t *lds)
 {
-    if (d.k1_q_ring <= 0 || !d.d_qrecs || !d.d_k1_q_sink || d.W % 8 != 0 || d.k1_q_threads % 64 != 0 || d.k1_q_threads > 1024)
+    // (k1_q_threads is four lanes per slot; QC lanes per slot need a multiple of 64 threads as well)
+    const int threads = d.k1_q_threads / 4 * QC;
+    if (d.k1_q_ring <= 0 || !d.d_qrecs || !d.d_k1_q_sink || d.W % 8 != 0 || threads % 64 != 0 || threads > 256 * QC)
         return false;
     q->n_levels = d.n_node_levels; q->W = d.W; q->P = d.k1_q_threads / 4; q->ring = d.k1_q_ring;
     q->qrecs = d.d_qrecs; q->lfovf = d.d_qfovf; q->dep = d.d_dep; q->sink = d.d_k1_q_sink;
     q->lfovf_lds = d.qfovf_len <= 4096 ? d.qfovf_len : 0;
-    *lds = (size_t)(d.k1_q_ring + 2) * 64 + (size_t)q->lfovf_lds * 4;
+    *lds = (size_t)(d.k1_q_ring + 2) * QC * 16 + (size_t)q->lfovf_lds * 4;
     return *lds <= 150 * 1024;
 }
 
@@ -783,7 +790,8 @@ static hipError_t launch_levels_batch(Dag *const *ds, int G, void *staging, hipS
     return hipGetLastError();
 }
 
-// the same for graphs that take the kernel with 64-byte slices
+// the same for graphs that take the kernel with 64-byte (QC = 4) or 32-byte (QC = 2) slices
+template <int QC>
 static hipError_t launch_quad_batch(Dag *const *ds, int G, void *staging, hipStream_t s)
 {
     std::vector<QuadParams> lp(G);
@@ -792,7 +800,7 @@ static hipError_t launch_quad_batch(Dag *const *ds, int G, void *staging, hipStr
     int32_t most_copied = 0;
     for (int g = 0; g < G; ++g) {
         size_t lds = 0;
-        if (!quad_params(*ds[g], &lp[g], &lds)) return hipErrorNotSupported;
+        if (!quad_params(*ds[g], QC, &lp[g], &lds)) return hipErrorNotSupported;
         if (g == 0) lds0 = lds;
         if (lds != lds0 || ds[g]->k1_q_threads != ds[0]->k1_q_threads || ds[g]->W != ds[0]->W || ds[g]->n != ds[0]->n)
             return hipErrorNotSupported;
@@ -806,12 +814,13 @@ static hipError_t launch_quad_batch(Dag *const *ds, int G, void *staging, hipStr
     e = hipMemcpyAsync(d_ep, ep.data(), sizeof(ExpandParams) * G, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return e;
     if (lds0 > 48 * 1024) {
-        e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_levels_q_batch), lds0);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_levels_q_batch<QC>), lds0);
         if (e != hipSuccess) return e;
     }
     const Dag &d0 = *ds[0];
-    const int blocks_per = d0.W / 8;
-    hipLaunchKernelGGL(propagate_levels_q_batch, dim3(blocks_per * G), dim3(d0.k1_q_threads), lds0, s, d_lp, blocks_per);
+    const int blocks_per = d0.W / (2 * QC);
+    hipLaunchKernelGGL(propagate_levels_q_batch<QC>, dim3(blocks_per * G), dim3(d0.k1_q_threads / 4 * QC), lds0, s, d_lp,
+                       blocks_per);
     const size_t total = (size_t)most_copied * d0.W;
     if (total) hipLaunchKernelGGL(expand_rows_batch, dim3((unsigned)((total + 255) / 256), G), dim3(256), 0, s, d_ep);
     return hipGetLastError();
@@ -826,7 +835,8 @@ hipError_t launch_propagate_batch(Dag *const *ds, int G, void *staging, hipStrea
 {
     if (G <= 0) return hipSuccess;
     if (ds[0]->n == 0 || ds[0]->W == 0 || ds[0]->M == 0) return hipErrorNotSupported;
-    if (G >= 2 && ds[0]->k1_q_ring > 0) return launch_quad_batch(ds, G, staging, s);
+    // (32-byte slices, QC = 2, were measured too: as fast up to sixteen graphs, a third slower from 32 on)
+    if (G >= 2 && ds[0]->k1_q_ring > 0) return launch_quad_batch<4>(ds, G, staging, s);
     if (ds[0]->k1_wc == 1) return launch_levels_batch<1>(ds, G, staging, s);
     if (ds[0]->k1_wc == 2) return launch_levels_batch<2>(ds, G, staging, s);
     return launch_levels_batch<4>(ds, G, staging, s);

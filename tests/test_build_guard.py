@@ -31,7 +31,7 @@ def test_generated_code_matches_the_counts(asm):
     assert b.check_counted_waits(asm) == []
 
 
-@pytest.mark.parametrize("key,n", [("16propagate_levelsILi1", 21), ("24propagate_levels_q_batch", 14)])
+@pytest.mark.parametrize("key,n", [("16propagate_levelsILi1", 21), ("24propagate_levels_q_batchILi4", 14)])
 def test_a_missing_load_between_two_waits_is_found(asm, key, n):
     lo, hi = function_span(asm, key)
     body = asm[lo:hi]
@@ -71,4 +71,4 @@ def test_a_store_after_the_request_is_found(asm):
 
 def test_a_kernel_that_is_gone_is_found(asm):
     bad = b.check_counted_waits(asm.replace("propagate_levels_q_batch", "propagate_levels_x_batch"))
-    assert any("24propagate_levels_q_batch" in x for x in bad)
+    assert any("24propagate_levels_q_batchILi" in x for x in bad)
