@@ -126,6 +126,25 @@ def test_deps_of_several_handles_in_one_launch(tt, name):
         x.close()
 
 
+def test_deps_of_different_graphs_in_one_call(tt):
+    """tictac_dag_recompute_deps_batch on handles of different graphs: graphs of one size and one launch shape share
+    a launch (the kernel with 64-byte slices here: rows of 16 words), a graph of another size in the same list
+    sends the call through one launch per handle; either way every handle gets its own bitsets."""
+    graphs = [wl.stress_dag(levels=40, width=120, n_recv=1024, seed=s, batch=4) for s in (61, 62, 63)]
+    graphs.append(wl.stress_dag(levels=25, width=90, n_recv=512, seed=64, batch=4))
+    deps = [oracle.find_dependencies(g.n_ops, g.row_ptr, g.col_idx, g.recv_ids) for g in graphs]
+    hs = [tt.build_deps(g.n_ops, g.row_ptr, g.col_idx, g.recv_ids) for g in graphs]
+    for group in (hs[:3], hs, [hs[3], hs[0]]):
+        for x in group:
+            x.deps_view().zero_()
+        tt.recompute_deps_batch(group)
+        for x in group:
+            i = hs.index(x)
+            assert np.array_equal(x.deps().cpu().numpy().view(np.uint64), deps[i]), i
+    for x in hs:
+        x.close()
+
+
 def test_no_recvs_and_empty_graph(tt):
     d = wl.no_recv_dag(17)
     h = tt.build_deps(d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
