@@ -18,7 +18,11 @@
 //   * Q, the set of recvs pointed at by a class with a positive time, is tracked by the number
 //     of pointers, the sum of their targets and the latest target (one pointer: the sum is
 //     the member of Q, the common case on layered models; two pointers at two recvs: one
-//     comparison).  Only the general path enumerates Q, from the class registers;
+//     comparison).  With many classes per lane the sum of the squares of the targets and the
+//     target before the latest are kept as well: with three or four pointers the two unknown
+//     targets are the roots of a quadratic, and when all targets are distinct the scan over Q
+//     is two or three comparisons in straight-line code.  Only the general path enumerates Q,
+//     from the class registers;
 //   * M of a class is needed only when Q is empty or the comparator ties.  It is formed at the
 //     first such round as the sum of the transfer times over the runs of consecutive recv
 //     indices of its row and brought up to date from the order built so far; rounds that do
@@ -189,7 +193,11 @@ tac_reg_kernel(const TacRegParams p)
         // recv; Q is the set of recvs pointed at (the outstanding recvs with P > 0).  Tracked
         // wave-uniformly: the number of pointers, the
         // sum of their targets, and the target of the latest one.
-        int qm = 0, qs = 0, qlast = 0;
+        // (qs2: the sum of the squares of the targets; qprev: the target of the pointer before the latest)
+        int qm = 0, qs = 0, qlast = 0, qs2 = 0, qprev = 0;
+        // (kept only where classes are many: graphs with few classes rarely have more than two members in Q, and
+        // the forced rounds are measurably slower with the two extra values)
+        constexpr bool kSums = KT >= 4;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
         int32_t *ord_next = ordl;           // where the next selected recv is recorded
 
@@ -261,6 +269,7 @@ tac_reg_kernel(const TacRegParams p)
                 const int sole = __builtin_amdgcn_readlane(sole_##k, l);                  \
                 qm += 1;                                                                  \
                 qs += sole;                                                               \
+                if constexpr (kSums) { qs2 += sole * sole; qprev = qlast; }               \
                 qlast = sole;                                                             \
             }
 #define TT_TO_P(k, hit1, hm)     /* hm: the ballot of hit1 */                            \
@@ -318,6 +327,10 @@ tac_reg_kernel(const TacRegParams p)
                 qm = __builtin_amdgcn_readfirstlane(qm);                                  \
                 qs = __builtin_amdgcn_readfirstlane(qs);                                  \
                 qlast = __builtin_amdgcn_readfirstlane(qlast);                            \
+                if constexpr (kSums) {                                                    \
+                    qs2 = __builtin_amdgcn_readfirstlane(qs2);                            \
+                    qprev = __builtin_amdgcn_readfirstlane(qprev);                        \
+                }                                                                         \
             }
         // pointers counted afresh from the class registers (after a round that removed an
         // unknown number of them)
@@ -330,6 +343,7 @@ tac_reg_kernel(const TacRegParams p)
                     const int sole = __builtin_amdgcn_readlane(sole_##k, l);              \
                     qm += 1;                                                              \
                     qs += sole;                                                           \
+                    if constexpr (kSums) { qs2 += sole * sole; qprev = qlast; }           \
                     qlast = sole;                                                         \
                 }                                                                         \
             }
@@ -341,7 +355,7 @@ tac_reg_kernel(const TacRegParams p)
             // classes is not touched in it.
             while (qm == 1) {
                 const int best = qs;
-                qm = 0; qs = 0;
+                qm = 0; qs = 0; qs2 = 0;
                 TT_APPLY()
                 TT_UNIFORM_Q()
             }
@@ -357,10 +371,59 @@ tac_reg_kernel(const TacRegParams p)
                 if (__builtin_amdgcn_readfirstlane((int)(xa != ya))) {
                     const int best = __builtin_amdgcn_readfirstlane((int)(xa < ya)) ? b_ : a_;
                     const int other = a_ + b_ - best;
-                    qm = 1; qs = other; qlast = other;
+                    qm = 1; qs = other; qlast = other; qs2 = other * other;
                     TT_APPLY()
                     TT_UNIFORM_Q()
                     continue;
+                }
+            }
+            if (kSums && (qm == 3 || qm == 4)) {
+                // Three or four pointers.  The latest target (and, with four, the one before it: qlast and
+                // qprev are targets of two different pointers whenever there are that many) is known; the two
+                // others, u <= v, follow from the sums: u + v and u^2 + v^2 are what is left of qs and qs2, and
+                // (v - u)^2 = 2 (u^2 + v^2) - (u + v)^2.  When all targets are distinct, Q is these recvs and
+                // the ascending scan is two or three comparisons in straight-line code; the sums of those
+                // that stay are known, nothing is counted again.  Anything else (two pointers at one recv, a
+                // tie in a comparison) is left to the general path.
+                const bool four = qm == 4;
+                const int kp = four ? qprev : 0;
+                const int su = qs - qlast - kp, sq = qs2 - qlast * qlast - kp * kp;
+                const int dd = 2 * sq - su * su;
+                const int rt = __builtin_amdgcn_readfirstlane((int)(__builtin_sqrtf((float)dd) + 0.5f));
+                const int u_ = (su - rt) >> 1, v_ = (su + rt) >> 1;
+                bool distinct = dd > 0 && rt * rt == dd && ((su - rt) & 1) == 0 && u_ != qlast && v_ != qlast;
+                if (four) distinct = distinct && u_ != qprev && v_ != qprev && qprev != qlast;
+                if (distinct) {
+                    // members in ascending order (u_ < v_ already); with three, the fourth is a copy of the third
+                    int m0 = u_, m1 = v_, m2 = qlast, m3 = four ? qprev : INT32_MAX;
+                    { const int lo = min(m2, m3), hi = max(m2, m3); m2 = lo; m3 = hi; }
+                    { const int lo = min(m0, m2), hi = max(m0, m2); m0 = lo; m2 = hi; }
+                    { const int lo = min(m1, m3), hi = max(m1, m3); m1 = lo; m3 = hi; }
+                    { const int lo = min(m1, m2), hi = max(m1, m2); m1 = lo; m2 = hi; }
+                    const int m3r = four ? m3 : m2;
+                    const double P0 = P[m0], P1 = P[m1], P2 = P[m2], P3 = P[m3r];
+                    const double t0 = t[m0], t1 = t[m1], t2 = t[m2], t3 = t[m3r];
+                    const double x1 = fmin(P0, t1), y1 = fmin(P1, t0);          // m1 precedes m0 when x1 < y1
+                    const bool s1 = x1 < y1;
+                    const double Pa = s1 ? P1 : P0, ta = s1 ? t1 : t0;
+                    const double x2 = fmin(Pa, t2), y2 = fmin(P2, ta);
+                    const bool s2 = x2 < y2;
+                    const double Pb = s2 ? P2 : Pa, tb = s2 ? t2 : ta;
+                    const double x3 = fmin(Pb, t3), y3 = fmin(P3, tb);
+                    const bool s3 = four && x3 < y3;
+                    const bool no_tie = x1 != y1 && x2 != y2 && (!four || x3 != y3);
+                    if (__builtin_amdgcn_readfirstlane((int)no_tie)) {
+                        const int b1 = __builtin_amdgcn_readfirstlane((int)s1) ? m1 : m0;
+                        const int b2 = __builtin_amdgcn_readfirstlane((int)s2) ? m2 : b1;
+                        const int best = __builtin_amdgcn_readfirstlane((int)s3) ? m3 : b2;
+                        // two of the members that stay (the lowest two): targets of two different pointers
+                        const int r0 = best == m0 ? m1 : m0;
+                        const int r1 = (best == m0 || best == m1) ? m2 : m1;
+                        qm -= 1; qs -= best; qs2 -= best * best; qprev = r0; qlast = r1;
+                        TT_APPLY()
+                        TT_UNIFORM_Q()
+                        continue;
+                    }
                 }
             }
             if (qm >= 2 && qs == qm * qlast) {
@@ -373,7 +436,7 @@ tac_reg_kernel(const TacRegParams p)
                 if (other_target == 0) {
                     // several pointers at one recv: |Q| = 1 as well
                     const int best = qlast;
-                    qm = 0; qs = 0;
+                    qm = 0; qs = 0; qs2 = 0;
                     TT_APPLY()
                     TT_UNIFORM_Q()
                     continue;
@@ -452,7 +515,7 @@ tac_reg_kernel(const TacRegParams p)
             }
             best = __builtin_amdgcn_readfirstlane(best);
             TT_APPLY()
-            qm = 0; qs = 0;
+            qm = 0; qs = 0; qs2 = 0;
             TT_EACH_K(TT_RECOUNT)
             TT_UNIFORM_Q()
         }
