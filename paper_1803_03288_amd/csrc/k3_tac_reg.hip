@@ -16,13 +16,12 @@
 //     outstanding recv of the class, to whose P the class time is then added: the class
 //     "points" at that recv;
 //   * Q, the set of recvs pointed at by a class with a positive time, is tracked by the number
-//     of pointers, the sum of their targets and the latest target (one pointer: the sum is
-//     the member of Q, the common case on layered models; two pointers at two recvs: one
-//     comparison).  With many classes per lane the sum of the squares of the targets and the
-//     target before the latest are kept as well: with three or four pointers the two unknown
-//     targets are the roots of a quadratic, and when all targets are distinct the scan over Q
-//     is two or three comparisons in straight-line code.  Only the general path enumerates Q,
-//     from the class registers;
+//     of pointers and the targets of the latest two of them (one pointer: its target is the
+//     member of Q, the common case on layered models; two pointers at two recvs: one
+//     comparison).  With many classes per lane the latest four targets are kept: with three or
+//     four pointers at distinct recvs the scan over Q is a sorting network on scalars and two or
+//     three comparisons in straight-line code, and the members that stay are known afterwards.
+//     Only the general path enumerates Q, from the class registers;
 //   * M of a class is needed only when Q is empty or the comparator ties.  It is formed at the
 //     first such round as the sum of the transfer times over the runs of consecutive recv
 //     indices of its row and brought up to date from the order built so far; rounds that do
@@ -191,13 +190,13 @@ tac_reg_kernel(const TacRegParams p)
         wave_sync();
         // A class with exactly one outstanding recv left and a positive time "points" at that
         // recv; Q is the set of recvs pointed at (the outstanding recvs with P > 0).  Tracked
-        // wave-uniformly: the number of pointers, the
-        // sum of their targets, and the target of the latest one.
-        // (qs2: the sum of the squares of the targets; qprev: the target of the pointer before the latest)
-        int qm = 0, qs = 0, qlast = 0, qs2 = 0, qprev = 0;
-        // (kept only where classes are many: graphs with few classes rarely have more than two members in Q, and
-        // the forced rounds are measurably slower with the two extra values)
-        constexpr bool kSums = KT >= 4;
+        // wave-uniformly: the number of pointers and the targets of the latest ones, q0 the newest.
+        // While there are no more pointers than tracked targets, Q is known without looking at
+        // the classes.
+        int qm = 0, q0 = 0, q1 = 0, q2 = 0, q3 = 0;
+        // (four targets only where classes are many: graphs with few classes rarely have more than two
+        // members in Q, and the forced rounds are measurably slower with the two extra values)
+        constexpr bool kFour = KT >= 4;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
         int32_t *ord_next = ordl;           // where the next selected recv is recorded
 
@@ -262,15 +261,17 @@ tac_reg_kernel(const TacRegParams p)
 
         // A class that fell to one outstanding recv: its time goes to P of that recv, and with a
         // positive time it becomes a pointer.
+#define TT_PUSH_Q(target)                                                                 \
+                qm += 1;                                                                  \
+                if constexpr (kFour) { q3 = q2; q2 = q1; }                                \
+                q1 = q0;                                                                  \
+                q0 = (target);
 #define TT_POINTER(k)                                                                     \
             {                                                                             \
                 const int l = __builtin_ctzll(nm);                                        \
                 nm ^= 1ull << l;                                                          \
                 const int sole = __builtin_amdgcn_readlane(sole_##k, l);                  \
-                qm += 1;                                                                  \
-                qs += sole;                                                               \
-                if constexpr (kSums) { qs2 += sole * sole; qprev = qlast; }               \
-                qlast = sole;                                                             \
+                TT_PUSH_Q(sole)                                                           \
             }
 #define TT_TO_P(k, hit1, hm)     /* hm: the ballot of hit1 */                            \
         {                                                                                 \
@@ -325,11 +326,11 @@ tac_reg_kernel(const TacRegParams p)
 #define TT_UNIFORM_Q()                                                                    \
             {                                                                             \
                 qm = __builtin_amdgcn_readfirstlane(qm);                                  \
-                qs = __builtin_amdgcn_readfirstlane(qs);                                  \
-                qlast = __builtin_amdgcn_readfirstlane(qlast);                            \
-                if constexpr (kSums) {                                                    \
-                    qs2 = __builtin_amdgcn_readfirstlane(qs2);                            \
-                    qprev = __builtin_amdgcn_readfirstlane(qprev);                        \
+                q0 = __builtin_amdgcn_readfirstlane(q0);                                  \
+                q1 = __builtin_amdgcn_readfirstlane(q1);                                  \
+                if constexpr (kFour) {                                                    \
+                    q2 = __builtin_amdgcn_readfirstlane(q2);                              \
+                    q3 = __builtin_amdgcn_readfirstlane(q3);                              \
                 }                                                                         \
             }
         // pointers counted afresh from the class registers (after a round that removed an
@@ -341,10 +342,7 @@ tac_reg_kernel(const TacRegParams p)
                     const int l = __builtin_ctzll(nm);                                    \
                     nm ^= 1ull << l;                                                      \
                     const int sole = __builtin_amdgcn_readlane(sole_##k, l);              \
-                    qm += 1;                                                              \
-                    qs += sole;                                                           \
-                    if constexpr (kSums) { qs2 += sole * sole; qprev = qlast; }           \
-                    qlast = sole;                                                         \
+                    TT_PUSH_Q(sole)                                                       \
                 }                                                                         \
             }
         int step = 0;
@@ -354,53 +352,42 @@ tac_reg_kernel(const TacRegParams p)
             // pointers (all of them) are gone with it.  These rounds form the inner loop; M of the
             // classes is not touched in it.
             while (qm == 1) {
-                const int best = qs;
-                qm = 0; qs = 0; qs2 = 0;
+                const int best = q0;
+                qm = 0;
                 TT_APPLY()
                 TT_UNIFORM_Q()
             }
             if (step >= R) break;
-            if (qm == 2 && qs != 2 * qlast) {
+            if (qm == 2) {
+                if (q0 == q1) { qm = 1; continue; }      // two pointers at one recv: |Q| = 1 as well
                 // two pointers at two recvs a < b: Q = {a, b}, and the scan is one comparison:
                 // b precedes a when min{P_a, Time(b)} < min{P_b, Time(a)}.  A tie is left to
                 // the general path below.
-                const int o_ = qs - qlast;
-                const int a_ = min(o_, qlast), b_ = max(o_, qlast);
+                const int a_ = min(q0, q1), b_ = max(q0, q1);
                 const double xa = fmin(P[a_], t[b_]);
                 const double ya = fmin(P[b_], t[a_]);
                 if (__builtin_amdgcn_readfirstlane((int)(xa != ya))) {
                     const int best = __builtin_amdgcn_readfirstlane((int)(xa < ya)) ? b_ : a_;
-                    const int other = a_ + b_ - best;
-                    qm = 1; qs = other; qlast = other; qs2 = other * other;
+                    qm = 1; q0 = a_ + b_ - best;
                     TT_APPLY()
                     TT_UNIFORM_Q()
                     continue;
                 }
             }
-            if (kSums && (qm == 3 || qm == 4)) {
-                // Three or four pointers.  The latest target (and, with four, the one before it: qlast and
-                // qprev are targets of two different pointers whenever there are that many) is known; the two
-                // others, u <= v, follow from the sums: u + v and u^2 + v^2 are what is left of qs and qs2, and
-                // (v - u)^2 = 2 (u^2 + v^2) - (u + v)^2.  When all targets are distinct, Q is these recvs and
-                // the ascending scan is two or three comparisons in straight-line code; the sums of those
-                // that stay are known, nothing is counted again.  Anything else (two pointers at one recv, a
-                // tie in a comparison) is left to the general path.
+            if (kFour && (qm == 3 || qm == 4)) {
+                // Three or four pointers, all of them tracked.  When their targets are distinct, Q is these
+                // recvs and the ascending scan is two or three comparisons in straight-line code; those that
+                // stay are known, nothing is counted again.  Anything else (two pointers at one recv, a tie in
+                // a comparison) is left to the paths below.
                 const bool four = qm == 4;
-                const int kp = four ? qprev : 0;
-                const int su = qs - qlast - kp, sq = qs2 - qlast * qlast - kp * kp;
-                const int dd = 2 * sq - su * su;
-                const int rt = __builtin_amdgcn_readfirstlane((int)(__builtin_sqrtf((float)dd) + 0.5f));
-                const int u_ = (su - rt) >> 1, v_ = (su + rt) >> 1;
-                bool distinct = dd > 0 && rt * rt == dd && ((su - rt) & 1) == 0 && u_ != qlast && v_ != qlast;
-                if (four) distinct = distinct && u_ != qprev && v_ != qprev && qprev != qlast;
-                if (distinct) {
-                    // members in ascending order (u_ < v_ already); with three, the fourth is a copy of the third
-                    int m0 = u_, m1 = v_, m2 = qlast, m3 = four ? qprev : INT32_MAX;
-                    { const int lo = min(m2, m3), hi = max(m2, m3); m2 = lo; m3 = hi; }
-                    { const int lo = min(m0, m2), hi = max(m0, m2); m0 = lo; m2 = hi; }
-                    { const int lo = min(m1, m3), hi = max(m1, m3); m1 = lo; m3 = hi; }
-                    { const int lo = min(m1, m2), hi = max(m1, m2); m1 = lo; m2 = hi; }
-                    const int m3r = four ? m3 : m2;
+                int m0 = q0, m1 = q1, m2 = q2, m3 = four ? q3 : INT32_MAX;
+                { const int lo = min(m0, m1), hi = max(m0, m1); m0 = lo; m1 = hi; }
+                { const int lo = min(m2, m3), hi = max(m2, m3); m2 = lo; m3 = hi; }
+                { const int lo = min(m0, m2), hi = max(m0, m2); m0 = lo; m2 = hi; }
+                { const int lo = min(m1, m3), hi = max(m1, m3); m1 = lo; m3 = hi; }
+                { const int lo = min(m1, m2), hi = max(m1, m2); m1 = lo; m2 = hi; }
+                if (m0 != m1 && m1 != m2 && m2 != m3) {
+                    const int m3r = four ? m3 : m2;         // with three, the fourth is a copy of the third
                     const double P0 = P[m0], P1 = P[m1], P2 = P[m2], P3 = P[m3r];
                     const double t0 = t[m0], t1 = t[m1], t2 = t[m2], t3 = t[m3r];
                     const double x1 = fmin(P0, t1), y1 = fmin(P1, t0);          // m1 precedes m0 when x1 < y1
@@ -416,27 +403,31 @@ tac_reg_kernel(const TacRegParams p)
                         const int b1 = __builtin_amdgcn_readfirstlane((int)s1) ? m1 : m0;
                         const int b2 = __builtin_amdgcn_readfirstlane((int)s2) ? m2 : b1;
                         const int best = __builtin_amdgcn_readfirstlane((int)s3) ? m3 : b2;
-                        // two of the members that stay (the lowest two): targets of two different pointers
-                        const int r0 = best == m0 ? m1 : m0;
-                        const int r1 = (best == m0 || best == m1) ? m2 : m1;
-                        qm -= 1; qs -= best; qs2 -= best * best; qprev = r0; qlast = r1;
+                        // the members that stay, in ascending order
+                        qm -= 1;
+                        q0 = best == m0 ? m1 : m0;
+                        q1 = (best == m0 || best == m1) ? m2 : m1;
+                        q2 = best == m3 ? m2 : m3;
                         TT_APPLY()
                         TT_UNIFORM_Q()
                         continue;
                     }
                 }
             }
-            if (qm >= 2 && qs == qm * qlast) {
-                // the sum allows that all pointers aim at one recv; look at them to be sure
+            if (qm >= 2 && q0 == q1 && (!kFour || (q1 == q2 && (qm == 3 || q2 == q3)))) {
+                // the latest pointers aim at one recv; with more pointers than tracked targets, look at
+                // all of them to be sure
                 uint64_t other_target = 0;
+                if (qm > (kFour ? 4 : 2)) {
 #define TT_SAME(k)                                                                        \
-                if constexpr (k < KT)                                                     \
-                    other_target |= __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1 && sole_##k != qlast) & ctpos_##k;
-                TT_EACH_K(TT_SAME)
+                    if constexpr (k < KT)                                                 \
+                        other_target |= __ballot((uint32_t)pk_##k >= (uint32_t)-CNT1 && sole_##k != q0) & ctpos_##k;
+                    TT_EACH_K(TT_SAME)
+                }
                 if (other_target == 0) {
                     // several pointers at one recv: |Q| = 1 as well
-                    const int best = qlast;
-                    qm = 0; qs = 0; qs2 = 0;
+                    const int best = q0;
+                    qm = 0;
                     TT_APPLY()
                     TT_UNIFORM_Q()
                     continue;
@@ -515,7 +506,7 @@ tac_reg_kernel(const TacRegParams p)
             }
             best = __builtin_amdgcn_readfirstlane(best);
             TT_APPLY()
-            qm = 0; qs = 0; qs2 = 0;
+            qm = 0;
             TT_EACH_K(TT_RECOUNT)
             TT_UNIFORM_Q()
         }
