@@ -338,7 +338,7 @@ static hipError_t launch_sim_wave(SimWaveParams &p, const Dag &d, hipStream_t s)
 static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_t *kappa, hipStream_t s)
 {
     const int K = std::max((d.C + 63) / 64, (d.R + 63) / 64);   // slots per lane: classes, and positions of the order
-    const int KT = K <= 4 ? K : (K <= 6 ? 6 : 8);     // the instantiation that is launched below
+    const int KT = K;                                 // the instantiation that is launched below
     // (the class totals are summed in the space of F and A: one double per class slot must fit)
     if (d.R == 0 || d.R > 512 || d.C == 0 || K > 8 || !d.d_col_cls || !d.d_run_ptr || (size_t)64 * KT > 2 * (size_t)d.R + 1)
         return hipErrorNotSupported;
@@ -352,7 +352,9 @@ static hipError_t try_simulate_wave(const Dag &d, const SimArgs &a, const int32_
     if (K <= 2) return launch_sim_wave<2>(p, d, s);
     if (K <= 3) return launch_sim_wave<3>(p, d, s);
     if (K <= 4) return launch_sim_wave<4>(p, d, s);
+    if (K <= 5) return launch_sim_wave<5>(p, d, s);
     if (K <= 6) return launch_sim_wave<6>(p, d, s);
+    if (K <= 7) return launch_sim_wave<7>(p, d, s);
     return launch_sim_wave<8>(p, d, s);
 }
 
@@ -376,11 +378,13 @@ static hipError_t launch_sim_t(const SimKernelParams &p, int grid, size_t lds, h
 // device that never idles while an op is ready finishes at
 //     max( latest arrival,  max over classes c of  rho_c + sum of the times of the classes with rho >= rho_c ).
 // One wave per sample: arrivals by one wave scan per channel, rho by range maxima over the
-// arrival array (runs of the class rows), the last step by comparing every class with every class
-// (lane l owns classes l, l + 64, ...; the pairs (rho, time) are broadcast from LDS) or, with more than 256
-// classes, by sorting the classes by rho in registers and one suffix sum over the sorted order.
+// arrival array (runs of the class rows; lane l owns classes l, l + 64, ...), the last step by ranking the
+// release dates among the arrivals: on one channel the arrivals increase along the order, so the number of
+// arrivals up to rho is one binary search per channel; the class times are added up by that rank and one
+// suffix sum over the ranks gives the second term for every class.
 struct SimChanParams {
     int32_t B, R, C, N, n_waves, wave_bytes, levels, n_channels, chan_bytes;
+    int32_t nb, x_doubles;      // blocks of four recvs; doubles shared by the transfer times and the table of block maxima
     const int32_t *col_cls, *run_ptr, *run_lo, *run_hi;
     const int32_t *chan;        // [R] channel of every recv, 0 <= chan < n_channels <= 64
     const int32_t *order;
@@ -390,66 +394,39 @@ struct SimChanParams {
     double *makespan, *eff, *U, *L, *S;
 };
 
-// Sorts the 64 KP pairs (key, val) of a wave by key, ascending; element e = k * 64 + lane sits in register k of
-// its lane.  A bitonic network: partners at a distance below 64 exchange through the cross-lane permute, larger
-// distances are between registers of one lane.  A pair moves as a whole and only when the keys differ, so pairs
-// with equal keys are never mixed up.
-template <int KP>
-__device__ __forceinline__ void wave_sort_pairs(double (&key)[KP], double (&val)[KP], int lane)
-{
-#pragma unroll
-    for (int size = 2; size <= 64 * KP; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            if (stride < 64) {
-#pragma unroll
-                for (int k = 0; k < KP; ++k) {
-                    const int e = k * 64 + lane;
-                    const bool keep_min = ((e & stride) == 0) == ((e & size) == 0);
-                    const double pk = __hiloint2double(__shfl_xor(__double2hiint(key[k]), stride),
-                                                       __shfl_xor(__double2loint(key[k]), stride));
-                    const double pv = __hiloint2double(__shfl_xor(__double2hiint(val[k]), stride),
-                                                       __shfl_xor(__double2loint(val[k]), stride));
-                    const bool take = keep_min ? pk < key[k] : pk > key[k];
-                    key[k] = take ? pk : key[k];
-                    val[k] = take ? pv : val[k];
-                }
-            } else {
-                const int dk = stride >> 6;
-#pragma unroll
-                for (int k = 0; k < KP; ++k) {
-                    if ((k & dk) == 0) {
-                        const int k2 = k | dk;
-                        const bool ascending = ((k * 64) & size) == 0;
-                        const bool swap = ascending ? key[k2] < key[k] : key[k2] > key[k];
-                        const double tk = key[k], tv = val[k];
-                        key[k] = swap ? key[k2] : tk;
-                        val[k] = swap ? val[k2] : tv;
-                        key[k2] = swap ? tk : key[k2];
-                        val[k2] = swap ? tv : val[k2];
-                    }
-                }
-            }
-        }
-    }
-}
-
+// (three waves per SIMD: 168 registers per lane; with a cap of 128 the kernel spills and is slower)
 template <int KT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)
 simulate_channels_kernel(const SimChanParams p)
 {
     extern __shared__ double smem[];
     const int R = p.R, C = p.C, N = p.N;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t *chan_l = reinterpret_cast<int32_t *>(smem);    // [R] channel of every recv, shared by the waves
+    int32_t *coff = chan_l + R;             // [64] where the arrivals of a channel start in `lists`
+    int32_t *clen = coff + 64;              // [64] recvs of a channel
     double *mine = reinterpret_cast<double *>(reinterpret_cast<char *>(smem) + p.chan_bytes + (size_t)wave * p.wave_bytes);
-    double *t = mine;                       // [R]          Time(recv)
-    double *arr = t + R;                    // [levels][R]  level 0: arrival of recv r; level j: maxima over [i, i + 2^j)
-    // [64 KT][2] (rho, class time), 16-byte aligned; first the class totals while they are summed
-    double *pairs = arr + (size_t)p.levels * R + (((size_t)(1 + p.levels) * R) & 1);
-    double *csum = pairs;
+    const int Rp = (R + 3) & ~3, nb = p.nb;
+    double *arr = mine;                     // [Rp] arrival of recv r, zero beyond R
+    double *t = arr + Rp;                   // [R]  Time(recv), until the arrivals are known; then
+    double *tab = t;                        // [levels][nb] level j: maxima of the arrivals over the blocks [i, i + 2^j) of four recvs
+    double *csum = t + p.x_doubles;         // [64 KT] the class totals while they are summed; then
+    double *lists = csum;                   // [R] the arrivals channel by channel, in the order's sequence
     for (int r = threadIdx.x; r < R; r += blockDim.x) chan_l[r] = p.chan[r];
     __syncthreads();
+    if (wave == 0) {
+        int n_mine = 0;                     // lane c: recvs of channel c
+        for (int r = 0; r < R; ++r) n_mine += chan_l[r] == lane;
+        int incl = n_mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        coff[lane] = incl - n_mine;
+        clen[lane] = n_mine;
+    }
+    __syncthreads();
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
     // the first two runs of every class row (lo | hi << 16), fixed for the launch; longer rows read the rest
 #define SC_RUNS(k)                                                                        \
     int rb_##k = 0, re_##k = 0;                                                           \
@@ -491,10 +468,12 @@ simulate_channels_kernel(const SimChanParams p)
         SW_EACH_K(SC_TOTAL)
 #define SC_TIMES(q) if constexpr (q < KT) { if (q * 64 + lane < R) { t[q * 64 + lane] = rt_##q; arr[q * 64 + lane] = 0.0; } }
         SW_EACH_K(SC_TIMES)
+        if (R + lane < Rp) arr[R + lane] = 0.0;
         wave_sync();
 
         // ---- arrivals: per channel, prefix sums over the positions of the order ----
         double carry = 0.0;                 // lane c: time queued on channel c so far
+        int queued = 0;                     // lane c: recvs queued on channel c so far
         double sum_r = 0.0;
 #define SC_ARRIVE(q)                                                                      \
         if constexpr (q < KT) {                                                           \
@@ -504,13 +483,22 @@ simulate_channels_kernel(const SimChanParams p)
                 const int cl = ok ? chan_l[r] : -1;                                       \
                 const double x = ok ? t[r] : 0.0;                                         \
                 double a = 0.0;                                                           \
+                int nth = 0;                        /* this recv is the nth of its channel */ \
                 for (int c = 0; c < p.n_channels; ++c) {                                  \
                     const double inc = wave_incl_scan_f64_dpp(cl == c ? x : 0.0);         \
                     const double before = readlane_f64(carry, c);                         \
                     if (cl == c) a = before + inc;                                        \
                     if (lane == c) carry += lane63_f64(inc);                              \
+                    const uint64_t on_c = __ballot(cl == c);                              \
+                    const int n_before = __builtin_amdgcn_readlane(queued, c);            \
+                    if (cl == c) nth = n_before + __popcll(on_c & lanes_below);           \
+                    if (lane == c) queued += __popcll(on_c);                              \
                 }                                                                         \
-                if (ok) arr[r] = a;                                                       \
+                if (ok) {                                                                 \
+                    arr[r] = a;                                                           \
+                    /* (an order that is no permutation cannot write past the channel's share) */ \
+                    if (nth < clen[cl]) lists[coff[cl] + nth] = a;                        \
+                }                                                                         \
                 sum_r += x;                                                               \
             }                                                                             \
         }
@@ -520,18 +508,35 @@ simulate_channels_kernel(const SimChanParams p)
         wave_sync();
 
         // ---- rho of every class: maximum arrival over the runs of its row ----
+        // A run [lo, hi) is at most three recvs, whole blocks of four, and at most three recvs: the blocks are
+        // looked up in a table of maxima over 2^j blocks (two reads), the recvs at the ends are read one by one.
+        for (int i = lane; i < nb; i += 64) {
+            const double2 x = *reinterpret_cast<const double2 *>(arr + 4 * i), y = *reinterpret_cast<const double2 *>(arr + 4 * i + 2);
+            tab[i] = fmax(fmax(x.x, x.y), fmax(y.x, y.y));
+        }
+        wave_sync();
         for (int j = 1; j < p.levels; ++j) {
-            const double *prev = arr + (size_t)(j - 1) * R;
-            double *cur = arr + (size_t)j * R;
+            const double *prev = tab + (size_t)(j - 1) * nb;
+            double *cur = tab + (size_t)j * nb;
             const int h = 1 << (j - 1);
-            for (int i = lane; i < R; i += 64) cur[i] = fmax(prev[i], prev[min(i + h, R - 1)]);
+            for (int i = lane; i < nb; i += 64) cur[i] = fmax(prev[i], prev[min(i + h, nb - 1)]);
             wave_sync();
         }
 #define SC_RANGE_MAX(lo, hi)                                                              \
                 {                                                                         \
-                    const int j_ = 31 - __builtin_clz((hi) - (lo));                       \
-                    const double *lv_ = arr + (size_t)j_ * R;                             \
-                    m = fmax(m, fmax(lv_[lo], lv_[(hi) - (1 << j_)]));                    \
+                    const int lo_ = (lo), hi_ = (hi);                                     \
+                    const int b_lo = (lo_ + 3) >> 2, b_hi = hi_ >> 2;                     \
+                    const int e1 = min(4 * b_lo, hi_), s2 = max(4 * b_hi, e1);            \
+                    _Pragma("unroll")                                                     \
+                    for (int u = 0; u < 3; ++u) {                                         \
+                        if (lo_ + u < e1) m = fmax(m, arr[lo_ + u]);                      \
+                        if (s2 + u < hi_) m = fmax(m, arr[s2 + u]);                       \
+                    }                                                                     \
+                    if (b_lo < b_hi) {                                                    \
+                        const int j_ = 31 - __builtin_clz(b_hi - b_lo);                   \
+                        const double *lv_ = tab + (size_t)j_ * nb;                        \
+                        m = fmax(m, fmax(lv_[b_lo], lv_[b_hi - (1 << j_)]));              \
+                    }                                                                     \
                 }
 #define SC_RHO(k)                                                                         \
         if constexpr (k < KT) {                                                           \
@@ -546,10 +551,6 @@ simulate_channels_kernel(const SimChanParams p)
                 }                                                                         \
                 rho_##k = m;                                                              \
             }                                                                             \
-            if constexpr (KT < 5) {                                                       \
-                pairs[2 * (k * 64 + lane)] = rho_##k;                                     \
-                pairs[2 * (k * 64 + lane) + 1] = ct_##k;                                  \
-            }                                                                             \
         }
         SW_EACH_K(SC_RHO)
         wave_sync();
@@ -557,36 +558,48 @@ simulate_channels_kernel(const SimChanParams p)
         // ---- the compute device: makespan = max over classes of (release date + time of the classes released
         // then or later) ----
         double mloc = last_arrival, ct_sum = 0.0;
-        if constexpr (KT < 5) {
-            // few classes: every class against every class (pairs broadcast from LDS)
-#define SC_ACC_DECL(k) double w_##k = 0.0;
-            SW_EACH_K(SC_ACC_DECL)
-            for (int c = 0; c < C; ++c) {
-                const double2 pr = *reinterpret_cast<const double2 *>(pairs + 2 * c);   // the same for every lane
-#define SC_ACC(k) if constexpr (k < KT) { w_##k += pr.x >= rho_##k ? pr.y : 0.0; }
-                SW_EACH_K(SC_ACC)
+        {
+            // the rank of a release date is the number of arrivals up to it, one branch-free binary
+            // search per channel (release dates are arrivals, so a later release date has a higher rank and equal
+            // ones the same); the class times are added up by rank, a suffix sum over the ranks follows
+            double *A = arr;                // [R + 1] by rank (the arrivals and the table are not read any more)
+            for (int j = lane; j <= R; j += 64) A[j] = 0.0;
+#define SC_RANK_DECL(k) int rank_##k = 0, pos_##k = 0;
+            SW_EACH_K(SC_RANK_DECL)
+            for (int c = 0; c < p.n_channels; ++c) {
+                const int len = min(__builtin_amdgcn_readlane(queued, c), clen[c]);
+                if (len == 0) continue;
+                const double *lc = lists + coff[c];
+#define SC_RANK_ZERO(k) pos_##k = 0;
+                SW_EACH_K(SC_RANK_ZERO)
+                for (int step = 1 << (31 - __builtin_clz(len)); step > 0; step >>= 1) {
+#define SC_RANK_STEP(k)                                                                   \
+                    if constexpr (k < KT) {                                               \
+                        const int np = pos_##k + step;                                    \
+                        const double v = lc[min(np, len) - 1];                            \
+                        if (np <= len && v <= rho_##k) pos_##k = np;                      \
+                    }
+                    SW_EACH_K(SC_RANK_STEP)
+                }
+#define SC_RANK_ADD(k) rank_##k += pos_##k;
+                SW_EACH_K(SC_RANK_ADD)
             }
-#define SC_MAX(k) if constexpr (k < KT) { if (k * 64 + lane < C) mloc = fmax(mloc, rho_##k + w_##k); ct_sum += ct_##k; }
-            SW_EACH_K(SC_MAX)
-        } else {
-            // many classes: sorted by release date in registers, a suffix sum gives the second term (classes
-            // released at the same instant: the first of them in the sorted order carries the whole group)
-            constexpr int KP = 8;
-            double key[KP], val[KP];
-#pragma unroll
-            for (int k = 0; k < KP; ++k) { key[k] = -1.0; val[k] = 0.0; }     // (release dates are >= 0)
-#define SC_KEYS(k) if constexpr (k < KT) { if (k * 64 + lane < C) { key[k] = rho_##k; val[k] = ct_##k; } ct_sum += ct_##k; }
-            SW_EACH_K(SC_KEYS)
-            wave_sort_pairs<KP>(key, val, lane);
+            wave_sync();
+#define SC_RANK_SUM(k) if constexpr (k < KT) { if (k * 64 + lane < C) atomicAdd(&A[rank_##k], ct_##k); ct_sum += ct_##k; }
+            SW_EACH_K(SC_RANK_SUM)
+            wave_sync();
             double sfx = 0.0;
-#pragma unroll
-            for (int k = KP - 1; k >= 0; --k) {
-                const double inc = wave_incl_scan_f64_dpp(val[k]);
+            for (int base = (R / 64) * 64; base >= 0; base -= 64) {
+                const int j = base + lane;
+                const double x = j <= R ? A[j] : 0.0;
+                const double inc = wave_incl_scan_f64_dpp(x);
                 const double tot = lane63_f64(inc);
-                const double w = sfx + (tot - inc + val[k]);        // this element and everything after it
-                if (key[k] >= 0.0) mloc = fmax(mloc, key[k] + w);
+                if (j <= R) A[j] = sfx + (tot - inc + x);           // this rank and every later one
                 sfx += tot;
             }
+            wave_sync();
+#define SC_RANK_MAX(k) if constexpr (k < KT) { if (k * 64 + lane < C) mloc = fmax(mloc, rho_##k + A[rank_##k]); }
+            SW_EACH_K(SC_RANK_MAX)
         }
         const double m = wave_max_f64_dpp(mloc);
         const double sum_c = wave_sum_f64_dpp(ct_sum);
@@ -605,13 +618,20 @@ simulate_channels_kernel(const SimChanParams p)
 template <int KT>
 static hipError_t launch_sim_chan(SimChanParams &p, const Dag &d, hipStream_t s)
 {
+    const int nb = (d.R + 3) / 4;
     int levels = 1;
-    while ((1 << levels) <= d.R) ++levels;
+    while ((1 << levels) <= nb) ++levels;             // floor(log2 nb) + 1 levels of the table of block maxima
     p.levels = levels;
-    const size_t wave_bytes = (((size_t)d.R * (1 + levels) + 1 + (size_t)128 * KT) * 8 + 15) & ~(size_t)15;
+    p.nb = nb;
+    // the transfer times, later the table; at least one double beyond the padded arrivals for the sums by rank
+    const size_t x_doubles = (std::max((size_t)d.R, (size_t)levels * nb) + 2) & ~(size_t)1;
+    p.x_doubles = (int32_t)x_doubles;
+    // after those: the class totals, then the arrivals by channel
+    const size_t extra = std::max((size_t)64 * KT, ((size_t)d.R + 1) & ~(size_t)1);
+    const size_t wave_bytes = ((size_t)4 * nb + x_doubles + extra) * 8;       // a multiple of 16
     int waves = 4;
     while (waves > 1 && wave_bytes * waves > 40 * 1024) waves >>= 1;
-    const size_t chan_bytes = ((size_t)d.R * 4 + 15) & ~(size_t)15;
+    const size_t chan_bytes = (((size_t)d.R + 128) * 4 + 15) & ~(size_t)15;
     const size_t lds = chan_bytes + wave_bytes * waves;
     if (lds > 150 * 1024) return hipErrorNotSupported;     // 160 KB of LDS per compute unit
     p.wave_bytes = (int32_t)wave_bytes;
@@ -638,7 +658,7 @@ hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels
 {
     if (a.B == 0) return hipSuccess;
     const int K = std::max((d.C + 63) / 64, (d.R + 63) / 64);   // slots per lane: classes, and positions of the order
-    const int KT = K <= 4 ? (K < 1 ? 1 : K) : (K <= 6 ? 6 : 8);
+    const int KT = K < 1 ? 1 : K;
     if (d.R == 0 || d.R > 512 || K > 8 || n_channels > 64 || (d.C > 0 && (!d.d_col_cls || !d.d_run_ptr))) return hipErrorNotSupported;
     SimChanParams p{};
     p.B = a.B; p.R = d.R; p.C = d.C; p.N = d.N; p.n_channels = n_channels;
@@ -651,7 +671,9 @@ hipError_t launch_simulate_channels(Dag &d, const SimArgs &a, int32_t n_channels
     case 2: return launch_sim_chan<2>(p, d, s);
     case 3: return launch_sim_chan<3>(p, d, s);
     case 4: return launch_sim_chan<4>(p, d, s);
+    case 5: return launch_sim_chan<5>(p, d, s);
     case 6: return launch_sim_chan<6>(p, d, s);
+    case 7: return launch_sim_chan<7>(p, d, s);
     default: return launch_sim_chan<8>(p, d, s);
     }
 }
