@@ -456,6 +456,27 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         // words per workgroup slice, threads, and the chunks of levels of the node kernel
         // a workgroup's LDS traffic per level grows with its slice, so wide bitsets get many narrow slices
         d->k1_wc = d->W <= 1 ? 1 : (d->W <= 2 ? 2 : (d->W >= 16 ? 1 : 4));
+        // Graphs with narrow levels take a level per LDS round trip when one wave holds every row of its slice,
+        // every record and the input lists of the nodes that fit no record in LDS (propagate_nodes_wave); the
+        // slice is narrowed until that fits.
+        size_t list_entries = 0;
+        for (int32_t q = 0; q < M; ++q) {
+            const Dag::NodeRec &r = nodes[q];
+            int nn = 0, nr = 0;
+            for (int j = 0; j < 6; ++j) if (r.in[j] != INT32_MIN) (r.in[j] < 0 ? nr : nn) += 1;
+            if (r.ovf_beg >= 0)
+                for (int32_t e = 1; e <= ovf_idx[r.ovf_beg]; ++e) (ovf_idx[r.ovf_beg + e] < 0 ? nr : nn) += 1;
+            if (nn > 4 || nr > 2) list_entries += 1 + (size_t)nn + nr;
+        }
+        d->k1_wave = false;
+        for (int wc = d->k1_wc; wc >= 1 && max_width <= 64 && list_entries <= 4096 && M > 0; wc >>= 1) {
+            if (max_width * wc <= 64 &&
+                ((size_t)(M + 2) * wc + 1) * 8 + (size_t)M * 32 + (size_t)(n_node_levels + 1) * 4 + list_entries * 4 <= 150 * 1024) {
+                d->k1_wc = wc;
+                d->k1_wave = true;
+                break;
+            }
+        }
         int threads = max_width * d->k1_wc;
         threads = threads < 64 ? 64 : (threads > 1024 ? 1024 : (threads + 63) / 64 * 64);
         d->k1_threads = threads;
@@ -471,6 +492,7 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         // the LDS ring: a power of two of positions, at least two chunks (or all nodes), at most 64 KB beyond that
         int32_t ring = 64;
         while (ring < M && (ring < 2 * kK1Rpt * per_pass || (size_t)ring * 2 * d->k1_wc * 8 <= 64 * 1024)) ring *= 2;
+        if (d->k1_wave) ring = M;                   // every row stays: no ring, positions are used as they are
         d->k1_ring = ring;
         // level-major records (see internal.h): when a workgroup has more than one wave, the padding at
         // most quadruples the records, and sixteen levels of slots fit the ring: at most 64 KB, and 32 KB for
@@ -679,7 +701,7 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
                         int a = 0, b = 0;
                         for (int32_t x : tmp) {
                             if (x < 0) f.rcv[b++] = ~x;
-                            else f.in[a++] = (x & (ring - 1)) * row_bytes;
+                            else f.in[a++] = (d->k1_wave ? x : (x & (ring - 1))) * row_bytes;
                         }
                     } else {
                         f.ovf = (int32_t)fovf.size();

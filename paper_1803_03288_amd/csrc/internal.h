@@ -56,6 +56,7 @@ struct Dag {
         int32_t ovf;                // -1 for a fast node
     };
     int32_t k1_ring = 0;
+    bool k1_wave = false;       // narrow levels, everything in LDS: one wave per slice, k1_ring = M rows, no ring
     FastRec *d_frecs = nullptr;     // [M] (not built when a level is wider than one pass)
     int32_t *d_fovf = nullptr;
     int32_t fovf_len = 0;

@@ -362,12 +362,38 @@ _Pragma("unroll")                                                               
 #undef K1_REQUEST
 }
 
-// Narrow graphs (no level wider than 64 / WC nodes, all nodes and their records in LDS): one
-// wave per slice and no barrier at all.  The LDS operations of a wave are carried out in the
-// order in which they are issued, so a row written at one level can be read by another lane at
-// the next without a wait in between; the record of the next level's node is read from LDS a
-// level ahead, which leaves one LDS round trip per level: the reads of the input rows.  Rows go
-// to memory as they are computed and are never read back here.
+// Narrow graphs (no level wider than 64 / WC nodes, all rows of the slice and all records in LDS; the
+// host narrows the slice until they fit): one wave per slice and no barrier at all.  The LDS
+// operations of a wave are carried out in the order in which they are issued, so a row written at one
+// level can be read by another lane at the next without a wait in between; the record of the next
+// level's node is read from LDS a level ahead, which leaves one LDS round trip per level: the reads of
+// the input rows.  Rows go to memory as they are computed and are never read back here.
+// Table of n elements from memory to LDS by one wave, eight loads in flight per lane (a load per trip to memory
+// would make the copy as long as the propagation itself).
+// (keep_loaded: the value is in its registers at this point of the program, so the load that brings it is
+// issued before; without it the compiler moves every load down to the store that uses it, behind that store's test)
+__device__ __forceinline__ void keep_loaded(int32_t &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void keep_loaded(int4 &v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
+template <typename T>
+__device__ __forceinline__ void copy_to_lds(T *dst, const T *__restrict__ src, int n, int lane)
+{
+    for (int i0 = 0; i0 < n; i0 += 8 * 64) {
+        T v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * 64 + lane;
+            v[j] = src[min(i, n - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) keep_loaded(v[j]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = i0 + j * 64 + lane;
+            if (i < n) dst[i] = v[j];
+        }
+    }
+}
+
 template <int WC>
 __global__ void __launch_bounds__(64)
 propagate_nodes_wave(const PropParams p)
@@ -376,56 +402,69 @@ propagate_nodes_wave(const PropParams p)
     const int W = p.W, L = p.n_levels, M = p.M;
     const int w = threadIdx.x % WC, sub = threadIdx.x / WC;
     const int gw = slice_of_block() * WC + w;
-    int4 *recs = reinterpret_cast<int4 *>(ring + (size_t)(p.ring + 2) * WC);
+    int4 *recs = reinterpret_cast<int4 *>(ring + ((((size_t)p.ring + 2) * WC + 1) & ~(size_t)1));   // 16-byte aligned
     int32_t *lvl = reinterpret_cast<int32_t *>(recs + (size_t)2 * M);
     int32_t *fov = lvl + (L + 1);
     if (threadIdx.x < 2 * WC) ring[(size_t)p.ring * WC + threadIdx.x] = 0;
-    const int4 *src = reinterpret_cast<const int4 *>(p.frecs);
-    for (int i = threadIdx.x; i < 2 * M; i += 64) recs[i] = src[i];
-    for (int i = threadIdx.x; i <= L; i += 64) lvl[i] = p.nlvl_ptr[i];
-    for (int i = threadIdx.x; i < p.fovf_lds; i += 64) fov[i] = p.fovf[i];
+    copy_to_lds(recs, reinterpret_cast<const int4 *>(p.frecs), 2 * M, threadIdx.x);
+    copy_to_lds(lvl, p.nlvl_ptr, L + 1, threadIdx.x);
+    copy_to_lds(fov, p.fovf, p.fovf_lds, threadIdx.x);
     __syncthreads();
     if (L == 0) return;
 
+    // A level in straight-line code.  A lane without a node at the level works on the record of some other
+    // node (the index is clamped), reads rows that exist, and writes its result to the spare row after the zero
+    // row; nothing is branched on but the two rare kinds of node (recv inputs, inputs in a list).  Two register
+    // sets for the records, used in turn, so that nothing is moved between levels.
     int beg = lvl[0], end = lvl[1], end2 = lvl[min(2, L)];
-    int4 ra = make_int4(0, 0, 0, 0), rb = ra;
-    if (beg + sub < end) { ra = recs[(size_t)(beg + sub) * 2]; rb = recs[(size_t)(beg + sub) * 2 + 1]; }
-    for (int lv = 0; lv < L; ++lv) {
-        // the record of the next level's node and the bound after it, a level ahead
-        int4 na = make_int4(0, 0, 0, 0), nb = na;
-        if (lv + 1 < L && end + sub < end2) { na = recs[(size_t)(end + sub) * 2]; nb = recs[(size_t)(end + sub) * 2 + 1]; }
-        const int end3 = lvl[min(lv + 3, L)];
-        const int pos = beg + sub;
-        if (pos < end) {
-            const char *rbase = reinterpret_cast<const char *>(ring) + w * 8;
-            const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + ra.x);
-            const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + ra.y);
-            const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + ra.z);
-            const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + ra.w);
-            uint64_t bits = (rb.x >> 6) == gw ? 1ull << (rb.x & 63) : 0ull;
-            bits |= (rb.y >> 6) == gw ? 1ull << (rb.y & 63) : 0ull;
-            uint64_t val = bits | v0 | v1 | v2 | v3;
-            const int ovf_beg = rb.w;
-            if (ovf_beg >= 0) {                       // any other node: all inputs from its list (every node is in the ring)
-                const int ovf_cnt = fov[ovf_beg];
-                for (int e = 1; e <= ovf_cnt; ++e) {
-                    const int x = fov[ovf_beg + e];
-                    if (x < 0) {
-                        const int i = ~x;
-                        if ((i >> 6) == gw) val |= 1ull << (i & 63);
-                    } else {
-                        val |= ring[(size_t)x * WC + w];
-                    }
-                }
-            }
-            if (gw >= W) val = 0;
-            ring[(size_t)pos * WC + w] = val;
-            if (gw < W) p.dep[(size_t)rb.z * W + gw] = val;
-        }
-        wave_sync();
-        beg = end; end = end2; end2 = end3;
-        ra = na; rb = nb;
+    char *rbase = reinterpret_cast<char *>(ring) + w * 8;
+    const int spare = (p.ring + 1) * WC * 8;
+    int4 ra0, rb0, ra1, rb1;
+    {
+        const int q = min(beg + sub, M - 1);
+        ra0 = recs[(size_t)q * 2]; rb0 = recs[(size_t)q * 2 + 1];
     }
+#define K1W_LEVEL(ra, rb, na, nb, lvx)                                                              \
+    {                                                                                               \
+        const int pos = beg + sub;                                                                  \
+        const bool valid = pos < end;                                                               \
+        const uint64_t v0 = *reinterpret_cast<const uint64_t *>(rbase + ra.x);                      \
+        const uint64_t v1 = *reinterpret_cast<const uint64_t *>(rbase + ra.y);                      \
+        const uint64_t v2 = *reinterpret_cast<const uint64_t *>(rbase + ra.z);                      \
+        const uint64_t v3 = *reinterpret_cast<const uint64_t *>(rbase + ra.w);                      \
+        /* the record of the next level's node and the bound after it, a level ahead */             \
+        const int q = min(end + sub, M - 1);                                                        \
+        na = recs[(size_t)q * 2]; nb = recs[(size_t)q * 2 + 1];                                     \
+        const int end3 = lvl[min((lvx) + 3, L)];                                                      \
+        uint64_t val = (v0 | v1) | (v2 | v3);                                                       \
+        if (__ballot(valid && (rb.x & rb.w) != -1) != 0ull) {    /* a recv input or a list */        \
+            if (rb.x >= 0 && (rb.x >> 6) == gw) val |= 1ull << (rb.x & 63);                         \
+            if (rb.y >= 0 && (rb.y >> 6) == gw) val |= 1ull << (rb.y & 63);                         \
+            if (valid && rb.w >= 0) {               /* all inputs from the list (every row is in LDS) */ \
+                const int cnt = fov[rb.w];                                                          \
+                for (int e = 1; e <= cnt; ++e) {                                                    \
+                    const int x = fov[rb.w + e];                                                    \
+                    if (x < 0) {                                                                    \
+                        const int i = ~x;                                                           \
+                        if ((i >> 6) == gw) val |= 1ull << (i & 63);                                \
+                    } else {                                                                        \
+                        val |= ring[(size_t)x * WC + w];                                            \
+                    }                                                                               \
+                }                                                                                   \
+            }                                                                                       \
+        }                                                                                           \
+        if (gw >= W) val = 0;                                                                       \
+        *reinterpret_cast<uint64_t *>(rbase + (valid ? pos * (WC * 8) : spare)) = val;              \
+        if (valid && gw < W) p.dep[(size_t)rb.z * W + gw] = val;                                    \
+        wave_sync();                                                                                \
+        beg = end; end = end2; end2 = end3;                                                         \
+    }
+    for (int lv = 0; lv < L; lv += 2) {
+        K1W_LEVEL(ra0, rb0, ra1, rb1, lv)
+        if (lv + 1 >= L) break;
+        K1W_LEVEL(ra1, rb1, ra0, rb0, lv + 1)
+    }
+#undef K1W_LEVEL
 }
 
 // Level-major records (see internal.h): thread group j of the workgroup takes slot l * P + j at
@@ -869,18 +908,18 @@ static hipError_t launch_nodes(const Dag &d, hipStream_t s)
     }
     const int ring = d.k1_ring;
     p.ring = ring;
-    // one wave per slice when no level is wider than a wave and everything fits in LDS
-    if (!wide && threads == 64 && d.M <= ring && (d.fovf_len == 0 || p.fovf_lds > 0)) {
-        const size_t lds_w = (size_t)(ring + 2) * WC * 8 + (size_t)d.M * 32 + (size_t)(d.n_node_levels + 1) * 4 +
-                             (size_t)p.fovf_lds * 4;
-        if (lds_w <= 150 * 1024) {
-            if (lds_w > 48 * 1024) {
-                hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_nodes_wave<WC>), lds_w);
-                if (e != hipSuccess) return e;
-            }
-            hipLaunchKernelGGL(propagate_nodes_wave<WC>, dim3(blocks), dim3(64), lds_w, s, p);
-            return hipGetLastError();
+    // one wave per slice when no level is wider than a wave and everything fits in LDS (decided when the records were made)
+    if (d.k1_wave) {
+        const size_t lds_w = ((((size_t)ring + 2) * WC + 1) & ~(size_t)1) * 8 + (size_t)d.M * 32 +
+                             (size_t)(d.n_node_levels + 1) * 4 + (size_t)p.fovf_lds * 4;
+        if (wide || threads != 64 || ring != d.M || lds_w > 150 * 1024 || (d.fovf_len > 0 && p.fovf_lds == 0))
+            return hipErrorInvalidValue;
+        if (lds_w > 48 * 1024) {
+            hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(propagate_nodes_wave<WC>), lds_w);
+            if (e != hipSuccess) return e;
         }
+        hipLaunchKernelGGL(propagate_nodes_wave<WC>, dim3(blocks), dim3(64), lds_w, s, p);
+        return hipGetLastError();
     }
     size_t lds = (size_t)ring * WC * 8;
     if (wide) lds += (size_t)4 * per_pass * 16 + (size_t)(LVL_CHUNK + WC + 3) * 4;
