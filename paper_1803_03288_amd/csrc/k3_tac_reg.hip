@@ -198,6 +198,8 @@ tac_reg_kernel(const TacRegParams p)
         // members in Q, and the forced rounds are measurably slower with the two extra values)
         constexpr bool kFour = KT >= 4;
         int m_sync = -1;                    // M_k is current up to this step; -1: not formed yet
+        // lane 4 i + j: bit offsets of member i and of member j in the packed scalars of the scan over three or four
+        const int pair_shift = 10 * min((lane >> 2) & 3, 2) | (10 * max((lane & 3) - 1, 0)) << 8;
         int32_t *ord_next = ordl;           // where the next selected recv is recorded
 
         // outstanding recvs as 32-bit halves in LDS, rebuilt from the order so far on the rare
@@ -387,22 +389,26 @@ tac_reg_kernel(const TacRegParams p)
                 { const int lo = min(m1, m3), hi = max(m1, m3); m1 = lo; m3 = hi; }
                 { const int lo = min(m1, m2), hi = max(m1, m2); m1 = lo; m2 = hi; }
                 if (m0 != m1 && m1 != m2 && m2 != m3) {
-                    const int m3r = four ? m3 : m2;         // with three, the fourth is a copy of the third
-                    const double P0 = P[m0], P1 = P[m1], P2 = P[m2], P3 = P[m3r];
-                    const double t0 = t[m0], t1 = t[m1], t2 = t[m2], t3 = t[m3r];
-                    const double x1 = fmin(P0, t1), y1 = fmin(P1, t0);          // m1 precedes m0 when x1 < y1
-                    const bool s1 = x1 < y1;
-                    const double Pa = s1 ? P1 : P0, ta = s1 ? t1 : t0;
-                    const double x2 = fmin(Pa, t2), y2 = fmin(P2, ta);
-                    const bool s2 = x2 < y2;
-                    const double Pb = s2 ? P2 : Pa, tb = s2 ? t2 : ta;
-                    const double x3 = fmin(Pb, t3), y3 = fmin(P3, tb);
-                    const bool s3 = four && x3 < y3;
-                    const bool no_tie = x1 != y1 && x2 != y2 && (!four || x3 != y3);
-                    if (__builtin_amdgcn_readfirstlane((int)no_tie)) {
-                        const int b1 = __builtin_amdgcn_readfirstlane((int)s1) ? m1 : m0;
-                        const int b2 = __builtin_amdgcn_readfirstlane((int)s2) ? m2 : b1;
-                        const int best = __builtin_amdgcn_readfirstlane((int)s3) ? m3 : b2;
+                    // Lane 4 i + j (i < j) evaluates the comparator for the members i and j: j precedes i when
+                    // min{P_i, Time(j)} < min{P_j, Time(i)}.  Its members come out of two scalars that hold three
+                    // members of ten bits each (0, 1, 2 for i; 1, 2, 3 for j; with three members the fourth is a copy
+                    // of the third).  The scan then walks over the outcomes in scalar code.
+                    const int m3r = four ? m3 : m2;
+                    const int pack_i = m0 | m1 << 10 | m2 << 20, pack_j = m1 | m2 << 10 | m3r << 20;
+                    const int mi = __builtin_amdgcn_ubfe(pack_i, pair_shift & 31, 10);
+                    const int mj = __builtin_amdgcn_ubfe(pack_j, pair_shift >> 8, 10);
+                    const double xi = fmin(P[mi], t[mj]), yi = fmin(P[mj], t[mi]);
+                    const uint64_t lt = __ballot(xi < yi), eq = __ballot(xi == yi);
+                    int bi = (int)(lt >> 1) & 1;                                 // members 0 and 1: lane 1
+                    uint64_t looked = 1ull << 1;
+                    looked |= 1ull << (4 * bi + 2);
+                    if ((lt >> (4 * bi + 2)) & 1) bi = 2;
+                    if (four) {
+                        looked |= 1ull << (4 * bi + 3);
+                        if ((lt >> (4 * bi + 3)) & 1) bi = 3;
+                    }
+                    if ((eq & looked) == 0ull) {                                // no tie in a comparison that was made
+                        const int best = bi == 0 ? m0 : (bi == 1 ? m1 : (bi == 2 ? m2 : m3));
                         // the members that stay, in ascending order
                         qm -= 1;
                         q0 = best == m0 ? m1 : m0;
