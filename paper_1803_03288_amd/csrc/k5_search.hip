@@ -351,7 +351,9 @@ hipError_t launch_order_search(Dag &d, const SearchArgs &a, hipStream_t s)
     if (K <= 2) return launch_search_t<2>(p, d, s);
     if (K <= 3) return launch_search_t<3>(p, d, s);
     if (K <= 4) return launch_search_t<4>(p, d, s);
+    if (K <= 5) return launch_search_t<5>(p, d, s);
     if (K <= 6) return launch_search_t<6>(p, d, s);
+    if (K <= 7) return launch_search_t<7>(p, d, s);
     return launch_search_t<8>(p, d, s);
 }
 
