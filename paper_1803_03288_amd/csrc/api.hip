@@ -369,7 +369,8 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
     // rep[v] = the node whose dep op v has (itself if v is a node); recvs are not nodes, they
     // enter a node as single bits.
     std::vector<int32_t> rep(n, -1), node_level(n, 0);
-    std::vector<std::vector<int32_t>> node_in(0);
+    std::vector<int32_t> node_in, node_in_ptr(1, 0);     // inputs of node k: node_in[node_in_ptr[k] .. node_in_ptr[k + 1])
+    node_in.reserve(E);
     std::vector<int32_t> node_ops;                       // in topological order
     std::vector<int32_t> node_index(n, -1);              // op -> index into node_ops
     std::vector<int32_t> tmp;
@@ -382,14 +383,14 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         rep[v] = v;
         node_index[v] = (int32_t)node_ops.size();
         node_ops.push_back(v);
-        std::vector<int32_t> in;                         // ~i for recv i, else index of the input node
+        const size_t first = node_in.size();             // ~i for recv i, else index of the input node
         for (int32_t u : tmp) {
-            if (recv_of_op[u] >= 0) in.push_back(~recv_of_op[u]);
-            else in.push_back(node_index[rep[u]]);
+            if (recv_of_op[u] >= 0) node_in.push_back(~recv_of_op[u]);
+            else node_in.push_back(node_index[rep[u]]);
         }
-        std::sort(in.begin(), in.end());
-        in.erase(std::unique(in.begin(), in.end()), in.end());
-        node_in.push_back(std::move(in));
+        std::sort(node_in.begin() + first, node_in.end());
+        node_in.erase(std::unique(node_in.begin() + first, node_in.end()), node_in.end());
+        node_in_ptr.push_back((int32_t)node_in.size());
     }
     const int32_t M = (int32_t)node_ops.size();
     // Nodes are grouped by the level of their op in the full graph (an input of a node lies on a
@@ -418,7 +419,8 @@ static int build(int32_t n, const int32_t *row_ptr, const int32_t *col_idx, int3
         r.ovf_beg = -1;
         for (int j = 0; j < 6; ++j) r.in[j] = INT32_MIN;
         int j = 0;
-        for (int32_t x : node_in[k]) {
+        for (int32_t e = node_in_ptr[k]; e < node_in_ptr[k + 1]; ++e) {
+            const int32_t x = node_in[e];
             const int32_t y = x < 0 ? x : pos_of_index[x];
             if (j < 6) {
                 r.in[j] = y;
