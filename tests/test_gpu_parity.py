@@ -795,6 +795,47 @@ def test_stress_both_kernels_sampled_rounds(tt):
 # enough for the oracle to run every round
 # --------------------------------------------------------------------------
 
+# layered graphs whose numbers of classes need four, five, six and eight class slots per lane in the
+# one-wave-per-sample kernels (seven: inception3; one to three: the small graphs above)
+CLASS_SLOTS = {
+    # (enough recvs for the simulation kernel with one wave per sample: 32 per class slot)
+    4: lambda: wl.layered_dag(32, levels=10, width=24, fan_in=(1, 3), back=3, n_recv=130, attach=(1, 3), name="slots4"),
+    5: lambda: wl.layered_dag(33, levels=11, width=28, fan_in=(1, 3), back=3, n_recv=165, attach=(1, 3), name="slots5"),
+    6: lambda: wl.layered_dag(35, levels=13, width=33, fan_in=(1, 3), back=3, n_recv=200, attach=(1, 3), name="slots6"),
+    8: lambda: wl.layered_dag(39, levels=15, width=40, fan_in=(1, 3), back=3, n_recv=260, attach=(1, 3), name="slots8"),
+}
+
+
+@pytest.mark.parametrize("slots", list(CLASS_SLOTS))
+def test_every_number_of_class_slots(tt, slots):
+    """The one-wave-per-sample kernels are instantiated per number of class slots per lane: TAC with the fused
+    simulation, the simulation under given orders, several channels and the order search on graphs that need
+    four, five, six and eight of them, each against the oracle."""
+    name = f"slots{slots}"
+    d, h, dep = get(tt, name, CLASS_SLOTS[slots])
+    print(f"[slots] {name}: N={d.n_compute} R={d.n_recv} classes={h.n_classes}", flush=True)
+    assert (h.n_classes + 63) // 64 == slots
+    R, B = d.n_recv, 12
+    assert R >= 32 * slots
+    op, rv = wl.timing_samples(d, 0, B)
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name)
+    rng = np.random.default_rng(61)
+    orders = np.stack([rng.permutation(R) for _ in range(B)]).astype(np.int32)
+    gop, grv, gord = cuda(op), cuda(rv), cuda(orders)
+    args = (d.n_ops, d.row_ptr, d.col_idx, d.recv_ids)
+    for C, chan in ((3, np.arange(R) % 3), (4, rng.integers(0, 4, size=R))):
+        chan = chan.astype(np.int32)
+        exp = oracle.simulate_channels(*args, C, chan, orders, op, rv)
+        got = tt.simulate_channels(h, C, chan, gord, gop, grv)
+        for a, b, nm in zip(got, exp, "m E U L S".split()):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: {C} channels, {nm}"
+    moves = rng.integers(0, R, size=(60, 2)).astype(np.int32)
+    exp = oracle.order_search(*args, orders, moves, op, rv)
+    got = tt.order_search(h, gord, cuda(moves), gop, grv)
+    for a, b, nm in zip(got, exp, ("best_order", "best_makespan", "start_makespan", "n_accepted")):
+        assert np.array_equal(a.cpu().numpy(), b), f"{name}: {nm}"
+
+
 MANY_CLASSES = {
     # per-sample state beyond what one workgroup's LDS holds (about 9 600 classes, 160 recvs)
     "mid_stress": lambda: wl.stress_dag(levels=50, width=400, n_recv=160, seed=31, batch=8),
