@@ -72,8 +72,11 @@ SMALL = {
     "wide_levels": lambda: wl.layered_dag(21, levels=4, width=1500, fan_in=(2, 3), back=1, n_recv=1100, attach=(1, 3)),
     # deep and narrow with edges that span thousands of positions: inputs that have left the LDS ring
     "long_edges": lambda: wl.deep_narrow_dag(22, levels=2500, width=4, n_recv=60),
-    # the same with wider rows (W = 3 words, four-word slices)
+    # the same with wider rows (W = 3 words, four-word slices; W = 2 words, two-word slices)
     "long_edges_w3": lambda: wl.deep_narrow_dag(23, levels=1300, width=4, n_recv=150),
+    "long_edges_w2": lambda: wl.deep_narrow_dag(27, levels=1500, width=4, n_recv=100),
+    # two-word rows with a level wider than one pass of the propagation workgroup
+    "wide_levels_w2": lambda: wl.layered_dag(28, levels=4, width=700, fan_in=(2, 3), back=1, n_recv=100, attach=(1, 3)),
     # levels of a hundred ops (several waves per workgroup: the level-major kernel) with edges that reach
     # back past the rows kept in LDS, for one-, two- and four-word slices
     "deep_w1": lambda: wl.deep_narrow_dag(24, levels=700, width=100, n_recv=60),
@@ -104,7 +107,7 @@ def test_deps_and_tic_bit_exact(tt, name):
     assert h.n_classes == np.unique(rows, axis=0).shape[0]
 
 
-@pytest.mark.parametrize("name", ["stress", "deep_w1", "deep_w2", "resnet50", "tiny"])
+@pytest.mark.parametrize("name", ["stress", "deep_w1", "deep_w2", "deep_w3", "resnet50", "tiny"])
 def test_deps_of_several_handles_in_one_launch(tt, name):
     """tictac_dag_recompute_deps_batch: the bitsets of several handles, cleared first, are propagated again by
     one call (one launch where the graphs take the level-major kernel, one after the other elsewhere) and
