@@ -304,7 +304,7 @@ tac_reg_kernel(const TacRegParams p)
         // that class's time goes to P of that recv.
 #define TT_UPDATE(k)                                                                      \
             if constexpr (k < KT) {                                                       \
-                mk_##k = __builtin_amdgcn_sbfe(rb[k], best, 1);   /* 0 or -1; the bit offset is best mod 32 */ \
+                mk_##k = __builtin_amdgcn_sbfe(row_##k, best, 1); /* 0 or -1; the bit offset is best mod 32 */ \
                 __builtin_assume(mk_##k >= -1 && mk_##k <= 0);                            \
                 pk_##k += mk_##k * delta;           /* both fit 24 bits: one multiply-add */ \
                 hmax = max(hmax, (uint32_t)(pk_##k & mk_##k));   /* count fell to 1: top 12 bits all set */ \
@@ -315,12 +315,18 @@ tac_reg_kernel(const TacRegParams p)
                 const uint64_t hm_ = __builtin_amdgcn_ballot_w64(hit1);                   \
                 if (hm_ != 0ull) TT_TO_P(k, hit1, hm_)                                    \
             }
+        // (with many class slots all words of the row are requested before the first is used: one LDS round trip
+        // instead of one per read, which is what the compiler schedules by itself)
+#define TT_ROW_LOAD(k) uint32_t row_##k = 0; if constexpr (k < KT) { row_##k = rb[k]; }
+#define TT_ROW_KEEP(k) if constexpr (k < KT && KT >= 4) { asm volatile("" : "+v"(row_##k)); }
 #define TT_APPLY()                                                                        \
             {                                                                             \
                 *ord_next++ = best;                     /* every lane writes the same value */ \
                 const uint32_t *rb = rows_lane + (best >> 5) * (64 * KS);                 \
                 const int delta = CNT1 + (best & IDX_MASK);    /* the mask tells the compiler it fits 24 bits */ \
                 uint32_t hmax = 0;                                                        \
+                TT_EACH_K(TT_ROW_LOAD)                                                    \
+                TT_EACH_K(TT_ROW_KEEP)                                                    \
                 TT_EACH_K(TT_UPDATE)                                                      \
                 if (__ballot(hmax >= (uint32_t)-CNT1) != 0ull) { TT_EACH_K(TT_EVENT) }    \
                 ++step;                                                                   \
@@ -368,8 +374,8 @@ tac_reg_kernel(const TacRegParams p)
                 const int a_ = min(q0, q1), b_ = max(q0, q1);
                 const double xa = fmin(P[a_], t[b_]);
                 const double ya = fmin(P[b_], t[a_]);
-                if (__builtin_amdgcn_readfirstlane((int)(xa != ya))) {
-                    const int best = __builtin_amdgcn_readfirstlane((int)(xa < ya)) ? b_ : a_;
+                if (__ballot(xa != ya) != 0ull) {               // (the same in every lane)
+                    const int best = __ballot(xa < ya) != 0ull ? b_ : a_;
                     qm = 1; q0 = a_ + b_ - best;
                     TT_APPLY()
                     TT_UNIFORM_Q()
