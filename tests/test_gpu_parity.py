@@ -839,6 +839,25 @@ def test_every_number_of_class_slots(tt, slots):
         assert np.array_equal(a.cpu().numpy(), b), f"{name}: {nm}"
 
 
+@pytest.mark.parametrize("slots", [4, 6, 8])
+def test_ties_and_zero_times_with_many_class_slots(tt, slots):
+    """The paths that graphs with four or more class slots per lane take for three or four members of Q:
+    times from a handful of values (exact ties in the comparator, several pointers at one recv), zero
+    compute times (classes that never point) and zero transfer times (the literal path), against the oracle."""
+    name = f"slots{slots}"
+    d, h, dep = get(tt, name, CLASS_SLOTS[slots])
+    rng = np.random.default_rng(70 + slots)
+    B = 40
+    op = rng.integers(0, 4, size=(B, d.n_compute)).astype(np.float64) * 0.25
+    rv = rng.integers(1, 4, size=(B, d.n_recv)).astype(np.float64) * 0.25
+    run_tac_sim_parity(tt, d, h, dep, op, rv, name + "/ties")
+    op1 = rng.integers(1, 9, size=(B, d.n_compute)).astype(np.float64) * 0.125     # no zero class times: many pointers
+    run_tac_sim_parity(tt, d, h, dep, op1, rv, name + "/ties, positive times")
+    rv0 = rv.copy()
+    rv0[rng.random(rv0.shape) < 0.1] = 0.0
+    run_tac_sim_parity(tt, d, h, dep, op[:8], rv0[:8], name + "/zero-transfers")
+
+
 MANY_CLASSES = {
     # per-sample state beyond what one workgroup's LDS holds (about 9 600 classes, 160 recvs)
     "mid_stress": lambda: wl.stress_dag(levels=50, width=400, n_recv=160, seed=31, batch=8),
