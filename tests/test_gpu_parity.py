@@ -578,7 +578,7 @@ def test_float32_timing_arrays(tt, name, k):
             assert np.array_equal(a.cpu().numpy(), b), f"{name}: simulate {nm}"
 
 
-@pytest.mark.parametrize("name", ["tiny", "layered70", "resnet50", "r129"])
+@pytest.mark.parametrize("name", ["tiny", "layered70", "resnet50", "r129", "slots5", "inception3"])
 def test_times_that_are_not_quantised(tt, name):
     """Lognormal times as they come (sums round differently in different orders): float64 outputs
     within 1e-5 relative of the oracle's.  The simulation, the several-channel simulation and the
@@ -589,8 +589,9 @@ def test_times_that_are_not_quantised(tt, name):
     makespan must be the one the oracle computes for it.  Two runs on the same inputs are equal byte for byte."""
     makers = dict(SMALL)
     makers.update(EXTRA)
+    makers["slots5"] = CLASS_SLOTS[5]
     d, h, dep = get(tt, name, makers.get(name))
-    R, B = d.n_recv, 48
+    R, B = d.n_recv, (8 if name == "inception3" else 48)
     rng = np.random.default_rng(77)
     op = rng.lognormal(np.log(1e-3), 0.5, size=(B, d.n_compute))
     rv = rng.lognormal(np.log(2e-3), 0.7, size=(B, R))
