@@ -75,6 +75,8 @@ SMALL = {
     # the same with wider rows (W = 3 words, four-word slices; W = 2 words, two-word slices)
     "long_edges_w3": lambda: wl.deep_narrow_dag(23, levels=1300, width=4, n_recv=150),
     "long_edges_w2": lambda: wl.deep_narrow_dag(27, levels=1500, width=4, n_recv=100),
+    # narrow levels and many words per row (one wave per one-word slice, eighteen slices)
+    "narrow_w18": lambda: wl.deep_narrow_dag(29, levels=300, width=4, n_recv=1100),
     # two-word rows with a level wider than one pass of the propagation workgroup
     "wide_levels_w2": lambda: wl.layered_dag(28, levels=4, width=700, fan_in=(2, 3), back=1, n_recv=100, attach=(1, 3)),
     # levels of a hundred ops (several waves per workgroup: the level-major kernel) with edges that reach
