@@ -1301,14 +1301,18 @@ static int ensure_send_tables(Dag *d, int32_t n_send, const int32_t *send_ids, h
         }
         is_send[v] = 1;
     }
-    std::vector<int4> rec(n);
-    std::vector<int32_t> succ(E > 0 ? E : 1), fill(n), send_free;
+    // rec[v]: where the successors of v start in succ (-1: none), the column of its time (-1: a recv), 1 for a send.
+    // succ[e]: a successor (the top bit marks the last one of its list), and what running that successor needs, so
+    // that an op released by the op before it is run without a read of rec: its column, where its own successors
+    // start, 1 for a send.  64 entries of padding: a wave reads 64 entries at a time.
+    std::vector<int4> rec(n), succ((size_t)E + 64, make_int4(0, 0, 0, 0));
+    std::vector<int32_t> fill(n), send_free;
     std::vector<uint16_t> indeg(n);
     std::vector<uint32_t> ready0(((size_t)n + 31) / 32, 0u);
     std::vector<uint8_t> col_kind(d->N > 0 ? d->N : 1, 0);
     int32_t at = 0;
     for (int32_t v = 0; v < n; ++v) {
-        rec[v] = make_int4(at, n_succ[v], col_of_op[v], is_send[v]);
+        rec[v] = make_int4(n_succ[v] > 0 ? at : -1, 0, col_of_op[v], is_send[v]);
         fill[v] = at;
         at += n_succ[v];
         const int32_t deg = d->h_row_ptr[v + 1] - d->h_row_ptr[v];
@@ -1321,7 +1325,11 @@ static int ensure_send_tables(Dag *d, int32_t n_send, const int32_t *send_ids, h
         if (is_send[v]) col_kind[col_of_op[v]] = 1;
     }
     for (int32_t v = 0; v < n; ++v)
-        for (int32_t e = d->h_row_ptr[v]; e < d->h_row_ptr[v + 1]; ++e) succ[fill[d->h_col_idx[e]]++] = v;
+        for (int32_t e = d->h_row_ptr[v]; e < d->h_row_ptr[v + 1]; ++e) {
+            const int32_t u = d->h_col_idx[e], at_u = fill[u]++;
+            const bool last = at_u + 1 == rec[u].x + n_succ[u];
+            succ[at_u] = make_int4(last ? (int32_t)((uint32_t)v | 0x80000000u) : v, rec[v].z, rec[v].x, rec[v].w);
+        }
 
     Packer tables;
     tables.add(&d->d_send_rec, rec);

@@ -141,8 +141,8 @@ struct Dag {
     std::vector<int32_t> h_row_ptr, h_col_idx, h_recv_ids, h_send_ids;
     bool send_tables_built = false;
     void *d_send_block = nullptr;
-    int4 *d_send_rec = nullptr;
-    int32_t *d_send_succ = nullptr, *d_send_free = nullptr, *d_send_recv_ids = nullptr;
+    int4 *d_send_rec = nullptr, *d_send_succ = nullptr;
+    int32_t *d_send_free = nullptr, *d_send_recv_ids = nullptr;
     uint16_t *d_send_indeg = nullptr;
     uint32_t *d_send_ready0 = nullptr;
     uint8_t *d_send_col_kind = nullptr;

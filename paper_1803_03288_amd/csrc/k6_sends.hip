@@ -16,7 +16,9 @@
 //   * the uplink needs no queue: requests arrive in non-decreasing time (the steps above are taken in
 //     time order), and for the requests of one instant only the sum of their times matters, so
 //     busy = max(busy, instant) + sum; the last send ends at the final value of busy.
-// Per step two dependent reads of tables in device memory (record, then successors and the op's time); the
+// A step reads from device memory the op's time and its successor list.  Both addresses come with the list entry
+// through which the op was released (the lane that released it keeps them), so an op released by the op before it,
+// the common case on chains, costs one trip to memory; any other op costs a second one for its record.  The
 // per-sample state in LDS is 2 bytes per op plus a bit per op plus 12 bytes per recv.
 #include <algorithm>
 
@@ -27,8 +29,9 @@ namespace tictac {
 
 struct SendSimParams {
     int32_t B, n, R, N;
-    const int4 *rec;                // [n] per op: successors at succ[x .. x + y), column of its time (z; -1 recv), w: 1 = send
-    const int32_t *succ;            // [E] successor op ids
+    const int4 *rec;                // [n] per op: successors from succ[x] on (-1: none), column of its time (z; -1 recv), w: 1 = send
+    const int4 *succ;               // [E + 64] x: successor op id, top bit set on the last of a list; y, z, w: that op's
+                                    // column, start of its successors and send flag (as in rec)
     const uint16_t *indeg;          // [n] number of predecessors
     const uint32_t *ready0;         // [ceil(n / 32)] compute ops (not sends) without predecessors
     const int32_t *send0;           // [n_send0] columns of the sends without predecessors (requested at 0)
@@ -57,7 +60,7 @@ simulate_sends_kernel(const SendSimParams p)
     const int n_words = (n + 31) >> 5;
     char *mine = reinterpret_cast<char *>(smem) + (size_t)wave * p.wave_bytes;
     double *F = reinterpret_cast<double *>(mine);                               // [R] end of the k-th transfer
-    int32_t *rop = reinterpret_cast<int32_t *>(F + R);                          // [R] op id of the k-th recv
+    int32_t *rop = reinterpret_cast<int32_t *>(F + R);                          // [R] where the successors of the k-th recv start
     uint32_t *rdy = reinterpret_cast<uint32_t *>(rop + R);                      // [n_words]
     uint16_t *waiting = reinterpret_cast<uint16_t *>(rdy + n_words);            // [n] (padded to a multiple of two)
 
@@ -77,7 +80,7 @@ simulate_sends_kernel(const SendSimParams p)
             if (!ok) r = 0;
             const double x = ok ? rt[r] : 0.0;
             const double inc = wave_incl_scan_f64_dpp(x);
-            if (k < R) { F[k] = fc + inc; rop[k] = ok ? p.recv_ids[r] : -1; }
+            if (k < R) { F[k] = fc + inc; rop[k] = ok ? p.rec[p.recv_ids[r]].x : -1; }
             fc += lane63_f64(inc);
         }
         const double sum_r = fc;
@@ -100,27 +103,32 @@ simulate_sends_kernel(const SendSimParams p)
         }
         wave_sync();
 
-        // the successors of op u are released at time `at`
-        auto release = [&](int u, double at) {
-            if (u < 0) return;
-            const int4 ru = p.rec[u];
-            const int beg = __builtin_amdgcn_readfirstlane(ru.x), cnt = __builtin_amdgcn_readfirstlane(ru.y);
+        // What the lane knows of the op it released last: id, column of its time, start of its successors.
+        int held_op = -1, held_col = 0, held_beg = 0;
+        // the successors listed from succ[beg] on are released at time `at`
+        auto release = [&](int beg, double at) {
+            if (beg < 0) return;
             double sent = 0.0;
             bool any_send = false;
-            for (int e0 = 0; e0 < cnt; e0 += 64) {
-                const int e = e0 + lane;
-                if (e < cnt) {
-                    const int s2 = p.succ[beg + e];
+            for (int base = beg;; base += 64) {
+                const int4 se = p.succ[base + lane];
+                const uint64_t ends = __ballot(se.x < 0);
+                const int n_here = ends ? __builtin_ctzll(ends) + 1 : 64;   // entries of this list among the 64 read
+                if (lane < n_here) {
+                    const int s2 = se.x & 0x7fffffff;
                     // (16-bit counters: the atomic works on the 32-bit word that holds the counter)
                     uint32_t *word = reinterpret_cast<uint32_t *>(waiting) + (s2 >> 1);
                     const int sh = (s2 & 1) * 16;
                     const uint32_t old = atomicSub(word, 1u << sh);
                     if (((old >> sh) & 0xffffu) == 1u) {
-                        const int4 rs = p.rec[s2];
-                        if (rs.w) { sent += ot[rs.z]; any_send = true; }
-                        else atomicOr(&rdy[s2 >> 5], 1u << (s2 & 31));
+                        if (se.w) { sent += ot[se.y]; any_send = true; }
+                        else {
+                            atomicOr(&rdy[s2 >> 5], 1u << (s2 & 31));
+                            held_op = s2; held_col = se.y; held_beg = se.z;
+                        }
                     }
                 }
+                if (ends) break;
             }
             if (__ballot(any_send) != 0ull) {
                 up_busy = fmax(up_busy, at) + wave_sum_f64_dpp(sent);
@@ -153,8 +161,18 @@ simulate_sends_kernel(const SendSimParams p)
                 ++k;
                 continue;
             }
-            const int4 rv = p.rec[v];
-            const double finish = t_dev + uniform(ot[__builtin_amdgcn_readfirstlane(rv.z)]);
+            int v_col, v_beg;
+            const uint64_t holders = __ballot(held_op == v);
+            if (holders) {
+                const int l = __builtin_ctzll(holders);
+                v_col = __builtin_amdgcn_readlane(held_col, l);
+                v_beg = __builtin_amdgcn_readlane(held_beg, l);
+            } else {
+                const int4 rv = p.rec[v];
+                v_col = __builtin_amdgcn_readfirstlane(rv.z);
+                v_beg = __builtin_amdgcn_readfirstlane(rv.x);
+            }
+            const double finish = t_dev + uniform(ot[v_col]);
             if (lane == 0) rdy[v >> 5] &= ~(1u << (v & 31));
             // transfers that end while the op runs release their successors first (requests to the uplink
             // are served in the order of their instants)
@@ -162,7 +180,7 @@ simulate_sends_kernel(const SendSimParams p)
                 release(__builtin_amdgcn_readfirstlane(rop[k]), uniform(F[k]));
                 ++k;
             }
-            release(v, finish);
+            release(v_beg, finish);
             t_dev = finish;
             m = fmax(m, finish);
         }
